@@ -1,0 +1,25 @@
+"""CPU oracle for the aggregation hot path (TEST INFRASTRUCTURE).
+
+A plain, slow, fp64 implementation of what the HIP library computes, written
+from the paper's definitions: graph normalisation, forward and transposed
+neighbour aggregation, chunked aggregation, the dense transform and a GCN
+epoch.  Only tests, the smoke check and the benchmark's cpu_baseline leg may
+import it; the product never does, and it imports nothing from the product.
+
+Pins (tests/test_oracle_pins.py): dense brute force on tiny graphs, the
+constant-vector closed form, the sqrt-degree fixed point, textbook graphs
+(empty, complete, star, ring), the adjoint identity on directed graphs,
+chunk/slice invariance, finite-difference gradients of the epoch loss, and a
+hand-derived fixture under tests/golden/.  No function here is unpinned.
+"""
+from .graph import (  # noqa: F401
+    Graph, Sparse, build_graph, plan_chunks,
+    SYMMETRISE, DEDUP, ADD_SELF_LOOPS, NORM_GCN_SYM, GCN_FLAGS, DIRECTED_GCN_FLAGS,
+)
+from .aggregate import (  # noqa: F401
+    aggregate, aggregate_fwd, aggregate_bwd, aggregate_bwd_scatter,
+    chunked_aggregate, round_bf16, num_threads, build_native,
+)
+from .gcn import (  # noqa: F401
+    nn_fwd, nn_bwd, softmax_cross_entropy, epoch_layerwise, epoch_decoupled,
+)
