@@ -1,0 +1,182 @@
+/*
+ * ntp.h - C boundary of the per-worker aggregation hot path of feature-dimension
+ * tensor-parallel full-graph GNN training, for one AMD MI355X (gfx950).
+ *
+ * One worker of the method holds the whole graph and a column slice [N x F_slice] of
+ * the vertex features (Section 3.1 of the paper); it aggregates that slice over the
+ * normalised adjacency in the forward pass (eq. 1, eq. 3) and over its transpose in the
+ * backward pass (Section 4.2.1), optionally chunk by chunk when the topology does not
+ * fit the device (Section 4.2.1, Alg. 1), and applies the dense transform of eq. (4).
+ *
+ * Conventions
+ *  - Every call returns an int status: NTP_OK (0) or a negative NTP_E* code.  The text of
+ *    the last error on the calling thread is ntp_last_error().
+ *  - "host" pointers are ordinary process memory; "device" pointers are HIP device memory
+ *    of the current device.  The library never frees or keeps caller buffers: pointers
+ *    are used only by the work enqueued during the call.
+ *  - Feature / gradient matrices are row-major; ld* are row strides in ELEMENTS (>= the
+ *    slice width).  Input and output of one call must not overlap.
+ *  - stream arguments are hipStream_t passed as void* (NULL = the null stream).  The
+ *    aggregate and nn calls only enqueue work; they do not synchronise with the host,
+ *    except that the first call needing a larger scratch buffer allocates it.
+ *  - A graph handle may be used by one thread at a time; calls on one handle that overlap
+ *    in time on different streams race on its scratch memory.
+ */
+#ifndef NTP_H
+#define NTP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define NTP_OK            0
+#define NTP_EINVAL       -1   /* bad argument (null pointer, bad size, id out of range, overlap) */
+#define NTP_ENOMEM       -2   /* host or device allocation failed */
+#define NTP_EHIP         -3   /* a HIP runtime call failed */
+#define NTP_EBUDGET      -4   /* topology not fully device-resident (use the chunked call), or
+                                 the device budget cannot hold even the staging buffers */
+#define NTP_EUNSUPPORTED -5   /* combination not implemented */
+
+/* ntp_graph_build flags */
+#define NTP_SYMMETRISE      1u   /* also add the reverse of every input edge */
+#define NTP_DEDUP           2u   /* drop input self loops, keep the first of equal (src,dst) */
+#define NTP_ADD_SELF_LOOPS  4u   /* append one (v,v) entry of weight 1 per vertex (A + I) */
+#define NTP_NORM_GCN_SYM    8u   /* scale entry (u->v) by 1/sqrt(deg_in(v) * deg_out(u)) */
+#define NTP_HOST_ONLY      16u   /* build and plan on the host only; no device memory is
+                                    touched; aggregate calls then fail with NTP_EBUDGET */
+#define NTP_FORCE_STREAM   32u   /* keep no chunk resident: every chunk is copied from pinned
+                                    host memory on every chunked call (cold streaming) */
+
+/* which compressed form */
+#define NTP_CSR 0   /* by destination: row v lists in-neighbours u ascending  (forward)  */
+#define NTP_CSC 1   /* by source:      row u lists out-neighbours v ascending (backward) */
+
+/* element types of feature / gradient / weight buffers */
+#define NTP_F32  0
+#define NTP_BF16 1  /* bfloat16 storage, fp32 accumulation, round-to-nearest-even stores */
+
+#define NTP_FWD 0
+#define NTP_BWD 1
+
+#define NTP_ACT_NONE 0
+#define NTP_ACT_RELU 1
+
+typedef struct ntp_graph ntp_graph_t;
+
+/*
+ * Build the normalised adjacency A_hat of Section 4.1.3 (D~^-1/2 (A+I) D~^-1/2 with
+ * NTP_SYMMETRISE|NTP_DEDUP|NTP_ADD_SELF_LOOPS|NTP_NORM_GCN_SYM) from a directed edge list
+ * and keep it in both compressed forms, as the replicated per-worker topology of
+ * Section 3.1.  Edge i is src[i] -> dst[i] (host int32 arrays of n_edges, ids in
+ * [0, n_vertices)).  edge_weight (host, nullable) is the per-edge gamma of Section 4.1.3;
+ * NULL means 1.  The stored value of an entry is
+ *     (float)((double)w * (1.0 / sqrt((double)deg_in(dst) * (double)deg_out(src))))
+ * with NTP_NORM_GCN_SYM (degrees = final row lengths, self loop included), else w.
+ * Processing order: input order; reversed copies after all originals; dedup keeps the
+ * first; self loops last; rows sorted by neighbour id, stable.
+ *
+ * Chunking (Section 4.2.1): the rows of each form are cut into contiguous ranges of at
+ * most chunk_edges entries, greedily, whole rows only; a row with more entries than
+ * chunk_edges is cut further by entry range.  chunk_edges = 0 lets the library choose
+ * (one chunk if everything fits the budget).  device_budget_bytes bounds the device
+ * memory the handle may hold for topology (resident chunks + two staging buffers);
+ * 0 = unlimited.  Chunks that fit stay resident from build time on; the others are
+ * streamed from pinned host memory by ntp_chunked_aggregate.
+ *
+ * The input arrays are copied; *out is owned by the library until ntp_graph_free.
+ * Errors: NTP_EINVAL (bad ids/sizes/flags), NTP_ENOMEM, NTP_EHIP, NTP_EBUDGET.
+ */
+int ntp_graph_build(int64_t n_vertices, int64_t n_edges,
+                    const int32_t* src, const int32_t* dst, const float* edge_weight,
+                    uint32_t flags, int64_t device_budget_bytes, int64_t chunk_edges,
+                    ntp_graph_t** out);
+
+/* Sizes of a built graph.  Any out pointer may be NULL.  nnz counts stored entries of the
+ * CSR (edges after symmetrisation/dedup + self loops); n_chunks/max_degree refer to the
+ * CSR; is_symmetric is 1 when CSC and CSR are bit-identical (the CSC then aliases it). */
+int ntp_graph_info(const ntp_graph_t* g, int64_t* n_vertices, int64_t* nnz,
+                   int32_t* n_chunks, int32_t* is_symmetric, int64_t* max_degree);
+
+/* Copy one compressed form to host arrays (rowptr[n+1] int64, colidx[nnz] int32,
+ * val[nnz] fp32), for bit-exact comparison.  Any of the three may be NULL. */
+int ntp_graph_export(const ntp_graph_t* g, int which,
+                     int64_t* rowptr, int32_t* colidx, float* val);
+
+/* Chunk table of one form: for chunk c, rows [row_begin[c], row_end[c]) and entries
+ * [entry_begin[c], entry_end[c]); resident[c] = 1 if it lives on the device.  Arrays
+ * (host, nullable) must hold n_chunks elements; *n_chunks is always written. */
+int ntp_graph_chunks(const ntp_graph_t* g, int which, int32_t* n_chunks,
+                     int64_t* row_begin, int64_t* row_end,
+                     int64_t* entry_begin, int64_t* entry_end, int32_t* resident);
+
+/* Device bytes held by the handle (resident topology, staging buffers, scratch). */
+int ntp_graph_device_bytes(const ntp_graph_t* g, int64_t* bytes);
+
+/*
+ * Forward aggregation of eq. (1)/(3) on one column slice (step 1 of Section 3.1; AGG in
+ * Alg. 1):   Y[v, 0:f] = sum over stored entries (v,u) of val(v,u) * X[u, 0:f].
+ * X, Y: device, [n_vertices x f_slice] with strides ldx, ldy; dtype NTP_F32 or NTP_BF16.
+ * fp32 accumulation; deterministic (no atomics).  Requires a fully resident CSR, else
+ * NTP_EBUDGET.  Asynchronous on `stream`.
+ */
+int ntp_aggregate_fwd(ntp_graph_t* g, const void* X, void* Y,
+                      int64_t f_slice, int64_t ldx, int64_t ldy, int dtype, void* stream);
+
+/*
+ * Backward aggregation (Section 4.2.1; AGG of the reverse loop in Alg. 1): the gradient of
+ * a source vertex is the weighted sum of the gradients of the vertices it points to,
+ *     Gin[u, 0:f] = sum over stored entries (v,u) of val(v,u) * Gout[v, 0:f] = A_hat^T Gout,
+ * computed as a gather over the by-source rows.  Same argument rules as the forward.
+ */
+int ntp_aggregate_bwd(ntp_graph_t* g, const void* Gout, void* Gin,
+                      int64_t f_slice, int64_t ldg_out, int64_t ldg_in, int dtype, void* stream);
+
+/*
+ * Chunk-scheduled aggregation (Section 4.2.1, inner chunk loop of Alg. 1): same result as
+ * ntp_aggregate_fwd / _bwd (direction NTP_FWD / NTP_BWD), produced chunk by chunk.
+ * Resident chunks are aggregated in place; every other chunk is copied from pinned host
+ * memory into one of two device staging buffers on copy_stream while the previous chunk
+ * is aggregated on compute_stream (events order the two).  X and Y stay on the device for
+ * the whole call.  Works for fully resident graphs too.  On return all work is enqueued;
+ * compute_stream has been made to wait for the copies it needs, and the staging buffers
+ * are protected across calls by events.  copy_stream must differ from compute_stream
+ * when any chunk is streamed (NTP_EINVAL otherwise).
+ */
+int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y,
+                          int64_t f_slice, int64_t ldx, int64_t ldy, int dtype,
+                          void* compute_stream, void* copy_stream);
+
+/*
+ * Dense transform, UPDATE of eq. (4):  H = act(A W),  A [n x k] (ld k), W [k x m] (ld m),
+ * H [n x m] (ld m), all device, row-major, dtype NTP_F32 (fp32 MFMA) or NTP_BF16 (bf16
+ * MFMA, fp32 accumulate, bf16 output).  act = NTP_ACT_NONE or NTP_ACT_RELU.
+ */
+int ntp_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,
+               int act, int dtype, void* stream);
+
+/*
+ * Gradients of the dense transform (UPDATE in the reverse loop of Alg. 1):
+ *   dZ = dH * 1[H > 0] for NTP_ACT_RELU (else dH);  dW = A^T dZ [k x m] (overwritten, always
+ *   fp32);  dA = dZ W^T [n x k] (skipped when dA is NULL).
+ * workspace: device scratch of at least ntp_nn_bwd_workspace_bytes(n,k,m) bytes, caller
+ * owned (holds the partial sums of the reduction over n).
+ */
+int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH,
+               void* dA, float* dW, int64_t n, int64_t k, int64_t m,
+               int act, int dtype, void* workspace, int64_t workspace_bytes, void* stream);
+
+int64_t ntp_nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m);
+
+/* Release a graph: waits for the device, frees device, pinned and host memory. NULL ok. */
+void ntp_graph_free(ntp_graph_t* g);
+
+/* Text of the last error raised on this thread ("" if none). Valid until the next call. */
+const char* ntp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NTP_H */

@@ -50,11 +50,16 @@ def make_graph(cfg: int, seed: int = 0, scale_down: int = 1):
     """Undirected edge list (each edge once) for config ``cfg``.
 
     Returns (n_vertices, src, dst).  With scale_down = k the vertex and edge
-    counts are divided by k (same generator, same parameters).
+    counts are divided by k (same generator, same parameters); the dense
+    Zipf graph divides its edge count by k^2 instead.
     """
     spec = CONFIGS[cfg]
     n = max(8, spec.n_vertices // scale_down)
     m = max(8, spec.n_undirected // scale_down)
+    if spec.graph == "zipf":
+        # the dense graph keeps its density (edges / vertices^2), not its average
+        # degree, which would exceed the degree cap on a small vertex set
+        m = max(8, spec.n_undirected // (scale_down * scale_down))
     if spec.graph == "er":
         src, dst = g.erdos_renyi_edges(n, m, seed)
     elif spec.graph == "rmat":

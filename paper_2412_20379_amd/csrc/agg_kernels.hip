@@ -1,0 +1,355 @@
+// Aggregation kernels for gfx950: Y[v,:] = sum_k val[k] * X[colidx[k],:] over the entries
+// of row v (eq. 1/3 of the paper on one column slice; the same kernel runs the by-source
+// rows for the backward pass of Section 4.2.1).
+//
+// Mapping.  A wavefront (64 lanes) is cut into R = 64/L groups of L lanes; the L lanes
+// of a group cover one feature row with one 4/8/16-byte vector load each, so a gather of
+// one neighbour row is one coalesced access.  Rows are binned by entry count on the host:
+//   - short rows:  one group per row, R rows per wavefront (no cross-lane reduction);
+//   - longer rows: one wavefront per row; 64 (index, weight) pairs are fetched with one
+//     coalesced load per lane, handed to the groups through the cross-lane network, the R
+//     groups gather R neighbour rows at a time and their sums are combined by a butterfly;
+//   - rows beyond the split threshold: cut into segments, one wavefront per segment, fp32
+//     partial sums to a scratch slot; reduce_kernel adds the slots of a row in order.
+// No atomics anywhere: the result is deterministic.
+#include <hip/hip_runtime.h>
+
+#include "ntp_internal.h"
+
+namespace ntp {
+
+namespace {
+
+__device__ __forceinline__ int bperm_i(int src_lane, int v) {
+    return __builtin_amdgcn_ds_bpermute(src_lane << 2, v);
+}
+__device__ __forceinline__ float bperm_f(int src_lane, float v) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
+}
+
+// a value every lane holds identically, moved to scalar registers
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v & 0xffffffff));
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// ---- element access: VEC consecutive elements <-> VEC floats -------------------------
+template <int VEC> struct IoF32 {
+    using elem = float;
+    static constexpr int kVec = VEC;
+    static __device__ __forceinline__ void load(const float* p, float (&v)[VEC]) {
+        if constexpr (VEC == 4) { const float4 t = *reinterpret_cast<const float4*>(p); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
+        else if constexpr (VEC == 2) { const float2 t = *reinterpret_cast<const float2*>(p); v[0] = t.x; v[1] = t.y; }
+        else { v[0] = *p; }
+    }
+    static __device__ __forceinline__ void store(float* p, const float (&v)[VEC]) {
+        if constexpr (VEC == 4) { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+        else if constexpr (VEC == 2) { *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]); }
+        else { *p = v[0]; }
+    }
+};
+
+template <int VEC> struct IoBf16 {
+    using elem = unsigned short;
+    static constexpr int kVec = VEC;
+    static __device__ __forceinline__ void unpack(unsigned w, float& lo, float& hi) {
+        lo = __uint_as_float(w << 16);
+        hi = __uint_as_float(w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void load(const unsigned short* p, float (&v)[VEC]) {
+        if constexpr (VEC == 8) { const uint4 t = *reinterpret_cast<const uint4*>(p); unpack(t.x, v[0], v[1]); unpack(t.y, v[2], v[3]); unpack(t.z, v[4], v[5]); unpack(t.w, v[6], v[7]); }
+        else if constexpr (VEC == 4) { const uint2 t = *reinterpret_cast<const uint2*>(p); unpack(t.x, v[0], v[1]); unpack(t.y, v[2], v[3]); }
+        else if constexpr (VEC == 2) { const unsigned t = *reinterpret_cast<const unsigned*>(p); unpack(t, v[0], v[1]); }
+        else { v[0] = __uint_as_float((unsigned)(*p) << 16); }
+    }
+    static __device__ __forceinline__ unsigned pack(float lo, float hi) {
+        return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+    }
+    static __device__ __forceinline__ void store(unsigned short* p, const float (&v)[VEC]) {
+        if constexpr (VEC == 8) { *reinterpret_cast<uint4*>(p) = make_uint4(pack(v[0], v[1]), pack(v[2], v[3]), pack(v[4], v[5]), pack(v[6], v[7])); }
+        else if constexpr (VEC == 4) { *reinterpret_cast<uint2*>(p) = make_uint2(pack(v[0], v[1]), pack(v[2], v[3])); }
+        else if constexpr (VEC == 2) { *reinterpret_cast<unsigned*>(p) = pack(v[0], v[1]); }
+        else { *p = (unsigned short)f32_to_bf16_rne(v[0]); }
+    }
+};
+
+// ---- the aggregation kernel -----------------------------------------------------------
+// L lanes per feature row, NACC vectors per lane (columns l*VEC + j*L*VEC), 4 wavefronts
+// per block, every wavefront an independent unit of work.  blockIdx.y walks column passes
+// when the slice is wider than L*VEC*NACC.
+template <class IO, int L, int NACC>
+__global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
+    using T = typename IO::elem;
+    constexpr int VEC = IO::kVec;
+    constexpr int R = 64 / L;
+    constexpr int PASS_W = L * VEC * NACC;
+    constexpr int UNR = L < 8 ? L : 8;      // gathers kept in flight per lane
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (wave >= a.wave_start[a.n_groups]) return;
+    int grp = 0;
+    while (grp + 1 < a.n_groups && wave >= a.wave_start[grp + 1]) ++grp;
+    const int item0 = wave - a.wave_start[grp];
+    const int mode = a.mode[grp];
+    const int g = lane / L;
+    const int l = lane % L;
+    const int colbase = (int)blockIdx.y * PASS_W + l * VEC;
+
+    bool act[NACC];
+#pragma unroll
+    for (int j = 0; j < NACC; ++j) act[j] = colbase + j * L * VEC < a.f;
+
+    const T* __restrict__ X = static_cast<const T*>(a.X) + colbase;
+    float acc[NACC][VEC];
+#pragma unroll
+    for (int j = 0; j < NACC; ++j)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[j][i] = 0.f;
+
+    // acc += w * X[c, columns of this lane]
+    auto gather = [&](int c, float w) {
+        const T* xr = X + (int64_t)c * a.ldx;
+#pragma unroll
+        for (int j = 0; j < NACC; ++j) {
+            if (act[j]) {
+                float x[VEC];
+                IO::load(xr + j * L * VEC, x);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[j][i] = fmaf(w, x[i], acc[j][i]);
+            }
+        }
+    };
+    // same, but an entry that is not there contributes exactly nothing (c is still a
+    // valid row so the load stays in bounds)
+    auto gather_if = [&](bool on, int c, float w) {
+        const T* xr = X + (int64_t)c * a.ldx;
+#pragma unroll
+        for (int j = 0; j < NACC; ++j) {
+            if (act[j]) {
+                float x[VEC];
+                IO::load(xr + j * L * VEC, x);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[j][i] = on ? fmaf(w, x[i], acc[j][i]) : acc[j][i];
+            }
+        }
+    };
+
+    if (mode == MODE_GROUP_PER_ROW) {
+        // ---- one group of L lanes per row ------------------------------------------
+        const int idx = item0 * R + g;
+        const bool valid = idx < a.item_count[grp];
+        int row = 0;
+        int64_t beg = 0;
+        int d = 0;
+        if (valid) {
+            row = a.rows[a.item_off[grp] + idx];
+            beg = a.rowptr[row - a.row_base];
+            d = (int)(a.rowptr[row - a.row_base + 1] - beg);
+        }
+        const int32_t* ci = a.colidx + (beg - a.e_base);
+        const float* vv = a.val + (beg - a.e_base);
+        for (int k0 = 0; __ballot(k0 < d) != 0; k0 += L) {
+            int c = row;
+            float w = 0.f;
+            if (k0 + l < d) { c = __builtin_nontemporal_load(ci + k0 + l); w = __builtin_nontemporal_load(vv + k0 + l); }
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                if (__ballot(k0 + j < d) == 0) break;
+                const int cj = bperm_i(g * L + j, c);
+                const float wj = bperm_f(g * L + j, w);
+                if (k0 + j < d) gather(cj, wj);
+            }
+        }
+        if (valid) {
+            T* y = static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase;
+#pragma unroll
+            for (int j = 0; j < NACC; ++j)
+                if (act[j]) IO::store(y + j * L * VEC, acc[j]);
+        }
+        return;
+    }
+
+    // ---- one wavefront per row or per segment ------------------------------------------
+    int row;
+    int64_t beg, end;
+    float* pout = nullptr;
+    if (mode == MODE_SEGMENT) {
+        const Segment* sp = a.segs + a.item_off[grp] + item0;
+        row = __builtin_amdgcn_readfirstlane(sp->row);
+        beg = uniform64(sp->e_begin);
+        end = beg + __builtin_amdgcn_readfirstlane(sp->len);
+        pout = a.partial + (int64_t)__builtin_amdgcn_readfirstlane(sp->slot) * a.f + colbase;
+    } else {
+        row = __builtin_amdgcn_readfirstlane(a.rows[a.item_off[grp] + item0]);
+        beg = uniform64(a.rowptr[row - a.row_base]);
+        end = uniform64(a.rowptr[row - a.row_base + 1]);
+    }
+    const int32_t* ci = a.colidx + (beg - a.e_base);
+    const float* vv = a.val + (beg - a.e_base);
+    const int64_t cnt = end - beg;
+
+    int c = row;
+    float w = 0.f;
+    if (lane < cnt) { c = __builtin_nontemporal_load(ci + lane); w = __builtin_nontemporal_load(vv + lane); }
+    for (int64_t base = 0; base < cnt; base += 64) {
+        const int n = (int)(cnt - base < 64 ? cnt - base : 64);
+        // fetch the next 64 pairs while this batch is gathered
+        int cn = row;
+        float wn = 0.f;
+        if (base + 64 + lane < cnt) { cn = __builtin_nontemporal_load(ci + base + 64 + lane); wn = __builtin_nontemporal_load(vv + base + 64 + lane); }
+        if (n == 64) {
+#pragma unroll UNR
+            for (int j = 0; j < L; ++j) {
+                int cj;
+                float wj;
+                if constexpr (R == 1) { cj = __builtin_amdgcn_readlane(c, j); wj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), j)); }
+                else { cj = bperm_i(j * R + g, c); wj = bperm_f(j * R + g, w); }
+                gather(cj, wj);
+            }
+        } else {
+            for (int j = 0; j * R < n; ++j) {
+                const int e = j * R + g;
+                const int cj = bperm_i(e, c);
+                const float wj = bperm_f(e, w);
+                gather_if(e < n, cj, wj);
+            }
+        }
+        c = cn;
+        w = wn;
+    }
+
+    // butterfly over the R groups
+#pragma unroll
+    for (int off = L; off < 64; off <<= 1)
+#pragma unroll
+        for (int j = 0; j < NACC; ++j)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[j][i] += bperm_f(lane ^ off, acc[j][i]);
+
+    if (g == 0) {
+        if (mode == MODE_SEGMENT) {
+#pragma unroll
+            for (int j = 0; j < NACC; ++j)
+                if (act[j]) IoF32<VEC>::store(pout + j * L * VEC, acc[j]);
+        } else {
+            T* y = static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase;
+#pragma unroll
+            for (int j = 0; j < NACC; ++j)
+                if (act[j]) IO::store(y + j * L * VEC, acc[j]);
+        }
+    }
+}
+
+// ---- second pass for split rows: Y[row,:] = sum of its partial-sum slots, in order ----
+template <class T>
+__global__ void __launch_bounds__(256) reduce_kernel(const ReduceArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= a.n_items) return;
+    const ReduceItem it = a.items[item];
+    for (int col = lane; col < a.f; col += 64) {
+        const float* p = a.partial + (int64_t)it.first_slot * a.f + col;
+        float s = 0.f;
+        for (int k = 0; k < it.n_slots; ++k) s += p[(int64_t)k * a.f];
+        T* y = static_cast<T*>(a.Y) + (int64_t)it.row * a.ldy + col;
+        if constexpr (sizeof(T) == 4) *y = s;
+        else *y = (T)f32_to_bf16_rne(s);
+    }
+}
+
+template <class IO, int L, int NACC>
+int launch_one(const AggArgs& a, int n_passes, hipStream_t st) {
+    const int total = a.wave_start[a.n_groups];
+    if (total <= 0) return NTP_OK;
+    dim3 grid((unsigned)((total + 3) / 4), (unsigned)n_passes);
+    hipLaunchKernelGGL((agg_kernel<IO, L, NACC>), grid, dim3(256), 0, st, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("aggregation kernel launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
+    return NTP_OK;
+}
+
+template <class IO>
+int launch_by_shape(const AggArgs& a, int L, int nacc, int n_passes, hipStream_t st) {
+    if (nacc == 1) {
+        switch (L) {
+            case 2: return launch_one<IO, 2, 1>(a, n_passes, st);
+            case 4: return launch_one<IO, 4, 1>(a, n_passes, st);
+            case 8: return launch_one<IO, 8, 1>(a, n_passes, st);
+            case 16: return launch_one<IO, 16, 1>(a, n_passes, st);
+            case 32: return launch_one<IO, 32, 1>(a, n_passes, st);
+            case 64: return launch_one<IO, 64, 1>(a, n_passes, st);
+        }
+    } else if (L == 64 && nacc == 2) {
+        return launch_one<IO, 64, 2>(a, n_passes, st);
+    } else if (L == 64 && nacc == 4) {
+        return launch_one<IO, 64, 4>(a, n_passes, st);
+    }
+    set_error("no aggregation kernel for lanes=%d acc=%d", L, nacc);
+    return NTP_EUNSUPPORTED;
+}
+
+}  // namespace
+
+void agg_shape(int64_t f, int vec, int* lanes_per_row, int* n_acc, int* n_passes) {
+    const int64_t nv = (f + vec - 1) / vec;    // vectors per row
+    int L = 2;
+    while (L < 64 && L < nv) L <<= 1;
+    int nacc = 1;
+    if (nv > 64) { nacc = nv > 128 ? 4 : 2; }
+    *lanes_per_row = L;
+    *n_acc = nacc;
+    *n_passes = (int)((nv + (int64_t)L * nacc - 1) / ((int64_t)L * nacc));
+}
+
+int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype) {
+    const int es = dtype == NTP_BF16 ? 2 : 4;
+    int vec = 16 / es;
+    const uintptr_t px = (uintptr_t)X, py = (uintptr_t)Y;
+    while (vec > 1 && (f % vec || ldx % vec || ldy % vec || px % (uintptr_t)(vec * es) || py % (uintptr_t)(vec * es))) vec >>= 1;
+    return vec;
+}
+
+int launch_aggregate(const AggArgs& a, int dtype, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    const int vec = agg_pick_vec(a.X, a.Y, a.f, a.ldx, a.ldy, dtype);
+    int L, nacc, passes;
+    agg_shape(a.f, vec, &L, &nacc, &passes);
+    if (dtype == NTP_F32) {
+        switch (vec) {
+            case 4: return launch_by_shape<IoF32<4>>(a, L, nacc, passes, st);
+            case 2: return launch_by_shape<IoF32<2>>(a, L, nacc, passes, st);
+            case 1: return launch_by_shape<IoF32<1>>(a, L, nacc, passes, st);
+        }
+    } else if (dtype == NTP_BF16) {
+        switch (vec) {
+            case 8: return launch_by_shape<IoBf16<8>>(a, L, nacc, passes, st);
+            case 4: return launch_by_shape<IoBf16<4>>(a, L, nacc, passes, st);
+            case 2: return launch_by_shape<IoBf16<2>>(a, L, nacc, passes, st);
+            case 1: return launch_by_shape<IoBf16<1>>(a, L, nacc, passes, st);
+        }
+    }
+    set_error("unsupported dtype %d", dtype);
+    return NTP_EUNSUPPORTED;
+}
+
+int launch_reduce(const ReduceArgs& a, int dtype, void* stream) {
+    if (a.n_items <= 0) return NTP_OK;
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid((unsigned)((a.n_items + 3) / 4));
+    if (dtype == NTP_F32) hipLaunchKernelGGL(reduce_kernel<float>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(reduce_kernel<unsigned short>, grid, dim3(256), 0, st, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("reduce kernel launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
+    return NTP_OK;
+}
+
+}  // namespace ntp

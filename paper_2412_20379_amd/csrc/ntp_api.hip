@@ -1,0 +1,463 @@
+// C boundary of libntp (see include/ntp.h): graph handle, device residency, the
+// aggregation calls and the chunk streamer of Section 4.2.1.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <climits>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "ntp_internal.h"
+
+using namespace ntp;
+
+#define HIP_TRY(expr)                                                                        \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) {                                                              \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e_));                        \
+            return NTP_EHIP;                                                                 \
+        }                                                                                    \
+    } while (0)
+
+struct Form {
+    HostSparse* m = nullptr;
+    Plan plan;
+    bool all_resident = false;
+};
+
+struct ntp_graph {
+    BuiltGraph g;
+    Form form[2];                  // NTP_CSR, NTP_CSC (unused when symmetric)
+    bool host_only = false;
+    bool pinned_entries = false;
+    // staging for streamed chunks
+    char* stage[2] = {nullptr, nullptr};
+    size_t stage_bytes = 0;
+    hipEvent_t ev_ready[2] = {nullptr, nullptr};   // copy of the chunk finished
+    hipEvent_t ev_free[2] = {nullptr, nullptr};    // kernels reading the buffer finished
+    bool stage_used[2] = {false, false};
+    int next_stage = 0;
+    char* pinned_meta = nullptr;                    // metas of streamed chunks
+    // partial sums of split rows
+    float* partial = nullptr;
+    size_t partial_bytes = 0;
+    int64_t device_bytes = 0;
+
+    Form& f(int which) { return form[(which == NTP_CSC && !g.symmetric) ? 1 : 0]; }
+    const Form& f(int which) const { return form[(which == NTP_CSC && !g.symmetric) ? 1 : 0]; }
+};
+
+namespace {
+
+void* alloc_plain(size_t bytes, void*) { return malloc(bytes); }
+void* alloc_pinned(size_t bytes, void*) {
+    void* p = nullptr;
+    if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) return nullptr;
+    return p;
+}
+
+void free_entries(HostSparse& m, bool pinned) {
+    if (pinned) { if (m.colidx) (void)hipHostFree(m.colidx); if (m.val) (void)hipHostFree(m.val); }
+    else { free(m.colidx); free(m.val); }
+    m.colidx = nullptr;
+    m.val = nullptr;
+}
+
+int upload_chunk(const HostSparse& m, Chunk& c, char* dst, hipStream_t st, bool async, const char* meta_src) {
+    const size_t ne = (size_t)(c.e_end - c.e_begin);
+    if (async) {
+        HIP_TRY(hipMemcpyAsync(dst, meta_src, c.meta.size(), hipMemcpyHostToDevice, st));
+        if (ne) {
+            HIP_TRY(hipMemcpyAsync(dst + c.img_off_colidx, m.colidx + c.e_begin, ne * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(hipMemcpyAsync(dst + c.img_off_val, m.val + c.e_begin, ne * 4, hipMemcpyHostToDevice, st));
+        }
+    } else {
+        HIP_TRY(hipMemcpy(dst, meta_src, c.meta.size(), hipMemcpyHostToDevice));
+        if (ne) {
+            HIP_TRY(hipMemcpy(dst + c.img_off_colidx, m.colidx + c.e_begin, ne * 4, hipMemcpyHostToDevice));
+            HIP_TRY(hipMemcpy(dst + c.img_off_val, m.val + c.e_begin, ne * 4, hipMemcpyHostToDevice));
+        }
+    }
+    return NTP_OK;
+}
+
+inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX : (1 << b)); }
+
+// Enqueue the kernels of one chunk whose image lives at `img` on the device.
+int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void* Y,
+              int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st) {
+    AggArgs a;
+    memset(&a, 0, sizeof a);
+    a.rowptr = reinterpret_cast<const int64_t*>(img + c.off_rowptr);
+    a.rows = reinterpret_cast<const int32_t*>(img + c.off_rows);
+    a.segs = reinterpret_cast<const Segment*>(img + c.off_segs);
+    a.colidx = reinterpret_cast<const int32_t*>(img + c.img_off_colidx);
+    a.val = reinterpret_cast<const float*>(img + c.img_off_val);
+    a.X = X;
+    a.Y = Y;
+    a.partial = G->partial;
+    a.row_base = c.row_begin;
+    a.e_base = c.e_begin;
+    a.ldx = ldx;
+    a.ldy = ldy;
+    a.f = (int32_t)f;
+
+    const int vec = agg_pick_vec(X, Y, f, ldx, ldy, dtype);
+    int L, nacc, passes;
+    agg_shape(f, vec, &L, &nacc, &passes);
+    const int R = 64 / L;
+
+    int ng = 0;
+    int64_t waves = 0;
+    auto add_group = [&](int mode, int off, int count, int64_t nw) {
+        a.wave_start[ng] = (int32_t)waves;
+        a.item_off[ng] = off;
+        a.item_count[ng] = count;
+        a.mode[ng] = mode;
+        waves += nw;
+        ++ng;
+    };
+    // heaviest work first: segments, then bins from long rows to short rows
+    if (c.n_segs > 0) add_group(MODE_SEGMENT, 0, c.n_segs, c.n_segs);
+    for (int b = NBINS - 1; b >= 0; --b) {
+        const int cnt = c.bin_count[b];
+        if (cnt == 0) continue;
+        const bool per_group = R > 1 && bin_max_degree(b) <= 2 * R;
+        if (per_group) add_group(MODE_GROUP_PER_ROW, c.bin_row_off[b], cnt, (cnt + R - 1) / R);
+        else add_group(MODE_WAVE_PER_ROW, c.bin_row_off[b], cnt, cnt);
+    }
+    if (waves > INT_MAX - 8) { set_error("chunk too large for one launch (%lld wavefronts)", (long long)waves); return NTP_EUNSUPPORTED; }
+    a.wave_start[ng] = (int32_t)waves;
+    a.n_groups = ng;
+    if (ng > 0) {
+        const int rc = launch_aggregate(a, dtype, st);
+        if (rc != NTP_OK) return rc;
+    }
+    if (c.n_reduce > 0) {
+        ReduceArgs r;
+        r.items = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
+        r.partial = G->partial;
+        r.Y = Y;
+        r.ldy = ldy;
+        r.f = (int32_t)f;
+        r.n_items = c.n_reduce;
+        const int rc = launch_reduce(r, dtype, st);
+        if (rc != NTP_OK) return rc;
+    }
+    return NTP_OK;
+}
+
+int ensure_partial(ntp_graph* G, const Form& F, int64_t f) {
+    const size_t need = (size_t)F.plan.n_slots * (size_t)f * sizeof(float);
+    if (need <= G->partial_bytes) return NTP_OK;
+    if (G->partial) {
+        HIP_TRY(hipDeviceSynchronize());       // earlier calls may still read the old buffer
+        HIP_TRY(hipFree(G->partial));
+        G->device_bytes -= (int64_t)G->partial_bytes;
+        G->partial = nullptr;
+        G->partial_bytes = 0;
+    }
+    void* p = nullptr;
+    if (hipMalloc(&p, need) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu scratch bytes failed", need); return NTP_ENOMEM; }
+    G->partial = (float*)p;
+    G->partial_bytes = need;
+    G->device_bytes += (int64_t)need;
+    return NTP_OK;
+}
+
+int check_agg_args(const ntp_graph* g, const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype) {
+    if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
+    if (g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
+    if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
+    if (f < 1 || f > INT_MAX / 4) { set_error("slice width %lld out of range", (long long)f); return NTP_EINVAL; }
+    if (ldx < f || ldy < f) { set_error("row stride smaller than the slice width"); return NTP_EINVAL; }
+    if (g->g.n > 0 && (!X || !Y)) { set_error("X or Y is NULL"); return NTP_EINVAL; }
+    if (X == Y && g->g.n > 0) { set_error("input and output must not overlap"); return NTP_EINVAL; }
+    if (ldx == f && ldy == f && g->g.n > 0) {
+        const size_t es = dtype == NTP_BF16 ? 2 : 4;
+        const char* x0 = (const char*)X; const char* y0 = (const char*)Y;
+        const size_t bytes = (size_t)g->g.n * (size_t)f * es;
+        if (x0 < y0 + bytes && y0 < x0 + bytes) { set_error("input and output must not overlap"); return NTP_EINVAL; }
+    }
+    return NTP_OK;
+}
+
+void destroy(ntp_graph* G) {
+    if (!G) return;
+    if (!G->host_only) (void)hipDeviceSynchronize();
+    for (int k = 0; k < 2; ++k) {
+        for (auto& c : G->form[k].plan.chunks)
+            if (c.d_image) (void)hipFree(c.d_image);
+        if (G->stage[k]) (void)hipFree(G->stage[k]);
+        if (G->ev_ready[k]) (void)hipEventDestroy(G->ev_ready[k]);
+        if (G->ev_free[k]) (void)hipEventDestroy(G->ev_free[k]);
+    }
+    if (G->partial) (void)hipFree(G->partial);
+    if (G->pinned_meta) (void)hipHostFree(G->pinned_meta);
+    free_entries(G->g.csr, G->pinned_entries);
+    free_entries(G->g.csc, G->pinned_entries);
+    delete G;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ntp_last_error(void) { return last_error(); }
+
+int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
+                    const float* edge_weight, uint32_t flags, int64_t budget, int64_t chunk_edges,
+                    ntp_graph_t** out) {
+    if (!out) { set_error("out is NULL"); return NTP_EINVAL; }
+    *out = nullptr;
+    if (n < 0 || n > INT_MAX - 1) { set_error("n_vertices %lld out of range", (long long)n); return NTP_EINVAL; }
+    if (n_edges < 0 || (n_edges > 0 && (!src || !dst))) { set_error("edge list missing"); return NTP_EINVAL; }
+    if (budget < 0 || chunk_edges < 0) { set_error("negative budget or chunk size"); return NTP_EINVAL; }
+    if (chunk_edges > INT_MAX) { set_error("chunk_edges must be below 2^31"); return NTP_EINVAL; }
+    const uint32_t known = NTP_SYMMETRISE | NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM | NTP_HOST_ONLY | NTP_FORCE_STREAM;
+    if (flags & ~known) { set_error("unknown flag bits 0x%x", flags & ~known); return NTP_EINVAL; }
+
+    ntp_graph* G = new (std::nothrow) ntp_graph();
+    if (!G) { set_error("out of host memory"); return NTP_ENOMEM; }
+    G->host_only = flags & NTP_HOST_ONLY;
+    const bool force_stream = flags & NTP_FORCE_STREAM;
+    // entries go to pinned memory whenever chunks may have to be streamed
+    G->pinned_entries = !G->host_only && (budget > 0 || force_stream);
+    EntryAllocator alloc{G->pinned_entries ? alloc_pinned : alloc_plain, nullptr};
+
+    int rc = build_host_graph(n, n_edges, src, dst, edge_weight, flags, alloc, &G->g);
+    if (rc != NTP_OK) { destroy(G); return rc; }
+    if (G->g.symmetric && G->g.csc.colidx) { free_entries(G->g.csc, G->pinned_entries); G->g.csc = HostSparse(); }
+
+    const int n_forms = G->g.symmetric ? 1 : 2;
+    G->form[0].m = &G->g.csr;
+    G->form[1].m = G->g.symmetric ? &G->g.csr : &G->g.csc;
+
+    // chunk size: caller's, else one chunk if everything fits, else half of what the
+    // budget leaves per staging buffer
+    int64_t ce = chunk_edges;
+    if (ce == 0 && (budget > 0 || force_stream)) {
+        int64_t need = 0;
+        for (int k = 0; k < n_forms; ++k) need += G->form[k].m->nnz * 8 + (n + 1) * 12 + 4096;
+        if (force_stream || need > budget) {
+            const int64_t per_buf = (budget > 0 ? budget : need) / 4;    // two buffers use half
+            ce = std::max<int64_t>(1024, std::min<int64_t>((per_buf - 4096) / 20, INT_MAX / 2));
+        }
+    }
+    for (int k = 0; k < n_forms; ++k) make_plan(*G->form[k].m, ce, &G->form[k].plan);
+    for (int k = 0; k < n_forms; ++k)
+        for (auto& c : G->form[k].plan.chunks)
+            if (c.e_end - c.e_begin > INT_MAX || G->form[k].plan.n_slots > INT_MAX / 2) {
+                set_error("a chunk holds more than 2^31 entries: pass a chunk_edges below that");
+                destroy(G);
+                return NTP_EUNSUPPORTED;
+            }
+
+    if (!G->host_only) {
+        size_t all = 0, max_img = 0;
+        for (int k = 0; k < n_forms; ++k) {
+            for (auto& c : G->form[k].plan.chunks) all += c.img_bytes;
+            max_img = std::max(max_img, G->form[k].plan.max_img_bytes);
+        }
+        const bool fits = !force_stream && (budget == 0 || (int64_t)all <= budget);
+        int64_t left = 0;
+        if (!fits) {
+            if (budget > 0 && (int64_t)(2 * max_img) > budget) {
+                set_error("device budget %lld cannot hold two staging buffers of %zu bytes", (long long)budget, max_img);
+                destroy(G);
+                return NTP_EBUDGET;
+            }
+            G->stage_bytes = max_img;
+            for (int b = 0; b < 2; ++b) {
+                void* p = nullptr;
+                if (hipMalloc(&p, max_img) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of a %zu-byte staging buffer failed", max_img); destroy(G); return NTP_ENOMEM; }
+                G->stage[b] = (char*)p;
+                G->device_bytes += (int64_t)max_img;
+                if (hipEventCreateWithFlags(&G->ev_ready[b], hipEventDisableTiming) != hipSuccess ||
+                    hipEventCreateWithFlags(&G->ev_free[b], hipEventDisableTiming) != hipSuccess) {
+                    set_error("hipEventCreate failed"); destroy(G); return NTP_EHIP;
+                }
+            }
+            left = force_stream ? 0 : budget - (int64_t)(2 * max_img);
+        }
+        // residency: everything if it fits, else chunks in round-robin order over the forms
+        size_t max_chunks = 0;
+        for (int k = 0; k < n_forms; ++k) max_chunks = std::max(max_chunks, G->form[k].plan.chunks.size());
+        size_t pinned_meta_bytes = 0;
+        for (size_t ci = 0; ci < max_chunks; ++ci)
+            for (int k = 0; k < n_forms; ++k) {
+                auto& chunks = G->form[k].plan.chunks;
+                if (ci >= chunks.size()) continue;
+                Chunk& c = chunks[ci];
+                const bool resident = fits || (int64_t)c.img_bytes <= left;
+                if (resident) {
+                    void* p = nullptr;
+                    if (hipMalloc(&p, c.img_bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of a %zu-byte chunk failed", c.img_bytes); destroy(G); return NTP_ENOMEM; }
+                    c.d_image = (char*)p;
+                    G->device_bytes += (int64_t)c.img_bytes;
+                    if (!fits) left -= (int64_t)c.img_bytes;
+                    rc = upload_chunk(*G->form[k].m, c, c.d_image, nullptr, false, c.meta.data());
+                    if (rc != NTP_OK) { destroy(G); return rc; }
+                } else {
+                    pinned_meta_bytes += c.meta.size();
+                }
+            }
+        for (int k = 0; k < n_forms; ++k) {
+            bool allr = true;
+            for (auto& c : G->form[k].plan.chunks) allr = allr && c.d_image;
+            G->form[k].all_resident = allr;
+        }
+        if (pinned_meta_bytes) {
+            void* p = nullptr;
+            if (hipHostMalloc(&p, pinned_meta_bytes, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); set_error("pinned allocation of %zu bytes failed", pinned_meta_bytes); destroy(G); return NTP_ENOMEM; }
+            G->pinned_meta = (char*)p;
+            size_t off = 0;
+            for (int k = 0; k < n_forms; ++k)
+                for (auto& c : G->form[k].plan.chunks)
+                    if (!c.d_image) {
+                        c.h_meta_pinned = G->pinned_meta + off;
+                        memcpy(c.h_meta_pinned, c.meta.data(), c.meta.size());
+                        off += c.meta.size();
+                    }
+        }
+        const hipError_t se = hipDeviceSynchronize();
+        if (se != hipSuccess) { set_error("hipDeviceSynchronize failed: %s", hipGetErrorString(se)); destroy(G); return NTP_EHIP; }
+    }
+    *out = G;
+    return NTP_OK;
+}
+
+int ntp_graph_info(const ntp_graph_t* g, int64_t* n, int64_t* nnz, int32_t* n_chunks,
+                   int32_t* is_symmetric, int64_t* max_degree) {
+    if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
+    if (n) *n = g->g.n;
+    if (nnz) *nnz = g->g.csr.nnz;
+    if (n_chunks) *n_chunks = (int32_t)g->form[0].plan.chunks.size();
+    if (is_symmetric) *is_symmetric = g->g.symmetric ? 1 : 0;
+    if (max_degree) *max_degree = g->g.csr.max_degree;
+    return NTP_OK;
+}
+
+int ntp_graph_export(const ntp_graph_t* g, int which, int64_t* rowptr, int32_t* colidx, float* val) {
+    if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
+    if (which != NTP_CSR && which != NTP_CSC) { set_error("which must be NTP_CSR or NTP_CSC"); return NTP_EINVAL; }
+    const HostSparse& m = *g->f(which).m;
+    if (rowptr) memcpy(rowptr, m.rowptr.data(), (size_t)(m.n + 1) * 8);
+    if (colidx && m.nnz) memcpy(colidx, m.colidx, (size_t)m.nnz * 4);
+    if (val && m.nnz) memcpy(val, m.val, (size_t)m.nnz * 4);
+    return NTP_OK;
+}
+
+int ntp_graph_chunks(const ntp_graph_t* g, int which, int32_t* n_chunks, int64_t* row_begin,
+                     int64_t* row_end, int64_t* entry_begin, int64_t* entry_end, int32_t* resident) {
+    if (!g || !n_chunks) { set_error("graph handle or n_chunks is NULL"); return NTP_EINVAL; }
+    if (which != NTP_CSR && which != NTP_CSC) { set_error("which must be NTP_CSR or NTP_CSC"); return NTP_EINVAL; }
+    const auto& chunks = g->f(which).plan.chunks;
+    *n_chunks = (int32_t)chunks.size();
+    for (size_t i = 0; i < chunks.size(); ++i) {
+        if (row_begin) row_begin[i] = chunks[i].row_begin;
+        if (row_end) row_end[i] = chunks[i].row_end;
+        if (entry_begin) entry_begin[i] = chunks[i].e_begin;
+        if (entry_end) entry_end[i] = chunks[i].e_end;
+        if (resident) resident[i] = chunks[i].d_image ? 1 : 0;
+    }
+    return NTP_OK;
+}
+
+int ntp_graph_device_bytes(const ntp_graph_t* g, int64_t* bytes) {
+    if (!g || !bytes) { set_error("NULL argument"); return NTP_EINVAL; }
+    *bytes = g->device_bytes;
+    return NTP_OK;
+}
+
+static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y, int64_t f,
+                              int64_t ldx, int64_t ldy, int dtype, void* stream) {
+    int rc = check_agg_args(g, X, Y, f, ldx, ldy, dtype);
+    if (rc != NTP_OK) return rc;
+    Form& F = g->f(which);
+    if (!F.all_resident) { set_error("topology is not fully device-resident: use ntp_chunked_aggregate"); return NTP_EBUDGET; }
+    if (g->g.n == 0) return NTP_OK;
+    rc = ensure_partial(g, F, f);
+    if (rc != NTP_OK) return rc;
+    for (auto& c : F.plan.chunks) {
+        rc = run_chunk(g, c, c.d_image, X, Y, f, ldx, ldy, dtype, (hipStream_t)stream);
+        if (rc != NTP_OK) return rc;
+    }
+    return NTP_OK;
+}
+
+int ntp_aggregate_fwd(ntp_graph_t* g, const void* X, void* Y, int64_t f, int64_t ldx, int64_t ldy,
+                      int dtype, void* stream) {
+    return aggregate_resident(g, NTP_CSR, X, Y, f, ldx, ldy, dtype, stream);
+}
+
+int ntp_aggregate_bwd(ntp_graph_t* g, const void* Gout, void* Gin, int64_t f, int64_t ldo, int64_t ldi,
+                      int dtype, void* stream) {
+    return aggregate_resident(g, NTP_CSC, Gout, Gin, f, ldo, ldi, dtype, stream);
+}
+
+int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y, int64_t f,
+                          int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream) {
+    int rc = check_agg_args(g, X, Y, f, ldx, ldy, dtype);
+    if (rc != NTP_OK) return rc;
+    if (direction != NTP_FWD && direction != NTP_BWD) { set_error("direction must be NTP_FWD or NTP_BWD"); return NTP_EINVAL; }
+    Form& F = g->f(direction == NTP_FWD ? NTP_CSR : NTP_CSC);
+    if (g->g.n == 0) return NTP_OK;
+    hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
+    if (!F.all_resident && cs == xs) { set_error("copy_stream must differ from compute_stream when chunks are streamed"); return NTP_EINVAL; }
+    rc = ensure_partial(g, F, f);
+    if (rc != NTP_OK) return rc;
+    for (auto& c : F.plan.chunks) {
+        if (c.d_image) {
+            rc = run_chunk(g, c, c.d_image, X, Y, f, ldx, ldy, dtype, cs);
+            if (rc != NTP_OK) return rc;
+            continue;
+        }
+        const int b = g->next_stage;
+        g->next_stage ^= 1;
+        // the buffer may still be read by the kernels of the chunk that used it last
+        if (g->stage_used[b]) HIP_TRY(hipStreamWaitEvent(xs, g->ev_free[b], 0));
+        rc = upload_chunk(*F.m, c, g->stage[b], xs, true, c.h_meta_pinned);
+        if (rc != NTP_OK) return rc;
+        HIP_TRY(hipEventRecord(g->ev_ready[b], xs));
+        HIP_TRY(hipStreamWaitEvent(cs, g->ev_ready[b], 0));
+        rc = run_chunk(g, c, g->stage[b], X, Y, f, ldx, ldy, dtype, cs);
+        if (rc != NTP_OK) return rc;
+        HIP_TRY(hipEventRecord(g->ev_free[b], cs));
+        g->stage_used[b] = true;
+    }
+    return NTP_OK;
+}
+
+int ntp_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,
+               int act, int dtype, void* stream) {
+    if (n < 0 || k < 1 || m < 1 || k > 65536 || m > 65536) { set_error("bad transform shape n=%lld k=%lld m=%lld", (long long)n, (long long)k, (long long)m); return NTP_EINVAL; }
+    if (n == 0) return NTP_OK;
+    if (!A || !W || !H) { set_error("NULL buffer"); return NTP_EINVAL; }
+    if (act != NTP_ACT_NONE && act != NTP_ACT_RELU) { set_error("unknown activation %d", act); return NTP_EINVAL; }
+    if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
+    return launch_nn_fwd(A, W, H, n, k, m, act, dtype, stream);
+}
+
+int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH, void* dA, float* dW,
+               int64_t n, int64_t k, int64_t m, int act, int dtype,
+               void* workspace, int64_t workspace_bytes, void* stream) {
+    if (n < 0 || k < 1 || m < 1 || k > 65536 || m > 65536) { set_error("bad transform shape n=%lld k=%lld m=%lld", (long long)n, (long long)k, (long long)m); return NTP_EINVAL; }
+    if (!dW) { set_error("dW is NULL"); return NTP_EINVAL; }
+    if (n > 0 && (!A || !dH || (dA && !W) || (act == NTP_ACT_RELU && !H))) { set_error("NULL buffer"); return NTP_EINVAL; }
+    if (act != NTP_ACT_NONE && act != NTP_ACT_RELU) { set_error("unknown activation %d", act); return NTP_EINVAL; }
+    if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
+    if (workspace_bytes < nn_bwd_workspace_bytes(n, k, m) || (!workspace && nn_bwd_workspace_bytes(n, k, m) > 0)) {
+        set_error("workspace too small: need %lld bytes", (long long)nn_bwd_workspace_bytes(n, k, m));
+        return NTP_EINVAL;
+    }
+    return launch_nn_bwd(A, W, H, dH, dA, dW, n, k, m, act, dtype, workspace, workspace_bytes, stream);
+}
+
+int64_t ntp_nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m) { return nn_bwd_workspace_bytes(n, k, m); }
+
+void ntp_graph_free(ntp_graph_t* g) { destroy(g); }
+
+}  // extern "C"

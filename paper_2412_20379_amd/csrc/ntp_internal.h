@@ -1,0 +1,166 @@
+// Internal structures of libntp: host-side graph, plan (bins, segments, chunks) and
+// the argument block handed to the aggregation kernels.  Not part of the C boundary.
+#pragma once
+
+#include <cstdint>
+#include <cstddef>
+#include <string>
+#include <vector>
+
+#include "ntp.h"
+
+namespace ntp {
+
+// ---------------------------------------------------------------------------------------
+// error reporting (thread-local text behind ntp_last_error)
+void set_error(const char* fmt, ...);
+const char* last_error();
+
+// ---------------------------------------------------------------------------------------
+// run fn(t, n_threads) on n_threads std::threads (t = 0..n_threads-1)
+int host_threads();
+void parallel_run(int n_threads, void (*fn)(int, int, void*), void* ctx);
+
+template <class F>
+inline void parallel_for_threads(int n_threads, F&& f) {
+    struct Ctx { F* f; } ctx{&f};
+    parallel_run(n_threads, [](int t, int nt, void* c) { (*static_cast<Ctx*>(c)->f)(t, nt); }, &ctx);
+}
+
+// ---------------------------------------------------------------------------------------
+// One compressed form on the host.  colidx/val may live in pinned memory (owner decides).
+struct HostSparse {
+    int64_t n = 0;
+    int64_t nnz = 0;
+    std::vector<int64_t> rowptr;   // n + 1
+    int32_t* colidx = nullptr;     // nnz
+    float* val = nullptr;          // nnz
+    bool pinned = false;           // colidx/val allocated with hipHostMalloc
+    int64_t max_degree = 0;
+};
+
+struct BuiltGraph {
+    int64_t n = 0;
+    HostSparse csr;    // by destination
+    HostSparse csc;    // by source (empty when symmetric: use csr)
+    bool symmetric = false;
+};
+
+// allocator hooks so that graph_build.cpp stays free of HIP: returns nullptr on failure
+struct EntryAllocator {
+    void* (*alloc)(size_t bytes, void* ctx);
+    void* ctx;
+};
+
+// Build both compressed forms from an edge list (see ntp.h for the processing order).
+// Returns NTP_OK or an error code (text set).
+int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
+                     const float* edge_weight, uint32_t flags, EntryAllocator alloc,
+                     BuiltGraph* out);
+
+// ---------------------------------------------------------------------------------------
+// Plan: how the rows of one compressed form are mapped to wavefronts.
+//
+// Rows are binned by entry count d:  bin 0: d <= 1, bin k (1..NBINS-2): 2^(k-1) < d <= 2^k,
+// last whole-row bin: everything up to split_threshold.  A row with more than
+// split_threshold entries is cut into segments of about seg_len entries; each segment is
+// summed by one wavefront into a partial-sum slot and a second small kernel adds the slots
+// of a row in order.
+constexpr int NBINS = 9;             // d<=1, 2, 3-4, 5-8, 9-16, 17-32, 33-64, 65-128, >128
+constexpr int NGROUPS = NBINS + 1;   // + the segment group
+
+struct Segment {        // one piece of a split row (device-visible, 24 bytes)
+    int64_t e_begin;    // first entry (global offset into colidx/val)
+    int32_t len;        // number of entries
+    int32_t row;        // row the piece belongs to
+    int32_t slot;       // partial-sum slot (global numbering within the form)
+    int32_t pad;
+};
+
+struct ReduceItem {     // a split row whose last segment lies in this chunk (16 bytes)
+    int32_t row;
+    int32_t first_slot;
+    int32_t n_slots;
+    int32_t pad;
+};
+
+struct Chunk {
+    int64_t row_begin = 0, row_end = 0;       // rows [row_begin, row_end)
+    int64_t e_begin = 0, e_end = 0;           // entries [e_begin, e_end)
+    bool partial_row = false;                  // chunk holds only pieces of one giant row
+    // meta blob (host copy; same layout on the device): rowptr slice | bin rows | segments | reduce items
+    std::vector<char> meta;
+    size_t off_rowptr = 0;                     // int64[row_end - row_begin + 1]
+    size_t off_rows = 0;                       // int32[n_bin_rows_total]
+    size_t off_segs = 0;                       // Segment[n_segs]
+    size_t off_reduce = 0;                     // ReduceItem[n_reduce]
+    int32_t bin_count[NBINS] = {0};            // rows per bin
+    int32_t bin_row_off[NBINS] = {0};          // offset of each bin's row list inside rows[]
+    int32_t n_segs = 0;
+    int32_t n_reduce = 0;
+    // device image layout: [meta | colidx | val], each part 256-byte aligned
+    size_t img_off_colidx = 0, img_off_val = 0, img_bytes = 0;
+    // residency
+    char* d_image = nullptr;                   // device image if resident
+    char* h_meta_pinned = nullptr;             // pinned copy of meta for streaming
+};
+
+struct Plan {
+    int64_t seg_len = 0;
+    int64_t split_threshold = 0;
+    int64_t chunk_edges = 0;
+    int64_t n_slots = 0;                       // partial-sum slots of the whole form
+    size_t max_img_bytes = 0;                  // largest chunk image (staging buffer size)
+    std::vector<Chunk> chunks;
+};
+
+// Build the plan of one compressed form.  chunk_edges <= 0: a single chunk.
+void make_plan(const HostSparse& m, int64_t chunk_edges, Plan* plan);
+
+// ---------------------------------------------------------------------------------------
+// Argument block of the aggregation kernel (passed by value).
+struct AggArgs {
+    const int64_t* rowptr;     // chunk slice: rowptr[r - row_base]
+    const int32_t* colidx;     // chunk slice: colidx[e - e_base]
+    const float* val;
+    const int32_t* rows;       // bin row lists (global row ids)
+    const Segment* segs;
+    const void* X;
+    void* Y;
+    float* partial;            // [n_slots x f] partial sums of split rows
+    int64_t row_base;
+    int64_t e_base;
+    int64_t ldx, ldy;
+    int32_t f;                 // slice width
+    int32_t n_groups;          // entries used in the tables below
+    int32_t wave_start[NGROUPS + 1];   // first wavefront of each group; last = total
+    int32_t item_off[NGROUPS];         // offset into rows[] (bins) or segs[] (segment group)
+    int32_t item_count[NGROUPS];       // rows / segments in the group
+    int32_t mode[NGROUPS];             // MODE_*
+};
+enum { MODE_GROUP_PER_ROW = 0, MODE_WAVE_PER_ROW = 1, MODE_SEGMENT = 2 };
+
+struct ReduceArgs {
+    const ReduceItem* items;
+    const float* partial;
+    void* Y;
+    int64_t ldy;
+    int32_t f;
+    int32_t n_items;
+};
+
+// kernels (agg_kernels.hip / nn_kernels.hip); stream is a hipStream_t
+int launch_aggregate(const AggArgs& a, int dtype, void* stream);
+int launch_reduce(const ReduceArgs& a, int dtype, void* stream);
+// lanes per row chosen for (f, vec): exposed for tests of the host logic
+void agg_shape(int64_t f, int vec, int* lanes_per_row, int* n_acc, int* n_passes);
+int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype);
+
+int launch_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,
+                  int act, int dtype, void* stream);
+int launch_nn_bwd(const void* A, const void* W, const void* H, const void* dH, void* dA, float* dW,
+                  int64_t n, int64_t k, int64_t m, int act, int dtype,
+                  void* workspace, int64_t workspace_bytes, void* stream);
+int64_t nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m);
+
+}  // namespace ntp

@@ -1,0 +1,158 @@
+// Host-side planning of one compressed form: chunk boundaries (Section 4.2.1: contiguous
+// destination ranges with all their entries, as large as allowed), degree bins that map
+// rows to wavefronts, and the segments of rows too long for one wavefront.
+#include "ntp_internal.h"
+
+#include <algorithm>
+#include <cstring>
+
+namespace ntp {
+
+namespace {
+
+inline int bin_of(int64_t d) {
+    if (d <= 1) return 0;
+    int b = 1;
+    int64_t hi = 2;
+    while (d > hi && b < NBINS - 1) { hi <<= 1; ++b; }
+    return b;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct ChunkBuilder {
+    const HostSparse& m;
+    Plan& plan;
+    std::vector<int32_t> bin_rows[NBINS];
+    std::vector<Segment> segs;
+    std::vector<ReduceItem> reduce;
+
+    void reset() {
+        for (auto& b : bin_rows) b.clear();
+        segs.clear();
+        reduce.clear();
+    }
+
+    void finish(Chunk& c) {
+        const int64_t nrows = c.row_end - c.row_begin;
+        size_t nbin = 0;
+        for (int b = 0; b < NBINS; ++b) {
+            c.bin_count[b] = (int32_t)bin_rows[b].size();
+            c.bin_row_off[b] = (int32_t)nbin;
+            nbin += bin_rows[b].size();
+        }
+        c.n_segs = (int32_t)segs.size();
+        c.n_reduce = (int32_t)reduce.size();
+        c.off_rowptr = 0;
+        c.off_rows = align_up(c.off_rowptr + (size_t)(nrows + 1) * 8, 16);
+        c.off_segs = align_up(c.off_rows + nbin * 4, 16);
+        c.off_reduce = align_up(c.off_segs + segs.size() * sizeof(Segment), 16);
+        const size_t meta_bytes = align_up(c.off_reduce + reduce.size() * sizeof(ReduceItem), 256);
+        c.meta.assign(meta_bytes, 0);
+        memcpy(c.meta.data() + c.off_rowptr, m.rowptr.data() + c.row_begin, (size_t)(nrows + 1) * 8);
+        for (int b = 0; b < NBINS; ++b)
+            if (!bin_rows[b].empty())
+                memcpy(c.meta.data() + c.off_rows + (size_t)c.bin_row_off[b] * 4, bin_rows[b].data(), bin_rows[b].size() * 4);
+        if (!segs.empty()) memcpy(c.meta.data() + c.off_segs, segs.data(), segs.size() * sizeof(Segment));
+        if (!reduce.empty()) memcpy(c.meta.data() + c.off_reduce, reduce.data(), reduce.size() * sizeof(ReduceItem));
+        const size_t ne = (size_t)(c.e_end - c.e_begin);
+        c.img_off_colidx = meta_bytes;
+        c.img_off_val = c.img_off_colidx + align_up(ne * 4, 256);
+        c.img_bytes = c.img_off_val + align_up(ne * 4, 256);
+        plan.max_img_bytes = std::max(plan.max_img_bytes, c.img_bytes);
+    }
+};
+
+}  // namespace
+
+void make_plan(const HostSparse& m, int64_t chunk_edges, Plan* plan) {
+    Plan& P = *plan;
+    P = Plan();
+    const int64_t n = m.n;
+    const bool chunked = chunk_edges > 0;
+    P.chunk_edges = chunked ? chunk_edges : 0;
+
+    // segment length: enough pieces to spread a hub over the chip, few enough that the
+    // partial sums stay a small fraction of the traffic
+    int64_t seg = 256;
+    while (seg < 4096 && seg * 32768 < m.nnz) seg <<= 1;
+    if (chunked) seg = std::min(seg, chunk_edges);
+    seg = std::max<int64_t>(seg, 1);
+    P.seg_len = seg;
+    P.split_threshold = chunked ? std::min(2 * seg, chunk_edges) : 2 * seg;
+
+    ChunkBuilder cb{m, P, {}, {}, {}};
+    int32_t next_slot = 0;
+    int64_t r = 0;
+    while (r < n) {
+        const int64_t e0 = m.rowptr[r];
+        int64_t r1;
+        if (!chunked) {
+            r1 = n;
+        } else {
+            // last row boundary with at most chunk_edges entries since e0, at least one row
+            const int64_t* b = std::upper_bound(m.rowptr.data() + r, m.rowptr.data() + n + 1, e0 + chunk_edges);
+            r1 = std::max<int64_t>(r + 1, (b - m.rowptr.data()) - 1);
+            r1 = std::min(r1, n);
+        }
+        const bool giant = chunked && (r1 == r + 1) && (m.rowptr[r + 1] - e0 > chunk_edges);
+        if (!giant) {
+            Chunk c;
+            c.row_begin = r; c.row_end = r1; c.e_begin = e0; c.e_end = m.rowptr[r1];
+            cb.reset();
+            for (int64_t v = r; v < r1; ++v) {
+                const int64_t d = m.rowptr[v + 1] - m.rowptr[v];
+                if (d > P.split_threshold) {
+                    const int64_t nseg = (d + seg - 1) / seg;
+                    const int64_t base = d / nseg, extra = d % nseg;
+                    int64_t e = m.rowptr[v];
+                    cb.reduce.push_back(ReduceItem{(int32_t)v, next_slot, (int32_t)nseg, 0});
+                    for (int64_t i = 0; i < nseg; ++i) {
+                        const int64_t l = base + (i < extra ? 1 : 0);
+                        cb.segs.push_back(Segment{e, (int32_t)l, (int32_t)v, next_slot++, 0});
+                        e += l;
+                    }
+                } else {
+                    cb.bin_rows[bin_of(d)].push_back((int32_t)v);
+                }
+            }
+            cb.finish(c);
+            P.chunks.push_back(std::move(c));
+        } else {
+            // one row larger than a chunk: its segments are packed into chunks of their own
+            const int64_t d = m.rowptr[r + 1] - e0;
+            const int64_t nseg = (d + seg - 1) / seg;
+            const int64_t base = d / nseg, extra = d % nseg;
+            const int32_t first_slot = next_slot;
+            int64_t e = e0;
+            int64_t i = 0;
+            while (i < nseg) {
+                Chunk c;
+                c.row_begin = r; c.row_end = r + 1; c.partial_row = true;
+                c.e_begin = e;
+                cb.reset();
+                int64_t used = 0;
+                while (i < nseg) {
+                    const int64_t l = base + (i < extra ? 1 : 0);
+                    if (used + l > chunk_edges && used > 0) break;
+                    cb.segs.push_back(Segment{e, (int32_t)l, (int32_t)r, next_slot++, 0});
+                    e += l; used += l; ++i;
+                }
+                c.e_end = e;
+                if (i == nseg) cb.reduce.push_back(ReduceItem{(int32_t)r, first_slot, (int32_t)nseg, 0});
+                cb.finish(c);
+                P.chunks.push_back(std::move(c));
+            }
+        }
+        r = r1;
+    }
+    if (n == 0) {   // an empty graph still has one (empty) chunk
+        Chunk c;
+        cb.reset();
+        cb.finish(c);
+        P.chunks.push_back(std::move(c));
+    }
+    P.n_slots = next_slot;
+}
+
+}  // namespace ntp

@@ -1,0 +1,116 @@
+"""Layer-wise and decoupled GCN epochs composed from the library calls.
+
+Harness code: it owns the device buffers (torch tensors) and the order of the calls;
+all aggregation and transform arithmetic runs inside libntp.  The softmax
+cross-entropy at the end of the forward pass is the downstream task of Alg. 1 and is
+not part of the library; it is a few torch ops on the logits.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as ntp
+
+
+class GcnEpoch:
+    """One forward + backward pass of an L-layer GCN on one GPU (no optimiser step).
+
+    layer-wise (Section 3.1):  A_l = A_hat H_{l-1};  H_l = relu(A_l W_l), logits = A_L W_L
+    decoupled (Section 4.1):   H = MLP(X);  Z = A_hat^L H
+    """
+
+    def __init__(self, graph: ntp.Graph, n: int, dims, device="cuda:0", order="layerwise", chunked=False):
+        self.g, self.n, self.dims, self.order, self.chunked = graph, n, tuple(dims), order, chunked
+        L = len(dims) - 1
+        f32 = dict(dtype=torch.float32, device=device)
+        self.aggs = [torch.empty(n, dims[l], **f32) for l in range(L)] if order == "layerwise" else []
+        self.hid = [torch.empty(n, dims[l + 1], **f32) for l in range(L)]
+        self.dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
+        wmax = max(dims)
+        self.tmp = [torch.empty(n, wmax, **f32) for _ in range(2)]
+        ws = max(ntp.ntp_nn_bwd_workspace_bytes(n, dims[l], dims[l + 1]) for l in range(L))
+        self.ws_bytes = ws
+        self.ws = torch.empty(max(ws, 4), dtype=torch.uint8, device=device)
+        self.copy_stream = torch.cuda.Stream(device=device) if chunked else None
+        self.loss = None
+        self.logits = None
+
+    def _agg(self, direction, src, dst, f):
+        st = torch.cuda.current_stream()
+        if self.chunked:
+            ntp.ntp_chunked_aggregate(self.g, direction, src, dst, f, f, f, ntp.NTP_F32, st, self.copy_stream)
+        elif direction == ntp.NTP_FWD:
+            ntp.ntp_aggregate_fwd(self.g, src, dst, f, f, f, ntp.NTP_F32, st)
+        else:
+            ntp.ntp_aggregate_bwd(self.g, src, dst, f, f, f, ntp.NTP_F32, st)
+
+    def _view(self, i, f):
+        return self.tmp[i].view(-1)[: self.n * f].view(self.n, f)
+
+    def _loss_grad(self, Z, labels):
+        logp = torch.log_softmax(Z, dim=1)
+        self.loss = -logp.gather(1, labels.view(-1, 1)).mean()
+        dZ = torch.exp(logp)
+        dZ.scatter_add_(1, labels.view(-1, 1), torch.full((self.n, 1), -1.0, device=Z.device))
+        dZ.div_(self.n)
+        return dZ
+
+    def run(self, X, weights, labels):
+        return self._layerwise(X, weights, labels) if self.order == "layerwise" else self._decoupled(X, weights, labels)
+
+    def _layerwise(self, X, Ws, labels):
+        n, d = self.n, self.dims
+        L = len(Ws)
+        st = torch.cuda.current_stream()
+        H = X
+        for l in range(L):
+            self._agg(ntp.NTP_FWD, H, self.aggs[l], d[l])
+            act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+            ntp.ntp_nn_fwd(self.aggs[l], Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
+            H = self.hid[l]
+        self.logits = H
+        dH = self._loss_grad(H, labels)
+        for l in range(L - 1, -1, -1):
+            act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+            dA = self._view(0, d[l]) if l > 0 else None
+            ntp.ntp_nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
+                           ntp.NTP_F32, self.ws, self.ws_bytes, st)
+            if l > 0:
+                dH = self._view(1, d[l])
+                self._agg(ntp.NTP_BWD, dA, dH, d[l])
+        return self.loss
+
+    def _decoupled(self, X, Ws, labels):
+        n, d = self.n, self.dims
+        L = len(Ws)
+        st = torch.cuda.current_stream()
+        ins = [X]
+        H = X
+        for l in range(L):
+            act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+            ntp.ntp_nn_fwd(H, Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
+            H = self.hid[l]
+            ins.append(H)
+        c = d[-1]
+        Z = H
+        for k in range(L):          # L rounds of aggregation at the output width, no intermediates kept
+            out = self._view(k % 2, c)
+            self._agg(ntp.NTP_FWD, Z, out, c)
+            Z = out
+        self.logits = Z
+        dZ = self._loss_grad(Z, labels)
+        for k in range(L):
+            out = self._view(k % 2, c)
+            self._agg(ntp.NTP_BWD, dZ, out, c)
+            dZ = out
+        dH = dZ
+        for l in range(L - 1, -1, -1):
+            act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+            dA = None
+            if l > 0:
+                # the two scratch views are free again except the one holding dH
+                dA = self._view(0 if dH.data_ptr() != self.tmp[0].data_ptr() else 1, d[l])
+            ntp.ntp_nn_bwd(ins[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
+                           ntp.NTP_F32, self.ws, self.ws_bytes, st)
+            dH = dA
+        return self.loss

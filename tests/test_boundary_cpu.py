@@ -1,0 +1,158 @@
+"""Host-side tests of the C boundary (no GPU): exported symbols, bit-exact graph
+construction against the oracle, chunk planning, argument checking."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import ntp_inputs as gen
+import paper_2412_20379_amd as ntp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HOST = ntp.NTP_HOST_ONLY
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "ntp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(ntp_[a-z_]+)\s*\(", text)))
+    assert declared, "no declarations found"
+    L = ntp.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(ntp.EXPORTED_SYMBOLS) == declared
+
+
+def _assert_same(g, og):
+    for which, m in ((ntp.NTP_CSR, og.csr), (ntp.NTP_CSC, og.csc)):
+        rowptr, colidx, val = ntp.ntp_graph_export(g, which)
+        np.testing.assert_array_equal(rowptr, m.rowptr)
+        np.testing.assert_array_equal(colidx, m.colidx)
+        np.testing.assert_array_equal(val.view(np.uint32), m.val.view(np.uint32))
+    info = ntp.ntp_graph_info(g)
+    assert info["nnz"] == og.nnz and info["n_vertices"] == og.n
+    assert info["is_symmetric"] == og.is_symmetric
+    assert info["max_degree"] == int(og.d_in.max()) if og.n else True
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_graph_build_bit_exact_configs(cfg):
+    n, src, dst = gen.make_graph(cfg, seed=0)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | HOST)
+    og = oracle.build_graph(n, src, dst)
+    _assert_same(g, og)
+    spec = gen.CONFIGS[cfg]
+    assert og.nnz == 2 * spec.n_undirected + n
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_graph_build_bit_exact_directed(seed):
+    n = 3000
+    src, dst = gen.directed_random_edges(n, 40000, seed, hub=5, hub_in=2500, hub_out=700)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | HOST)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    assert not og.is_symmetric
+    _assert_same(g, og)
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_graph_build_every_flag_combination(flags, weighted):
+    n = 200
+    src, dst = gen.directed_random_edges(n, 1500, seed=flags, hub=0, hub_in=100, hub_out=50)
+    # make sure loops and repeated pairs are present
+    src = np.concatenate([src, src[:50], np.arange(20, dtype=np.int32)])
+    dst = np.concatenate([dst, dst[:50], np.arange(20, dtype=np.int32)])
+    w = gen.stream_rng(flags, 9).random(src.size).astype(np.float32) + 0.5 if weighted else None
+    g = ntp.ntp_graph_build(n, src, dst, w, flags=flags | HOST)
+    og = oracle.build_graph(n, src, dst, flags, w)
+    _assert_same(g, og)
+
+
+def test_symmetric_input_without_symmetrise_flag_is_detected():
+    n = 500
+    s, d = gen.erdos_renyi_edges(n, 2000, 3)
+    src, dst = np.concatenate([s, d]), np.concatenate([d, s])
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | HOST)
+    assert ntp.ntp_graph_info(g)["is_symmetric"]
+    _assert_same(g, oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS))
+
+
+def test_empty_and_edgeless_graphs():
+    g = ntp.ntp_graph_build(0, [], [], flags=ntp.NTP_GCN_FLAGS | HOST)
+    assert ntp.ntp_graph_info(g)["nnz"] == 0
+    g = ntp.ntp_graph_build(5, [], [], flags=ntp.NTP_GCN_FLAGS | HOST)
+    rowptr, colidx, val = ntp.ntp_graph_export(g)
+    assert rowptr.tolist() == [0, 1, 2, 3, 4, 5] and colidx.tolist() == [0, 1, 2, 3, 4]
+    assert np.all(val == 1.0)
+
+
+@pytest.mark.parametrize("chunk_edges", [1, 3, 17, 100, 1009, 50000, 10 ** 9])
+def test_chunk_plan_matches_greedy_rule(chunk_edges):
+    n = 2000
+    src, dst = gen.directed_random_edges(n, 20000, 4, hub=9, hub_in=1500, hub_out=10)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | HOST, chunk_edges=chunk_edges)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    for which, m in ((ntp.NTP_CSR, og.csr), (ntp.NTP_CSC, og.csc)):
+        ch = ntp.ntp_graph_chunks(g, which)
+        # entries are covered once, in order
+        assert ch["entry_begin"][0] == 0 and ch["entry_end"][-1] == m.nnz
+        np.testing.assert_array_equal(ch["entry_begin"][1:], ch["entry_end"][:-1])
+        assert np.all(ch["entry_end"] - ch["entry_begin"] <= max(chunk_edges, 1))
+        # whole-row chunks follow the greedy rule; a row above the limit is cut by entry range
+        want = oracle.plan_chunks(m.rowptr, chunk_edges)
+        rows = sorted(set(zip(ch["row_begin"].tolist(), ch["row_end"].tolist())))
+        assert rows == want
+        for (r0, r1) in want:
+            sel = (ch["row_begin"] == r0) & (ch["row_end"] == r1)
+            assert ch["entry_begin"][sel].min() == m.rowptr[r0] and ch["entry_end"][sel].max() == m.rowptr[r1]
+            if sel.sum() > 1:
+                assert r1 == r0 + 1 and m.rowptr[r1] - m.rowptr[r0] > chunk_edges
+
+
+def test_argument_errors():
+    L = ntp.lib()
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_graph_build(3, [0, 5], [1, 2], flags=HOST)
+    assert e.value.code == ntp.NTP_EINVAL and "outside" in str(e.value)
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_graph_build(3, [0], [1], flags=HOST | 1024)
+    assert e.value.code == ntp.NTP_EINVAL
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_graph_build(-1, [], [], flags=HOST)
+    assert e.value.code == ntp.NTP_EINVAL
+    g = ntp.ntp_graph_build(3, [0], [1], flags=ntp.NTP_GCN_FLAGS | HOST)
+    x = np.zeros((3, 4), np.float32)
+    y = np.zeros((3, 4), np.float32)
+    with pytest.raises(ntp.NtpError) as e:      # host-only graph: nothing on the device
+        ntp.ntp_aggregate_fwd(g, x, y, 4, 4, 4)
+    assert e.value.code == ntp.NTP_EBUDGET
+    assert L.ntp_graph_info(None, None, None, None, None, None) == ntp.NTP_EINVAL
+    assert "NULL" in ntp.ntp_last_error()
+    assert L.ntp_graph_export(g.handle, 7, None, None, None) == ntp.NTP_EINVAL
+    # transform argument checks happen before any device work
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_nn_fwd(x, x, y, 3, 0, 4)
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_nn_fwd(x, x, y, 3, 4, 4, act=9)
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_nn_bwd(x, x, y, y, None, None, 3, 4, 4)
+    assert ntp.ntp_nn_bwd_workspace_bytes(100000, 256, 256) > 0
+    L.ntp_graph_free(None)                       # NULL is allowed
+
+
+def test_inputs_are_reproducible():
+    a = gen.make_graph(2, seed=0, scale_down=16)
+    b = gen.make_graph(2, seed=0, scale_down=16)
+    c = gen.make_graph(2, seed=1, scale_down=16)
+    np.testing.assert_array_equal(a[1], b[1])
+    np.testing.assert_array_equal(a[2], b[2])
+    assert not np.array_equal(a[1], c[1])
+    n, s, d = gen.make_graph(4, seed=0, scale_down=8)
+    deg = np.bincount(np.concatenate([s, d]), minlength=n)
+    assert deg.max() > 5 * deg.mean() and deg.min() >= 1             # heavy head, no isolated vertex
+    n, s, d = gen.make_graph(3, seed=0, scale_down=64)
+    deg = np.bincount(np.concatenate([s, d]), minlength=n)
+    assert deg.max() > 50 * deg.mean()                              # power-law hubs

@@ -1,0 +1,189 @@
+"""GPU parity of ntp_aggregate_fwd / ntp_aggregate_bwd against the CPU oracle."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import ntp_inputs as gen
+import paper_2412_20379_amd as ntp
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(scope="module")
+def hub_graph():
+    """directed, 3000 vertices, every degree bin populated, one hub above the split threshold"""
+    n = 3000
+    src, dst = gen.directed_random_edges(n, 40000, 21, hub=5, hub_in=2600, hub_out=900)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    assert not og.is_symmetric
+    yield g, og
+    g.close()
+
+
+@pytest.mark.parametrize("f", [1, 7, 13, 16, 32, 76, 100, 128, 256, 602, 1433])
+@pytest.mark.parametrize("direction", ["fwd", "bwd"])
+def test_widths_fp32(hub_graph, f, direction):
+    from gpu_util import check_agg
+    g, og = hub_graph
+    say("widths_fp32", f, direction)
+    x = gen.normal_features(og.n, f, seed=f)
+    check_agg(g, og, x, direction, "f32", "f=%d %s" % (f, direction))
+
+
+@pytest.mark.parametrize("f", [1, 6, 8, 16, 76, 100, 128, 520])
+@pytest.mark.parametrize("direction", ["fwd", "bwd"])
+def test_widths_bf16(hub_graph, f, direction):
+    from gpu_util import check_agg
+    g, og = hub_graph
+    say("widths_bf16", f, direction)
+    x = gen.normal_features(og.n, f, seed=100 + f)
+    check_agg(g, og, x, direction, "bf16", "bf16 f=%d %s" % (f, direction))
+
+
+@pytest.mark.parametrize("f,ld_in,ld_out", [(32, 40, 32), (32, 32, 48), (76, 602, 80), (13, 100, 13), (16, 17, 19), (64, 65, 66)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_strided_layouts(hub_graph, f, ld_in, ld_out, dtype):
+    from gpu_util import check_agg
+    g, og = hub_graph
+    say("strided", f, ld_in, ld_out, dtype)
+    x = gen.normal_features(og.n, f, seed=7)
+    check_agg(g, og, x, "fwd", dtype, "strided", ld_in=ld_in, ld_out=ld_out)
+    check_agg(g, og, x, "bwd", dtype, "strided", ld_in=ld_in, ld_out=ld_out)
+
+
+def test_degree_edge_cases():
+    """rows with exactly the entry counts around every bin and split boundary"""
+    from gpu_util import check_agg
+    degs = [1, 2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257,
+            511, 512, 513, 1023, 1024, 1025, 2047, 2048, 2049, 5000]
+    n = 6000
+    rng = gen.stream_rng(5, 1)
+    src, dst = [], []
+    for v, d in enumerate(degs):            # vertex v gets d-1 in-edges (+ self loop = d entries)
+        others = rng.choice(np.setdiff1d(np.arange(n), [v]), size=d - 1, replace=False)
+        src.append(others)
+        dst.append(np.full(d - 1, v))
+    src = np.concatenate(src).astype(np.int32)
+    dst = np.concatenate(dst).astype(np.int32)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    assert [int(og.d_in[v]) for v in range(len(degs))] == degs
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    for f in (4, 16, 32, 76, 128, 256):
+        say("degree_edge_cases f", f)
+        x = gen.normal_features(n, f, seed=f)
+        check_agg(g, og, x, "fwd", "f32", "degrees f=%d" % f)
+        check_agg(g, og, x, "bwd", "f32", "degrees bwd f=%d" % f)
+    check_agg(g, og, gen.normal_features(n, 32, seed=1), "fwd", "bf16", "degrees bf16")
+    g.close()
+
+
+def test_empty_rows_without_self_loops():
+    from gpu_util import check_agg, run_agg
+    n = 500
+    src, dst = gen.directed_random_edges(n, 600, 31)
+    flags = oracle.DEDUP | oracle.NORM_GCN_SYM
+    og = oracle.build_graph(n, src, dst, flags)
+    assert (og.d_in == 0).sum() > 50
+    g = ntp.ntp_graph_build(n, src, dst, flags=flags)
+    x = gen.normal_features(n, 24, seed=3)
+    got = check_agg(g, og, x, "fwd", "f32", "empty rows")
+    assert np.all(got[og.d_in == 0] == 0)
+    check_agg(g, og, x, "bwd", "f32", "empty rows bwd")
+    g.close()
+
+
+def test_custom_edge_weights_and_no_norm():
+    from gpu_util import check_agg
+    n = 800
+    src, dst = gen.directed_random_edges(n, 9000, 33, hub=1, hub_in=700, hub_out=5)
+    w = (gen.stream_rng(33, 9).random(src.size) + 0.01).astype(np.float32)
+    for flags in (0, oracle.DEDUP | oracle.ADD_SELF_LOOPS, oracle.SYMMETRISE | oracle.DEDUP | oracle.NORM_GCN_SYM | oracle.ADD_SELF_LOOPS):
+        og = oracle.build_graph(n, src, dst, flags, w)
+        g = ntp.ntp_graph_build(n, src, dst, w, flags=flags)
+        x = gen.normal_features(n, 20, seed=4)
+        check_agg(g, og, x, "fwd", "f32", "weights flags=%d" % flags)
+        check_agg(g, og, x, "bwd", "f32", "weights bwd flags=%d" % flags)
+        g.close()
+
+
+def test_deterministic_and_unaligned_pointers(hub_graph):
+    import torch
+    from gpu_util import DEV
+    g, og = hub_graph
+    f = 32
+    x = gen.normal_features(og.n, f, seed=9)
+    base = torch.zeros(og.n * f + 8, dtype=torch.float32, device=DEV)
+    outb = torch.zeros(og.n * f + 8, dtype=torch.float32, device=DEV)
+    ref, ref_abs = oracle.aggregate(og.csr, x, with_abs=True)
+    from helpers import assert_close, TOL_F32
+    prev = None
+    for off in (0, 1, 2, 4):                      # element offsets: 16-, 4-, 8-, 16-byte aligned
+        xin = base[off:off + og.n * f].view(og.n, f)
+        xin.copy_(torch.from_numpy(x))
+        out = outb[off:off + og.n * f].view(og.n, f)
+        out.zero_()
+        ntp.ntp_aggregate_fwd(g, xin, out, f, f, f)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert_close(got, ref, ref_abs, TOL_F32, "offset %d" % off)
+        if off in (0, 4):
+            out2 = torch.empty_like(out)
+            ntp.ntp_aggregate_fwd(g, xin, out2, f, f, f)
+            torch.cuda.synchronize()
+            assert np.array_equal(out2.cpu().numpy().view(np.uint32), got.view(np.uint32)), "not deterministic"
+            if prev is not None:
+                assert np.array_equal(prev.view(np.uint32), got.view(np.uint32))
+            prev = got
+
+
+def test_argument_errors_on_device(hub_graph):
+    import torch
+    from gpu_util import DEV
+    g, og = hub_graph
+    x = torch.zeros(og.n, 8, device=DEV)
+    y = torch.zeros(og.n, 8, device=DEV)
+    for bad in (dict(f=0, ldx=8, ldy=8), dict(f=8, ldx=4, ldy=8), dict(f=8, ldx=8, ldy=7)):
+        with pytest.raises(ntp.NtpError) as e:
+            ntp.ntp_aggregate_fwd(g, x, y, bad["f"], bad["ldx"], bad["ldy"])
+        assert e.value.code == ntp.NTP_EINVAL
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_aggregate_fwd(g, x, x, 8, 8, 8)
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_aggregate_fwd(g, x, y, 8, 8, 8, dtype=5)
+
+
+@pytest.mark.parametrize("cfg,widths", [(1, (1433, 16)), (2, (128, 256))])
+def test_configs_full(cfg, widths):
+    from gpu_util import check_agg
+    n, src, dst = gen.make_graph(cfg, seed=0)
+    og = oracle.build_graph(n, src, dst)
+    g = ntp.ntp_graph_build(n, src, dst)
+    for f in widths:
+        say("config", cfg, "f", f)
+        x = gen.make_features(cfg, f, seed=0) if cfg == 1 else gen.normal_features(n, f, 0)
+        check_agg(g, og, x, "fwd", "f32", "cfg%d f=%d" % (cfg, f))
+        check_agg(g, og, x, "bwd", "f32", "cfg%d bwd f=%d" % (cfg, f))
+    g.close()
+
+
+@pytest.mark.parametrize("cfg,scale,f,dtypes", [(3, 16, 32, ("f32",)), (3, 16, 13, ("f32",)),
+                                                 (4, 8, 76, ("f32", "bf16")), (4, 8, 16, ("f32", "bf16")),
+                                                 (5, 512, 16, ("f32",))])
+def test_configs_scaled_down(cfg, scale, f, dtypes):
+    from gpu_util import check_agg
+    n, src, dst = gen.make_graph(cfg, seed=0, scale_down=scale)
+    og = oracle.build_graph(n, src, dst)
+    g = ntp.ntp_graph_build(n, src, dst)
+    say("config", cfg, "scaled 1/%d" % scale, "n", n, "nnz", og.nnz, "max degree", int(og.d_in.max()))
+    x = gen.normal_features(n, f, 0)
+    for dt in dtypes:
+        check_agg(g, og, x, "fwd", dt, "cfg%d/%d f=%d %s" % (cfg, scale, f, dt))
+        check_agg(g, og, x, "bwd", dt, "cfg%d/%d bwd f=%d %s" % (cfg, scale, f, dt))
+    g.close()

@@ -1,0 +1,113 @@
+"""GPU parity of ntp_nn_fwd / ntp_nn_bwd (dense transform of eq. 4) against the oracle."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import gcn as ogcn
+import ntp_inputs as gen
+import paper_2412_20379_amd as ntp
+from helpers import assert_close, TOL_F32, TOL_BF16
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def _abs_scale(A, B):
+    return np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)
+
+
+SHAPES = [(1, 1, 1), (5, 3, 2), (300, 16, 7), (257, 33, 65), (1000, 128, 256), (2708, 1433, 16),
+          (4097, 256, 256), (3000, 256, 40), (2050, 100, 47), (1500, 602, 128), (999, 128, 41), (70000, 64, 32)]
+
+
+@pytest.mark.parametrize("n,k,m", SHAPES)
+@pytest.mark.parametrize("act", [ntp.NTP_ACT_NONE, ntp.NTP_ACT_RELU])
+def test_nn_fwd_fp32(n, k, m, act):
+    import torch
+    from gpu_util import dev_f32
+    say("nn_fwd", n, k, m, act)
+    A = gen.normal_features(n, k, seed=n + k)
+    W = gen.glorot_weight(k, m, seed=m)
+    H = torch.full((n, m), float("nan"), device="cuda:0")
+    ntp.ntp_nn_fwd(dev_f32(A), dev_f32(W), H, n, k, m, act)
+    torch.cuda.synchronize()
+    ref = ogcn.nn_fwd(A, W, act)
+    assert_close(H.cpu().numpy(), ref, _abs_scale(A, W), TOL_F32, "nn_fwd %s" % ((n, k, m),))
+
+
+@pytest.mark.parametrize("n,k,m", SHAPES)
+@pytest.mark.parametrize("act", [ntp.NTP_ACT_NONE, ntp.NTP_ACT_RELU])
+@pytest.mark.parametrize("need_dA", [True, False])
+def test_nn_bwd_fp32(n, k, m, act, need_dA):
+    import torch
+    from gpu_util import dev_f32
+    say("nn_bwd", n, k, m, act, need_dA)
+    A = gen.normal_features(n, k, seed=n + k)
+    W = gen.glorot_weight(k, m, seed=m)
+    dH = gen.normal_features(n, m, seed=7, stream=6)
+    Href = ogcn.nn_fwd(A, W, act).astype(np.float32)      # the H the backward call is given
+    dA_ref, dW_ref = ogcn.nn_bwd(A, W, Href, dH, act, need_dA=True)
+    dZ = dH * (Href > 0) if act == ntp.NTP_ACT_RELU else dH
+    dA = torch.full((n, k), float("nan"), device="cuda:0") if need_dA else None
+    dW = torch.full((k, m), float("nan"), device="cuda:0")
+    wsb = ntp.ntp_nn_bwd_workspace_bytes(n, k, m)
+    ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device="cuda:0")
+    ntp.ntp_nn_bwd(dev_f32(A), dev_f32(W), dev_f32(Href), dev_f32(dH), dA, dW, n, k, m, act, ntp.NTP_F32, ws, wsb)
+    torch.cuda.synchronize()
+    assert_close(dW.cpu().numpy(), dW_ref, _abs_scale(A.T, dZ), TOL_F32, "dW %s" % ((n, k, m),))
+    if need_dA:
+        assert_close(dA.cpu().numpy(), dA_ref, _abs_scale(dZ, W.T), TOL_F32, "dA %s" % ((n, k, m),))
+
+
+@pytest.mark.parametrize("n,k,m", [(300, 16, 8), (1000, 128, 256), (2049, 100, 48), (1500, 604, 128)])
+def test_nn_bf16(n, k, m):
+    import torch
+    from gpu_util import dev_bf16_bits, host_bf16, dev_f32
+    say("nn_bf16", n, k, m)
+    A = gen.normal_features(n, k, seed=n)
+    W = gen.glorot_weight(k, m, seed=m)
+    dH = gen.normal_features(n, m, seed=8, stream=6)
+    Ab, Av = dev_bf16_bits(A)
+    Wb, Wv = dev_bf16_bits(W)
+    Hb = torch.zeros((n, m), dtype=torch.int16, device="cuda:0")
+    ntp.ntp_nn_fwd(Ab, Wb, Hb, n, k, m, ntp.NTP_ACT_RELU, ntp.NTP_BF16)
+    torch.cuda.synchronize()
+    ref = oracle.round_bf16(ogcn.nn_fwd(Av, Wv, ntp.NTP_ACT_RELU)).astype(np.float64)
+    got = host_bf16(Hb)
+    assert_close(got, ref, _abs_scale(Av, Wv), TOL_BF16, "bf16 fwd")
+    # backward with the H the device produced
+    dHb, dHv = dev_bf16_bits(dH)
+    dAb = torch.zeros((n, k), dtype=torch.int16, device="cuda:0")
+    dW = torch.zeros((k, m), device="cuda:0")
+    wsb = ntp.ntp_nn_bwd_workspace_bytes(n, k, m)
+    ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device="cuda:0")
+    ntp.ntp_nn_bwd(Ab, Wb, Hb, dHb, dAb, dW, n, k, m, ntp.NTP_ACT_RELU, ntp.NTP_BF16, ws, wsb)
+    torch.cuda.synchronize()
+    dA_ref, dW_ref = ogcn.nn_bwd(Av, Wv, got, dHv, ntp.NTP_ACT_RELU)
+    dZ = dHv * (got > 0)
+    assert_close(dW.cpu().numpy(), dW_ref, _abs_scale(Av.T, dZ), TOL_F32 * 2, "bf16 dW")
+    assert_close(host_bf16(dAb), oracle.round_bf16(dA_ref).astype(np.float64), _abs_scale(dZ, Wv.T), TOL_BF16, "bf16 dA")
+
+
+def test_nn_deterministic():
+    import torch
+    from gpu_util import dev_f32
+    n, k, m = 20000, 128, 256
+    A, W = dev_f32(gen.normal_features(n, k, 1)), dev_f32(gen.glorot_weight(k, m, 1))
+    dH = dev_f32(gen.normal_features(n, m, 2))
+    H = torch.empty((n, m), device="cuda:0")
+    ntp.ntp_nn_fwd(A, W, H, n, k, m, ntp.NTP_ACT_RELU)
+    wsb = ntp.ntp_nn_bwd_workspace_bytes(n, k, m)
+    ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device="cuda:0")
+    outs = []
+    for _ in range(2):
+        dW = torch.empty((k, m), device="cuda:0")
+        ntp.ntp_nn_bwd(A, W, H, dH, None, dW, n, k, m, ntp.NTP_ACT_RELU, ntp.NTP_F32, ws, wsb)
+        torch.cuda.synchronize()
+        outs.append(dW.cpu().numpy())
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
