@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the aggregation hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic workload:
+  configs 1, 2 : one layer-wise GCN epoch (forward + backward) at full width: every
+                 forward aggregation, backward aggregation, transform and transform gradient;
+  configs 3, 4 : one worker's share of an epoch: the slice aggregations (forward and
+                 backward) at F_slice = width / 8 on the full graph, and the transforms on
+                 ceil(N / 8) vertices at full width.
+Prints ONE JSON line.  `value` is aggregation GEPS over the whole step: stored entries of
+A_hat (self loops included) x slice width, summed over the step's aggregation calls,
+divided by the step time (transforms included in the time).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def agg_bytes(n, nnz, f, elem=4):
+    """algorithmic bytes of one aggregation call: entries (index + weight), row pointers,
+    X read once, Y written once"""
+    return 8 * nnz + 8 * (n + 1) + 2 * n * f * elem
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--scale-down", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (the method's collectives are out of scope); "
+            "use --gpus 1.  value is the one GPU's throughput.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import ntp_inputs as gen
+    import paper_2412_20379_amd as ntp
+    from paper_2412_20379_amd.gcn import GcnEpoch
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(3)
+    dev = "cuda:0"
+    spec = gen.CONFIGS[args.config]
+    t0 = time.time()
+    n, src, dst = gen.make_graph(args.config, args.seed, args.scale_down)
+    t_gen = time.time() - t0
+    t0 = time.time()
+    g = ntp.ntp_graph_build(n, src, dst)
+    t_build = time.time() - t0
+    info = ntp.ntp_graph_info(g)
+    nnz = info["nnz"]
+    log("config %d: n=%d nnz=%d max_degree=%d (generated in %.1fs, graph build %.2fs)"
+        % (args.config, n, nnz, info["max_degree"], t_gen, t_build))
+
+    dims = spec.layers
+    L = len(dims) - 1
+    f32 = dict(dtype=torch.float32, device=dev)
+    events = []
+    edge_feats = 0            # stored entries x width, summed over aggregation calls of a step
+    flops_nn = 0
+
+    if args.config in (1, 2):
+        X = torch.from_numpy(gen.make_features(args.config, dims[0], args.seed, args.scale_down)).to(dev)
+        Ws = [torch.from_numpy(gen.glorot_weight(dims[i], dims[i + 1], args.seed, i)).to(dev) for i in range(L)]
+        labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)).to(dev)
+        ep = GcnEpoch(g, n, dims, order=args.order)
+
+        def step():
+            ep.run(X, Ws, labels)
+
+        def set_events(lst):
+            ep.events = lst
+        if args.order == "layerwise":
+            edge_feats = nnz * (sum(dims[:-1]) + sum(dims[1:-1]))
+        else:
+            edge_feats = nnz * dims[-1] * 2 * L
+        flops_nn = sum(2 * n * dims[i] * dims[i + 1] * (3 if i > 0 else 2) for i in range(L))
+        workload = "%s: %s GCN epoch fwd+bwd, %s, full width" % (spec.name, args.order, "->".join(map(str, dims)))
+    else:
+        # one worker's share (1 of 8): slice aggregations on the full graph, transforms on N/8 rows
+        W8 = spec.n_workers
+        slices = [-(-dims[l] // W8) for l in range(L)]          # ceil(width / 8) per layer input
+        n_share = -(-n // W8)
+        xs = [torch.from_numpy(gen.normal_features(n, s, args.seed + l)).to(dev) for l, s in enumerate(slices)]
+        ys = [torch.empty_like(x) for x in xs]
+        A = [torch.from_numpy(gen.normal_features(n_share, dims[l], args.seed + 10 + l)).to(dev) for l in range(L)]
+        Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev) for l in range(L)]
+        H = [torch.empty(n_share, dims[l + 1], **f32) for l in range(L)]
+        dH = [torch.from_numpy(gen.normal_features(n_share, dims[l + 1], args.seed + 20 + l)).to(dev) for l in range(L)]
+        dA = [torch.empty(n_share, dims[l], **f32) for l in range(L)]
+        dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
+        wsb = max(ntp.ntp_nn_bwd_workspace_bytes(n_share, dims[l], dims[l + 1]) for l in range(L))
+        ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device=dev)
+        holder = {"ev": None}
+
+        def timed(tag, fn, *a):
+            if holder["ev"] is None:
+                return fn(*a)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn(*a)
+            e1.record()
+            holder["ev"].append((tag, e0, e1))
+
+        def step():
+            st = torch.cuda.current_stream()
+            for l in range(L):
+                s = slices[l]
+                timed("agg_fwd f=%d" % s, ntp.ntp_aggregate_fwd, g, xs[l], ys[l], s, s, s, ntp.NTP_F32, st)
+                act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+                timed("nn_fwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_fwd, A[l], Ws[l], H[l], n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, st)
+            for l in range(L - 1, -1, -1):
+                act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+                timed("nn_bwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_bwd, A[l], Ws[l], H[l], dH[l], dA[l] if l > 0 else None, dW[l],
+                      n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, ws, wsb, st)
+                if l > 0:
+                    s = slices[l]
+                    timed("agg_bwd f=%d" % s, ntp.ntp_aggregate_bwd, g, ys[l], xs[l], s, s, s, ntp.NTP_F32, st)
+
+        def set_events(lst):
+            holder["ev"] = lst
+        edge_feats = nnz * (sum(slices) + sum(slices[1:]))
+        flops_nn = sum(2 * n_share * dims[i] * dims[i + 1] * (3 if i > 0 else 2) for i in range(L))
+        workload = ("%s: one worker's share (1/%d) of a %s epoch: slice aggregations F=%s fwd+bwd on the full graph, "
+                    "transforms on %d rows" % (spec.name, W8, "->".join(map(str, dims)), slices, n_share))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    set_events(events)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    set_events(None)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    geps = edge_feats / (ms_per_step * 1e-3) / 1e9
+
+    # per-call durations from the HIP events recorded inside the timed region
+    per = {}
+    for tag, e0, e1 in events:
+        per.setdefault(tag, []).append(e0.elapsed_time(e1))
+    calls = {k: dict(n=len(v), avg_ms=float(np.mean(v)), min_ms=float(np.min(v))) for k, v in per.items()}
+    agg_ms = sum(np.sum(v) for k, v in per.items() if k.startswith("agg")) / args.steps
+    nn_ms = sum(np.sum(v) for k, v in per.items() if k.startswith("nn")) / args.steps
+
+    # roofline of the dominant aggregation kernel: the width with the largest share of step time
+    agg_tags = [k for k in per if k.startswith("agg")]
+    by_width = {}
+    for k in agg_tags:
+        f = int(k.split("f=")[1])
+        by_width.setdefault(f, []).extend(per[k])
+    fdom = max(by_width, key=lambda f: np.sum(by_width[f]))
+    dur_ms = float(np.mean(by_width[fdom]))
+    balg = agg_bytes(n, nnz, fdom)
+    achieved = balg / (dur_ms * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get("cfg%d_f%d" % (args.config, fdom))
+        except Exception:
+            traffic = None
+    roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, fp32)" % fdom, achieved=achieved, peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=traffic,
+                    algorithmic_bytes_per_launch=balg, avg_launch_ms=dur_ms,
+                    geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
+    nn_tflops = flops_nn / (nn_ms * 1e-3) / 1e12 if nn_ms > 0 else None
+    roofline_nn = dict(bound="mfma", kernel="gemm_kernel (fp32 MFMA, all transform calls of a step)",
+                       achieved=nn_tflops, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                       frac=(nn_tflops / FP32_MFMA_PEAK_TFLOPS) if nn_tflops else None, traffic=None)
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.time()
+        og = oracle.build_graph(n, src, dst)
+        fo = fdom
+        xo = gen.normal_features(n, fo, args.seed)
+        rows = None
+        sample = "one forward aggregation of the whole graph at F_slice=%d" % fo
+        if og.nnz * fo > 3e9:      # bound the CPU work: a uniform row sample
+            k = max(1000, int(n * 3e9 / (og.nnz * fo)))
+            rows = np.sort(gen.stream_rng(args.seed, 99).choice(n, size=min(k, n), replace=False)).astype(np.int64)
+            sample = "forward aggregation of %d uniformly sampled rows at F_slice=%d" % (rows.size, fo)
+        best = None
+        done = 0
+        for _ in range(3):
+            t1 = time.perf_counter()
+            oracle.aggregate_fwd(og, xo, rows=rows)
+            dt = time.perf_counter() - t1
+            best = dt if best is None else min(best, dt)
+        if rows is None:
+            done = og.nnz * fo
+        else:
+            done = int((og.csr.rowptr[rows + 1] - og.csr.rowptr[rows]).sum()) * fo
+        cpu_baseline = dict(value=done / best / 1e9, unit="GEPS", cores=oracle.num_threads(), kind="oracle",
+                            sample=sample + ", fp64, best of 3 (%.3fs)" % best)
+        log("oracle baseline: %.2f GEPS on %d threads (%.1fs incl. graph build)" % (cpu_baseline["value"], cpu_baseline["cores"], time.time() - t0))
+
+    out = {
+        "metric": "aggregation GEPS (stored entries x F_slice / s) over the step; epoch ms in ms_per_step",
+        "value": geps, "unit": "GEPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": workload, "n_vertices": n, "nnz": nnz, "max_degree": info["max_degree"],
+                   "seed": args.seed, "scale_down": args.scale_down},
+        "roofline": roofline, "roofline_nn": roofline_nn, "cpu_baseline": cpu_baseline,
+        "agg_ms_per_step": float(agg_ms), "nn_ms_per_step": float(nn_ms),
+        "agg_geps_calls_only": edge_feats / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else None,
+        "calls": calls, "graph_build_s": t_build,
+    }
+    print(json.dumps(out), flush=True)
+    g.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -18,4 +18,4 @@ from .generators import (  # noqa: F401
     to_bf16_bits,
     bf16_bits_to_f32,
 )
-from .configs import CONFIGS, make_graph, WorkloadSpec  # noqa: F401
+from .configs import CONFIGS, make_graph, make_features, WorkloadSpec  # noqa: F401

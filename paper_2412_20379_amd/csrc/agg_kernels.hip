@@ -43,6 +43,7 @@ __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
 
 // ---- element access: VEC consecutive elements <-> VEC floats -------------------------
 template <int VEC> struct IoF32 {
+    static_assert(VEC == 1 || VEC == 2 || VEC == 4, "fp32 vectors of 1, 2 or 4 elements");
     using elem = float;
     static constexpr int kVec = VEC;
     static __device__ __forceinline__ void load(const float* p, float (&v)[VEC]) {
@@ -57,7 +58,19 @@ template <int VEC> struct IoF32 {
     }
 };
 
+// VEC fp32 partial sums to scratch (VEC may be 8 for bf16 features)
+template <int VEC>
+__device__ __forceinline__ void store_partial(float* p, const float (&v)[VEC]) {
+    if constexpr (VEC == 8) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+        IoF32<VEC>::store(p, v);
+    }
+}
+
 template <int VEC> struct IoBf16 {
+    static_assert(VEC == 1 || VEC == 2 || VEC == 4 || VEC == 8, "bf16 vectors of 1, 2, 4 or 8 elements");
     using elem = unsigned short;
     static constexpr int kVec = VEC;
     static __device__ __forceinline__ void unpack(unsigned w, float& lo, float& hi) {
@@ -239,7 +252,7 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
         if (mode == MODE_SEGMENT) {
 #pragma unroll
             for (int j = 0; j < NACC; ++j)
-                if (act[j]) IoF32<VEC>::store(pout + j * L * VEC, acc[j]);
+                if (act[j]) store_partial<VEC>(pout + j * L * VEC, acc[j]);
         } else {
             T* y = static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase;
 #pragma unroll

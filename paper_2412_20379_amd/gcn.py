@@ -28,14 +28,35 @@ class GcnEpoch:
         self.dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
         wmax = max(dims)
         self.tmp = [torch.empty(n, wmax, **f32) for _ in range(2)]
+        self.logits_buf = torch.empty(n, dims[-1], **f32) if order == "decoupled" else None
         ws = max(ntp.ntp_nn_bwd_workspace_bytes(n, dims[l], dims[l + 1]) for l in range(L))
         self.ws_bytes = ws
         self.ws = torch.empty(max(ws, 4), dtype=torch.uint8, device=device)
         self.copy_stream = torch.cuda.Stream(device=device) if chunked else None
         self.loss = None
         self.logits = None
+        self.events = None      # set to a list to collect (tag, start, end) HIP events per library call
+
+    def _timed(self, tag, fn, *a):
+        if self.events is None:
+            return fn(*a)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn(*a)
+        e1.record()
+        self.events.append((tag, e0, e1))
+
+    def _nn_fwd(self, *a):
+        self._timed("nn_fwd %dx%d" % (a[4], a[5]), ntp.ntp_nn_fwd, *a)
+
+    def _nn_bwd(self, *a):
+        self._timed("nn_bwd %dx%d%s" % (a[7], a[8], "" if a[4] is None else " +dA"), ntp.ntp_nn_bwd, *a)
 
     def _agg(self, direction, src, dst, f):
+        self._timed("agg_%s f=%d" % ("fwd" if direction == ntp.NTP_FWD else "bwd", f), self._agg_call, direction, src, dst, f)
+
+    def _agg_call(self, direction, src, dst, f):
         st = torch.cuda.current_stream()
         if self.chunked:
             ntp.ntp_chunked_aggregate(self.g, direction, src, dst, f, f, f, ntp.NTP_F32, st, self.copy_stream)
@@ -66,15 +87,15 @@ class GcnEpoch:
         for l in range(L):
             self._agg(ntp.NTP_FWD, H, self.aggs[l], d[l])
             act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
-            ntp.ntp_nn_fwd(self.aggs[l], Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
+            self._nn_fwd(self.aggs[l], Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
             H = self.hid[l]
         self.logits = H
         dH = self._loss_grad(H, labels)
         for l in range(L - 1, -1, -1):
             act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
             dA = self._view(0, d[l]) if l > 0 else None
-            ntp.ntp_nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
-                           ntp.NTP_F32, self.ws, self.ws_bytes, st)
+            self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
+                         ntp.NTP_F32, self.ws, self.ws_bytes, st)
             if l > 0:
                 dH = self._view(1, d[l])
                 self._agg(ntp.NTP_BWD, dA, dH, d[l])
@@ -88,13 +109,13 @@ class GcnEpoch:
         H = X
         for l in range(L):
             act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
-            ntp.ntp_nn_fwd(H, Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
+            self._nn_fwd(H, Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
             H = self.hid[l]
             ins.append(H)
         c = d[-1]
         Z = H
         for k in range(L):          # L rounds of aggregation at the output width, no intermediates kept
-            out = self._view(k % 2, c)
+            out = self._view(k % 2, c) if k < L - 1 else self.logits_buf
             self._agg(ntp.NTP_FWD, Z, out, c)
             Z = out
         self.logits = Z
@@ -110,7 +131,7 @@ class GcnEpoch:
             if l > 0:
                 # the two scratch views are free again except the one holding dH
                 dA = self._view(0 if dH.data_ptr() != self.tmp[0].data_ptr() else 1, d[l])
-            ntp.ntp_nn_bwd(ins[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
-                           ntp.NTP_F32, self.ws, self.ws_bytes, st)
+            self._nn_bwd(ins[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
+                         ntp.NTP_F32, self.ws, self.ws_bytes, st)
             dH = dA
         return self.loss

@@ -36,18 +36,42 @@ def _run(cfg, order, scale=1, chunked=False, directed=False):
     loss = ep.run(dev_f32(X), [dev_f32(w) for w in Ws], torch.from_numpy(labels.astype(np.int64)).to("cuda:0"))
     torch.cuda.synchronize()
     fn = ogcn.epoch_layerwise if order == "layerwise" else ogcn.epoch_decoupled
-    ref = fn(og, X, Ws, labels)
+    # The ReLU keeps or zeroes a pre-activation by its sign.  Where the pre-activation is
+    # zero to rounding, fp32 and fp64 may decide differently, and one such entry on a hub
+    # vertex moves dW by far more than rounding.  Both sides therefore take the device's
+    # (fp32) decisions; the test checks that these differ from the oracle's own fp64
+    # decisions only on entries that are zero to rounding.
+    own = fn(og, X, Ws, labels)
+    masks = [h.cpu().numpy() > 0 for h in ep.hid[:-1]]
+    for l, mk in enumerate(masks):
+        flips = mk != (own["hidden"][l] > 0)
+        frac = flips.mean()
+        say("  layer %d: %d ReLU decisions differ (%.1e of all)" % (l, int(flips.sum()), frac))
+        assert frac <= 1e-4
+    ref = fn(og, X, Ws, labels, relu_masks=masks)
+    for l, mk in enumerate(masks):
+        flips = mk != (own["hidden"][l] > 0)
+        if flips.any():      # a differing decision is only allowed on a value that is ~0
+            near0 = np.maximum(np.abs(ref["hidden"][l][flips]), np.abs(own["hidden"][l][flips])).max()
+            assert near0 <= 1e-4 * np.abs(own["hidden"][l]).max()
     say(cfg, order, "loss", float(loss), "oracle", ref["loss"])
     assert abs(float(loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
     Z = ep.logits.cpu().numpy().astype(np.float64)
     zs = np.abs(ref["logits"]).max()
     assert np.abs(Z - ref["logits"]).max() <= 2e-5 * zs
+    # dW_l sums n products of mixed sign: its rounding error scales with the sum of
+    # absolute products |A_l|^T |dZ_l|, not with the (much smaller) result.  An epoch
+    # chains about ten fp32 calls, so the bound is 5x the per-call 1e-5.
+    L = len(Ws)
     for l, dW in enumerate(ep.dW):
         got = dW.cpu().numpy().astype(np.float64)
-        scale_l = np.abs(ref["dW"][l]).max()
-        err = np.abs(got - ref["dW"][l]).max() / scale_l
-        say("  dW[%d] normwise error %.2e" % (l, err))
+        dZ = ref["dH"][l] * (ref["hidden"][l] > 0) if l < L - 1 else ref["dH"][l]
+        scale_l = np.abs(ref["nn_in"][l]).T @ np.abs(dZ)
+        err = (np.abs(got - ref["dW"][l]) / scale_l).max()
+        nerr = np.abs(got - ref["dW"][l]).max() / np.abs(ref["dW"][l]).max()
+        say("  dW[%d] error vs sum of |terms| %.2e, vs max|dW| %.2e" % (l, err, nerr))
         assert err <= 5e-5, "dW[%d]" % l
+        assert nerr <= 2e-3, "dW[%d] normwise" % l
     g.close()
 
 

@@ -264,6 +264,25 @@ def test_p7_identity_adjacency_reduces_to_mlp():
         np.testing.assert_allclose(x, y, rtol=1e-12, atol=1e-15)
 
 
+@pytest.mark.parametrize("epoch", ["layerwise", "decoupled"])
+def test_p7_relu_masks_argument(epoch):
+    """passing the epoch its own ReLU decisions changes nothing; a flipped decision on one
+    entry changes exactly what zeroing / keeping that entry implies"""
+    fn = gcn.epoch_layerwise if epoch == "layerwise" else gcn.epoch_decoupled
+    g, X, Ws, labels = _tiny_model(16)
+    a = fn(g, X, Ws, labels)
+    masks = [h > 0 for h in a["hidden"][:-1]]
+    b = fn(g, X, Ws, labels, relu_masks=masks)
+    assert a["loss"] == b["loss"]
+    for x, y in zip(a["dW"], b["dW"]):
+        np.testing.assert_array_equal(x, y)
+    masks[0][:] = True                          # identity activation on layer 0
+    c = fn(g, X, Ws, labels, relu_masks=masks)
+    pre0 = (c["nn_in"][0] @ Ws[0])
+    np.testing.assert_allclose(c["hidden"][0], pre0, rtol=1e-14)
+    assert c["loss"] != a["loss"]
+
+
 def test_p7_decoupled_is_power_of_ahat():
     g, X, Ws, labels = _tiny_model(14)
     out = gcn.epoch_decoupled(g, X, Ws, labels)
