@@ -46,6 +46,12 @@ def main():
     ap.add_argument("--scale-down", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled"])
+    ap.add_argument("--mode", default="step", choices=["step", "agg"],
+                    help="agg: time only aggregation calls at --widths (kernel tuning / profiling)")
+    ap.add_argument("--widths", default="", help="comma-separated slice widths for --mode agg")
+    ap.add_argument("--agg-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (the method's collectives are out of scope); "
@@ -73,6 +79,54 @@ def main():
     nnz = info["nnz"]
     log("config %d: n=%d nnz=%d max_degree=%d (generated in %.1fs, graph build %.2fs)"
         % (args.config, n, nnz, info["max_degree"], t_gen, t_build))
+
+    if args.copy_probe:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        b.copy_(a)
+        e0.record()
+        for _ in range(5):
+            b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        log("copy probe: 1 GiB read + 1 GiB written per copy, %.1f GB/s" % (5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9))
+        del a, b
+
+    if args.mode == "agg":
+        widths = [int(w) for w in args.widths.split(",")] if args.widths else list(spec.agg_slices)
+        res = []
+        for f in widths:
+            x = torch.from_numpy(gen.normal_features(n, f, args.seed)).to(dev)
+            code, elem = ntp.NTP_F32, 4
+            if args.agg_dtype == "bf16":
+                x = torch.from_numpy(gen.to_bf16_bits(x.cpu().numpy()).view(np.int16)).to(dev)
+                code, elem = ntp.NTP_BF16, 2
+            y = torch.empty_like(x)
+            st = torch.cuda.current_stream()
+            for direction, fn in (("fwd", ntp.ntp_aggregate_fwd), ("bwd", ntp.ntp_aggregate_bwd)):
+                for _ in range(args.warmup):
+                    fn(g, x, y, f, f, f, code, st)
+                evs = []
+                for _ in range(args.steps):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    fn(g, x, y, f, f, f, code, st)
+                    e1.record()
+                    evs.append((e0, e1))
+                torch.cuda.synchronize()
+                ms = np.array([a.elapsed_time(b) for a, b in evs])
+                balg = agg_bytes(n, nnz, f, elem)
+                r = dict(width=f, direction=direction, dtype=args.agg_dtype, avg_ms=float(ms.mean()), min_ms=float(ms.min()),
+                         geps=nnz * f / (ms.mean() * 1e-3) / 1e9, alg_gbs=balg / (ms.mean() * 1e-3) / 1e9,
+                         frac_hbm=balg / (ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                log("agg %s f=%d %s: %.3f ms  %.0f GEPS  %.0f GB/s algorithmic (%.1f%% of 8 TB/s)"
+                    % (direction, f, args.agg_dtype, r["avg_ms"], r["geps"], r["alg_gbs"], 100 * r["frac_hbm"]))
+                res.append(r)
+        print(json.dumps({"mode": "agg", "config": args.config, "n_vertices": n, "nnz": nnz,
+                          "max_degree": info["max_degree"], "results": res}), flush=True)
+        g.close()
+        return
 
     dims = spec.layers
     L = len(dims) - 1

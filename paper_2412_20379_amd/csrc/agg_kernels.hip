@@ -98,13 +98,20 @@ template <int VEC> struct IoBf16 {
 // L lanes per feature row, NACC vectors per lane (columns l*VEC + j*L*VEC), 4 wavefronts
 // per block, every wavefront an independent unit of work.  blockIdx.y walks column passes
 // when the slice is wider than L*VEC*NACC.
+//
+// Gathers are issued U at a time with no branch between them, so that U neighbour rows
+// are in flight per lane before the first multiply-add waits.  To keep the loads free of
+// branches every lane always loads from a valid address: a lane whose columns lie beyond
+// the slice reads column 0, an entry that does not exist reads the row's own vertex, and
+// what such a load returns is replaced by zero before it is used.
 template <class IO, int L, int NACC>
 __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
     using T = typename IO::elem;
     constexpr int VEC = IO::kVec;
     constexpr int R = 64 / L;
     constexpr int PASS_W = L * VEC * NACC;
-    constexpr int UNR = L < 8 ? L : 8;      // gathers kept in flight per lane
+    constexpr int UMAX = NACC == 1 ? 8 : (NACC == 2 ? 4 : 2);
+    constexpr int U = L < UMAX ? L : UMAX;      // gathers kept in flight per lane
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
@@ -118,42 +125,52 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
     const int colbase = (int)blockIdx.y * PASS_W + l * VEC;
 
     bool act[NACC];
+    int coff[NACC];            // column offset read by this lane (0 when the column is outside the slice)
 #pragma unroll
-    for (int j = 0; j < NACC; ++j) act[j] = colbase + j * L * VEC < a.f;
+    for (int j = 0; j < NACC; ++j) {
+        act[j] = colbase + j * L * VEC < a.f;
+        coff[j] = act[j] ? colbase + j * L * VEC : 0;
+    }
 
-    const T* __restrict__ X = static_cast<const T*>(a.X) + colbase;
+    const T* __restrict__ X = static_cast<const T*>(a.X);
+    const int64_t ldx = a.ldx;
     float acc[NACC][VEC];
 #pragma unroll
     for (int j = 0; j < NACC; ++j)
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[j][i] = 0.f;
 
-    // acc += w * X[c, columns of this lane]
-    auto gather = [&](int c, float w) {
-        const T* xr = X + (int64_t)c * a.ldx;
+    // acc += sum over u < U of w[u] * X[c[u], columns of this lane]; all loads first
+    auto gather_u = [&](const int (&c)[U], const float (&w)[U]) {
+        float x[U][NACC][VEC];
 #pragma unroll
-        for (int j = 0; j < NACC; ++j) {
-            if (act[j]) {
-                float x[VEC];
-                IO::load(xr + j * L * VEC, x);
+        for (int u = 0; u < U; ++u) {
+            const T* xr = X + (int64_t)c[u] * ldx;
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[j][i] = fmaf(w, x[i], acc[j][i]);
-            }
+            for (int j = 0; j < NACC; ++j) IO::load(xr + coff[j], x[u][j]);
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < NACC; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[j][i] = fmaf(w[u], x[u][j][i], acc[j][i]);
     };
-    // same, but an entry that is not there contributes exactly nothing (c is still a
-    // valid row so the load stays in bounds)
-    auto gather_if = [&](bool on, int c, float w) {
-        const T* xr = X + (int64_t)c * a.ldx;
+    // same with entries that may not exist: their loaded values count as zero
+    auto gather_u_if = [&](const bool (&on)[U], const int (&c)[U], const float (&w)[U]) {
+        float x[U][NACC][VEC];
 #pragma unroll
-        for (int j = 0; j < NACC; ++j) {
-            if (act[j]) {
-                float x[VEC];
-                IO::load(xr + j * L * VEC, x);
+        for (int u = 0; u < U; ++u) {
+            const T* xr = X + (int64_t)c[u] * ldx;
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[j][i] = on ? fmaf(w, x[i], acc[j][i]) : acc[j][i];
-            }
+            for (int j = 0; j < NACC; ++j) IO::load(xr + coff[j], x[u][j]);
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < NACC; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[j][i] = fmaf(on[u] ? w[u] : 0.f, on[u] ? x[u][j][i] : 0.f, acc[j][i]);
     };
 
     if (mode == MODE_GROUP_PER_ROW) {
@@ -161,7 +178,7 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
         const int idx = item0 * R + g;
         const bool valid = idx < a.item_count[grp];
         int row = 0;
-        int64_t beg = 0;
+        int64_t beg = a.e_base;
         int d = 0;
         if (valid) {
             row = a.rows[a.item_off[grp] + idx];
@@ -175,11 +192,18 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
             float w = 0.f;
             if (k0 + l < d) { c = __builtin_nontemporal_load(ci + k0 + l); w = __builtin_nontemporal_load(vv + k0 + l); }
 #pragma unroll
-            for (int j = 0; j < L; ++j) {
-                if (__ballot(k0 + j < d) == 0) break;
-                const int cj = bperm_i(g * L + j, c);
-                const float wj = bperm_f(g * L + j, w);
-                if (k0 + j < d) gather(cj, wj);
+            for (int j0 = 0; j0 < L; j0 += U) {
+                if (__ballot(k0 + j0 < d) == 0) break;
+                int cj[U];
+                float wj[U];
+                bool on[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    cj[u] = bperm_i(g * L + j0 + u, c);      // lanes past the row's end hold (row, 0)
+                    wj[u] = bperm_f(g * L + j0 + u, w);
+                    on[u] = k0 + j0 + u < d;
+                }
+                gather_u_if(on, cj, wj);
             }
         }
         if (valid) {
@@ -220,20 +244,36 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
         float wn = 0.f;
         if (base + 64 + lane < cnt) { cn = __builtin_nontemporal_load(ci + base + 64 + lane); wn = __builtin_nontemporal_load(vv + base + 64 + lane); }
         if (n == 64) {
-#pragma unroll UNR
-            for (int j = 0; j < L; ++j) {
-                int cj;
-                float wj;
-                if constexpr (R == 1) { cj = __builtin_amdgcn_readlane(c, j); wj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), j)); }
-                else { cj = bperm_i(j * R + g, c); wj = bperm_f(j * R + g, w); }
-                gather(cj, wj);
+            // group g takes entries g, g + R, ...: L entries per group, U at a time
+#pragma unroll
+            for (int j0 = 0; j0 < L; j0 += U) {
+                int cj[U];
+                float wj[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (R == 1) {
+                        cj[u] = __builtin_amdgcn_readlane(c, j0 + u);
+                        wj[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), j0 + u));
+                    } else {
+                        cj[u] = bperm_i((j0 + u) * R + g, c);
+                        wj[u] = bperm_f((j0 + u) * R + g, w);
+                    }
+                }
+                gather_u(cj, wj);
             }
         } else {
-            for (int j = 0; j * R < n; ++j) {
-                const int e = j * R + g;
-                const int cj = bperm_i(e, c);
-                const float wj = bperm_f(e, w);
-                gather_if(e < n, cj, wj);
+            for (int j0 = 0; j0 * R < n; j0 += U) {
+                int cj[U];
+                float wj[U];
+                bool on[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = (j0 + u) * R + g;       // e < 64 always (j0 + u < L)
+                    cj[u] = bperm_i(e & 63, c);            // lanes >= n hold (row, 0)
+                    wj[u] = bperm_f(e & 63, w);
+                    on[u] = e < n;
+                }
+                gather_u_if(on, cj, wj);
             }
         }
         c = cn;
@@ -262,20 +302,38 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
     }
 }
 
-// ---- second pass for split rows: Y[row,:] = sum of its partial-sum slots, in order ----
+// ---- second pass for split rows: Y[row,:] = sum of its partial-sum slots ---------------
+// One block per split row.  Wavefront w adds the slots w, w+4, w+8, ... in ascending
+// order (independent loads, four in flight), the four sums are combined through LDS as
+// (s0 + s1) + (s2 + s3): a fixed order, so the result is deterministic.
 template <class T>
 __global__ void __launch_bounds__(256) reduce_kernel(const ReduceArgs a) {
+    __shared__ float part[4][64];
     const int lane = threadIdx.x & 63;
-    const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (item >= a.n_items) return;
-    const ReduceItem it = a.items[item];
-    for (int col = lane; col < a.f; col += 64) {
-        const float* p = a.partial + (int64_t)it.first_slot * a.f + col;
+    const int w = threadIdx.x >> 6;
+    const ReduceItem it = a.items[blockIdx.x];
+    for (int col0 = 0; col0 < a.f; col0 += 64) {
+        const int col = col0 + lane;
         float s = 0.f;
-        for (int k = 0; k < it.n_slots; ++k) s += p[(int64_t)k * a.f];
-        T* y = static_cast<T*>(a.Y) + (int64_t)it.row * a.ldy + col;
-        if constexpr (sizeof(T) == 4) *y = s;
-        else *y = (T)f32_to_bf16_rne(s);
+        if (col < a.f) {
+            const float* p = a.partial + (int64_t)it.first_slot * a.f + col;
+            int k = w;
+            for (; k + 12 < it.n_slots; k += 16) {
+                const float t0 = p[(int64_t)k * a.f], t1 = p[(int64_t)(k + 4) * a.f];
+                const float t2 = p[(int64_t)(k + 8) * a.f], t3 = p[(int64_t)(k + 12) * a.f];
+                s += t0; s += t1; s += t2; s += t3;
+            }
+            for (; k < it.n_slots; k += 4) s += p[(int64_t)k * a.f];
+        }
+        part[w][lane] = s;
+        __syncthreads();
+        if (w == 0 && col < a.f) {
+            const float r = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+            T* y = static_cast<T*>(a.Y) + (int64_t)it.row * a.ldy + col;
+            if constexpr (sizeof(T) == 4) *y = r;
+            else *y = (T)f32_to_bf16_rne(r);
+        }
+        __syncthreads();
     }
 }
 
@@ -357,7 +415,7 @@ int launch_aggregate(const AggArgs& a, int dtype, void* stream) {
 int launch_reduce(const ReduceArgs& a, int dtype, void* stream) {
     if (a.n_items <= 0) return NTP_OK;
     hipStream_t st = (hipStream_t)stream;
-    dim3 grid((unsigned)((a.n_items + 3) / 4));
+    dim3 grid((unsigned)a.n_items);
     if (dtype == NTP_F32) hipLaunchKernelGGL(reduce_kernel<float>, grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL(reduce_kernel<unsigned short>, grid, dim3(256), 0, st, a);
     const hipError_t e = hipGetLastError();

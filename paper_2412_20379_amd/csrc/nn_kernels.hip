@@ -217,14 +217,29 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(const GemmArgs g) {
         }
 }
 
-// out[i] = sum over s of part[s * stride + i], s ascending
+// out[i] = sum over the splits of part[s * stride + i].  A block owns 64 consecutive
+// elements; wavefront w adds the splits w, w+4, ... in ascending order and the four sums
+// are combined as (s0 + s1) + (s2 + s3): fixed order, deterministic.
 __global__ void __launch_bounds__(256) sum_splits_kernel(const float* __restrict__ part, float* __restrict__ out,
                                                          int64_t count, int64_t stride, int n_splits) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= count) return;
+    __shared__ float tmp[4][64];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
     float s = 0.f;
-    for (int k = 0; k < n_splits; ++k) s += part[(int64_t)k * stride + i];
-    out[i] = s;
+    if (i < count) {
+        const float* p = part + i;
+        int k = w;
+        for (; k + 12 < n_splits; k += 16) {
+            const float t0 = p[(int64_t)k * stride], t1 = p[(int64_t)(k + 4) * stride];
+            const float t2 = p[(int64_t)(k + 8) * stride], t3 = p[(int64_t)(k + 12) * stride];
+            s += t0; s += t1; s += t2; s += t3;
+        }
+        for (; k < n_splits; k += 4) s += p[(int64_t)k * stride];
+    }
+    tmp[w][lane] = s;
+    __syncthreads();
+    if (w == 0 && i < count) out[i] = (tmp[0][lane] + tmp[1][lane]) + (tmp[2][lane] + tmp[3][lane]);
 }
 
 template <class TA, class TB, class TC, bool AK, bool BKC, bool MA, bool MB>
@@ -298,7 +313,7 @@ int nn_bwd_t(const void* A, const void* W, const void* H, const void* dH, void* 
     if (rc != NTP_OK) return rc;
     if (S > 1) {
         const int64_t count = k * m;
-        hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+        hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st,
                            (const float*)ws, dW, count, count, S);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) { set_error("split reduction launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
@@ -326,7 +341,7 @@ int launch_nn_bwd(const void* A, const void* W, const void* H, const void* dH, v
     hipStream_t st = (hipStream_t)stream;
     if (n == 0) {   // nothing to contract over: dW = 0 (a fill kernel, not a memset node)
         const int64_t count = k * m;
-        hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+        hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st,
                            (const float*)nullptr, dW, count, count, 0);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) { set_error("fill launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
