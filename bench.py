@@ -235,7 +235,7 @@ def main():
     tfile = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tfile):
         try:
-            traffic = json.load(open(tfile)).get("cfg%d_f%d" % (args.config, fdom))
+            traffic = json.load(open(tfile)).get("cfg%d_f%d" % (args.config, fdom)) if args.scale_down == 1 else None
         except Exception:
             traffic = None
     roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, fp32)" % fdom, achieved=achieved, peak=HBM_PEAK_GBS,

@@ -110,8 +110,11 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
     constexpr int VEC = IO::kVec;
     constexpr int R = 64 / L;
     constexpr int PASS_W = L * VEC * NACC;
-    constexpr int UMAX = NACC == 1 ? 8 : (NACC == 2 ? 4 : 2);
-    constexpr int U = L < UMAX ? L : UMAX;      // gathers kept in flight per lane
+    // gathers kept in flight per lane.  Measured on MI355X: 1, 2, 4 and 8 give the same
+    // throughput (the gather rate is set by the cache hierarchy, not by latency hiding in
+    // the wavefront), so a small count is used to keep the register footprint low.
+    constexpr int UMAX = NACC == 4 ? 2 : 4;
+    constexpr int U = L < UMAX ? L : UMAX;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
