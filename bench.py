@@ -46,8 +46,10 @@ def main():
     ap.add_argument("--scale-down", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled"])
-    ap.add_argument("--mode", default="step", choices=["step", "agg"],
-                    help="agg: time only aggregation calls at --widths (kernel tuning / profiling)")
+    ap.add_argument("--mode", default="step", choices=["step", "agg", "chunk"],
+                    help="agg: time only aggregation calls at --widths (kernel tuning / profiling); "
+                         "chunk: chunk-streamed vs in-memory aggregation")
+    ap.add_argument("--chunk-edges", type=int, default=0, help="entries per chunk for --mode chunk (default nnz/8)")
     ap.add_argument("--widths", default="", help="comma-separated slice widths for --mode agg")
     ap.add_argument("--agg-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--copy-probe", action="store_true",
@@ -92,6 +94,76 @@ def main():
         torch.cuda.synchronize()
         log("copy probe: 1 GiB read + 1 GiB written per copy, %.1f GB/s" % (5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9))
         del a, b
+
+    if args.mode == "chunk":
+        # Section 4.2.1 schedule: in-memory call vs chunked call with every chunk resident, with
+        # about half of the chunks resident (budget), and with every chunk streamed from pinned memory
+        f = int(args.widths.split(",")[0]) if args.widths else spec.agg_slices[0]
+        ce = args.chunk_edges or max(1024, nnz // 8)
+        x = torch.from_numpy(gen.normal_features(n, f, args.seed)).to(dev)
+        y = torch.empty_like(x)
+        cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+        # PCIe probe: pinned host -> device copy of 256 MiB
+        hp = torch.empty(1 << 26, dtype=torch.float32).pin_memory()
+        dp = torch.empty(1 << 26, dtype=torch.float32, device=dev)
+        dp.copy_(hp, non_blocking=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(4):
+            dp.copy_(hp, non_blocking=True)
+        torch.cuda.synchronize()
+        pcie_gbs = 4 * (1 << 28) / (time.perf_counter() - t0) / 1e9
+        del hp, dp
+
+        def timeit(graph, chunked):
+            def call():
+                if chunked:
+                    ntp.ntp_chunked_aggregate(graph, ntp.NTP_FWD, x, y, f, f, f, ntp.NTP_F32, cs, xs)
+                else:
+                    ntp.ntp_aggregate_fwd(graph, x, y, f, f, f, ntp.NTP_F32, cs)
+            for _ in range(args.warmup):
+                call()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                call()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / args.steps
+
+        t_inmem = timeit(g, False)
+        ref = y.clone()
+        out = {"mode": "chunk", "config": args.config, "n_vertices": n, "nnz": nnz, "width": f, "chunk_edges": ce,
+               "pcie_h2d_gbs": pcie_gbs, "t_inmem_ms": t_inmem}
+        g_all = ntp.ntp_graph_build(n, src, dst, chunk_edges=ce)
+        out["t_chunked_all_resident_ms"] = timeit(g_all, True)
+        assert torch.equal(y, ref)
+        g_all.close()
+        total_bytes = nnz * 8 + n * 12
+        g_half = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=int(total_bytes * 0.62), chunk_edges=ce)
+        chh = ntp.ntp_graph_chunks(g_half)
+        streamed = ~chh["resident"].astype(bool)
+        b_pcie_half = int(((chh["entry_end"] - chh["entry_begin"])[streamed] * 8 + (chh["row_end"] - chh["row_begin"])[streamed] * 12).sum())
+        out["t_warm_ms"] = timeit(g_half, True)
+        assert torch.equal(y, ref)
+        out["warm_resident_chunks"] = "%d of %d" % (int(chh["resident"].sum()), len(streamed))
+        out["warm_pcie_bytes"] = b_pcie_half
+        out["warm_floor_ms"] = max(t_inmem, b_pcie_half / (pcie_gbs * 1e9) * 1e3)
+        g_half.close()
+        g_cold = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | ntp.NTP_FORCE_STREAM, chunk_edges=ce)
+        chc = ntp.ntp_graph_chunks(g_cold)
+        b_pcie = int(((chc["entry_end"] - chc["entry_begin"]) * 8 + (chc["row_end"] - chc["row_begin"]) * 12).sum())
+        out["t_cold_ms"] = timeit(g_cold, True)
+        assert torch.equal(y, ref)
+        out["cold_pcie_bytes"] = b_pcie
+        out["cold_floor_ms"] = max(t_inmem, b_pcie / (pcie_gbs * 1e9) * 1e3)
+        out["cold_over_floor"] = out["t_cold_ms"] / out["cold_floor_ms"]
+        out["warm_over_floor"] = out["t_warm_ms"] / out["warm_floor_ms"]
+        out["all_resident_over_inmem"] = out["t_chunked_all_resident_ms"] / t_inmem
+        g_cold.close()
+        log(json.dumps(out, indent=1))
+        print(json.dumps(out), flush=True)
+        g.close()
+        return
 
     if args.mode == "agg":
         widths = [int(w) for w in args.widths.split(",")] if args.widths else list(spec.agg_slices)

@@ -20,6 +20,7 @@ from .aggregate import (  # noqa: F401
     aggregate, aggregate_fwd, aggregate_bwd, aggregate_bwd_scatter,
     chunked_aggregate, round_bf16, num_threads, build_native,
 )
+from .sampled import rows_from_undirected_edges  # noqa: F401
 from .gcn import (  # noqa: F401
     nn_fwd, nn_bwd, softmax_cross_entropy, epoch_layerwise, epoch_decoupled,
 )

@@ -172,6 +172,23 @@ def test_p6_chunk_and_slice_invariance():
     np.testing.assert_array_equal(oracle.aggregate_fwd(g, X, rows=rows), full[rows])
 
 
+def test_sampled_rows_match_full_build():
+    """the row-by-row construction used for full-size samples equals the rows of the full build"""
+    n = 900
+    src, dst = gen.rmat_edges(n, 7000, seed=17)
+    g = oracle.build_graph(n, src, dst)
+    rows = np.array([17, 3, 899, 0, 450, int(np.argmax(g.d_in))], dtype=np.int64)
+    m = oracle.rows_from_undirected_edges(n, src, dst, rows)
+    for i, v in enumerate(rows):
+        a, b = g.csr.rowptr[v], g.csr.rowptr[v + 1]
+        np.testing.assert_array_equal(m.colidx[m.rowptr[i]:m.rowptr[i + 1]], g.csr.colidx[a:b])
+        np.testing.assert_array_equal(m.val[m.rowptr[i]:m.rowptr[i + 1]].view(np.uint32), g.csr.val[a:b].view(np.uint32))
+    X = gen.normal_features(n, 5, 17)
+    np.testing.assert_array_equal(oracle.aggregate(m, X), oracle.aggregate_fwd(g, X, rows=rows))
+    with pytest.raises(ValueError):
+        oracle.rows_from_undirected_edges(n, [1, 2], [1, 3], rows)
+
+
 def test_abs_sum_bounds_result():
     n = 200
     src, dst = gen.rmat_edges(n, 900, seed=8)
