@@ -41,14 +41,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4])
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--scale-down", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled"])
-    ap.add_argument("--mode", default="step", choices=["step", "agg", "chunk"],
+    ap.add_argument("--mode", default="step", choices=["step", "agg", "chunk", "budget"],
                     help="agg: time only aggregation calls at --widths (kernel tuning / profiling); "
-                         "chunk: chunk-streamed vs in-memory aggregation")
+                         "chunk: chunk-streamed vs in-memory aggregation; "
+                         "budget: the config's own device budget and chunk size (config 5), with a sampled parity check")
     ap.add_argument("--chunk-edges", type=int, default=0, help="entries per chunk for --mode chunk (default nnz/8)")
     ap.add_argument("--widths", default="", help="comma-separated slice widths for --mode agg")
     ap.add_argument("--agg-dtype", default="f32", choices=["f32", "bf16"])
@@ -71,11 +72,103 @@ def main():
         sys.exit(3)
     dev = "cuda:0"
     spec = gen.CONFIGS[args.config]
+    if args.config == 5 and args.mode not in ("budget", "step"):
+        log("bench.py: config 5 runs under its device budget: use --mode budget or --mode step")
+        sys.exit(2)
     t0 = time.time()
     n, src, dst = gen.make_graph(args.config, args.seed, args.scale_down)
     t_gen = time.time() - t0
+    log("config %d: generated %d undirected edges on %d vertices in %.1fs" % (args.config, src.size, n, t_gen))
+
+    if args.mode == "budget":
+        # the config's own budget and chunk size, scaled with --scale-down
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from helpers import rel_errors
+        budget = (spec.device_budget_bytes or (64 << 30)) // args.scale_down
+        ce = max(1024, (spec.chunk_edges or (256 << 20)) // args.scale_down)
+        f = int(args.widths.split(",")[0]) if args.widths else spec.agg_slices[0]
+        out = {"mode": "budget", "config": args.config, "scale_down": args.scale_down, "n_vertices": n,
+               "width": f, "device_budget_bytes": budget, "chunk_edges": ce}
+        x_np = gen.normal_features(n, f, args.seed)
+        x = torch.from_numpy(x_np).to(dev)
+        y = torch.empty_like(x)
+        cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def timeit(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+
+        # 1. every chunk streamed from pinned host memory (cold)
+        t0 = time.time()
+        gc = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | ntp.NTP_FORCE_STREAM,
+                                 device_budget_bytes=budget, chunk_edges=ce)
+        out["build_cold_s"] = time.time() - t0
+        info = ntp.ntp_graph_info(gc)
+        nnz = info["nnz"]
+        out.update(nnz=nnz, max_degree=info["max_degree"], n_chunks=info["n_chunks"])
+        log("cold graph built in %.1fs: nnz=%d chunks=%d" % (out["build_cold_s"], nnz, info["n_chunks"]))
+        ch = ntp.ntp_graph_chunks(gc)
+        b_pcie = int(((ch["entry_end"] - ch["entry_begin"]) * 8 + (ch["row_end"] - ch["row_begin"]) * 12).sum())
+        out["t_cold_ms"] = timeit(lambda: ntp.ntp_chunked_aggregate(gc, ntp.NTP_FWD, x, y, f, f, f, ntp.NTP_F32, cs, xs), 2)
+        out["cold_pcie_bytes"] = b_pcie
+        out["cold_pcie_gbs"] = b_pcie / (out["t_cold_ms"] * 1e-3) / 1e9
+        y_cold = y.clone()
+        log("cold: %.1f ms per aggregation (%.1f GB/s over PCIe)" % (out["t_cold_ms"], out["cold_pcie_gbs"]))
+        gc.close()
+        # 2. the budget decides residency (everything that fits stays on the device)
+        t0 = time.time()
+        gw = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=budget, chunk_edges=ce)
+        out["build_s"] = time.time() - t0
+        chw = ntp.ntp_graph_chunks(gw)
+        out["resident_chunks"] = "%d of %d" % (int(chw["resident"].sum()), len(chw["resident"]))
+        out["device_bytes"] = ntp.ntp_graph_device_bytes(gw)
+        out["t_warm_ms"] = timeit(lambda: ntp.ntp_chunked_aggregate(gw, ntp.NTP_FWD, x, y, f, f, f, ntp.NTP_F32, cs, xs), args.steps)
+        assert torch.equal(y, y_cold), "streamed and resident results differ"
+        if chw["resident"].all():
+            out["t_inmem_ms"] = timeit(lambda: ntp.ntp_aggregate_fwd(gw, x, y, f, f, f, ntp.NTP_F32, cs), args.steps)
+            out["warm_over_inmem"] = out["t_warm_ms"] / out["t_inmem_ms"]
+        out["geps_warm"] = nnz * f / (out["t_warm_ms"] * 1e-3) / 1e9
+        out["alg_gbs_warm"] = agg_bytes(n, nnz, f) / (out["t_warm_ms"] * 1e-3) / 1e9
+        out["geps_cold"] = nnz * f / (out["t_cold_ms"] * 1e-3) / 1e9
+        log("resident: %s chunks, %.3f ms per aggregation, %.0f GEPS" % (out["resident_chunks"], out["t_warm_ms"], out["geps_warm"]))
+        # 3. parity on sampled rows, recomputed by the oracle from the edge list
+        rowptr, _, _ = (ntp.ntp_graph_export(gw) if nnz < (1 << 28) else (None, None, None))
+        if rowptr is None:
+            rp = np.empty(n + 1, dtype=np.int64)
+            ntp.binding._check(ntp.lib().ntp_graph_export(gw.handle, ntp.NTP_CSR, ntp.binding._ptr(rp), None, None))
+            rowptr = rp
+        deg = np.diff(rowptr)
+        top = np.argsort(deg)[-100:]
+        uni = gen.stream_rng(args.seed, 98).choice(n, size=min(n, 20000), replace=False)
+        rows = np.unique(np.concatenate([top, uni])).astype(np.int64)
+        t0 = time.time()
+        m = oracle.rows_from_undirected_edges(n, src, dst, rows)
+        assert np.array_equal(np.diff(m.rowptr), deg[rows]), "row lengths differ from the oracle's"
+        ref, ref_abs = oracle.aggregate(m, x_np, with_abs=True)
+        got = y[torch.from_numpy(rows).to(dev)].cpu().numpy()
+        nerr, cerr, zok = rel_errors(got, ref, ref_abs)
+        out["parity"] = {"rows": int(rows.size), "normwise": nerr, "componentwise": cerr, "pass": bool(nerr <= 1e-5 and cerr <= 1e-5 and zok),
+                         "oracle_s": time.time() - t0}
+        log("parity on %d sampled rows: normwise %.2e componentwise %.2e" % (rows.size, nerr, cerr))
+        gw.close()
+        print(json.dumps(out), flush=True)
+        if not out["parity"]["pass"]:
+            sys.exit(1)
+        return
+
     t0 = time.time()
-    g = ntp.ntp_graph_build(n, src, dst)
+    use_chunked = args.config == 5       # the config's device budget and chunk size apply
+    if use_chunked:
+        g = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=spec.device_budget_bytes // args.scale_down,
+                                chunk_edges=max(1024, spec.chunk_edges // args.scale_down))
+    else:
+        g = ntp.ntp_graph_build(n, src, dst)
     t_build = time.time() - t0
     info = ntp.ntp_graph_info(g)
     nnz = info["nnz"]
@@ -229,17 +322,33 @@ def main():
         W8 = spec.n_workers
         slices = [-(-dims[l] // W8) for l in range(L)]          # ceil(width / 8) per layer input
         n_share = -(-n // W8)
-        xs = [torch.from_numpy(gen.normal_features(n, s, args.seed + l)).to(dev) for l, s in enumerate(slices)]
+        # timing only: the big dense operands are drawn on the device (seeded)
+        tg = torch.Generator(device=dev)
+        tg.manual_seed(args.seed)
+        xs = [torch.randn(n, s, generator=tg, **f32) for s in slices]
         ys = [torch.empty_like(x) for x in xs]
-        A = [torch.from_numpy(gen.normal_features(n_share, dims[l], args.seed + 10 + l)).to(dev) for l in range(L)]
+        A = [torch.randn(n_share, dims[l], generator=tg, **f32) for l in range(L)]
         Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev) for l in range(L)]
         H = [torch.empty(n_share, dims[l + 1], **f32) for l in range(L)]
-        dH = [torch.from_numpy(gen.normal_features(n_share, dims[l + 1], args.seed + 20 + l)).to(dev) for l in range(L)]
+        dH = [torch.randn(n_share, dims[l + 1], generator=tg, **f32) for l in range(L)]
         dA = [torch.empty(n_share, dims[l], **f32) for l in range(L)]
         dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
         wsb = max(ntp.ntp_nn_bwd_workspace_bytes(n_share, dims[l], dims[l + 1]) for l in range(L))
         ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device=dev)
         holder = {"ev": None}
+        copy_stream = torch.cuda.Stream() if use_chunked else None
+
+        def agg_fwd(gr, xi, yo, s, ldx, ldy, code, st):
+            if use_chunked:
+                ntp.ntp_chunked_aggregate(gr, ntp.NTP_FWD, xi, yo, s, ldx, ldy, code, st, copy_stream)
+            else:
+                ntp.ntp_aggregate_fwd(gr, xi, yo, s, ldx, ldy, code, st)
+
+        def agg_bwd(gr, xi, yo, s, ldx, ldy, code, st):
+            if use_chunked:
+                ntp.ntp_chunked_aggregate(gr, ntp.NTP_BWD, xi, yo, s, ldx, ldy, code, st, copy_stream)
+            else:
+                ntp.ntp_aggregate_bwd(gr, xi, yo, s, ldx, ldy, code, st)
 
         def timed(tag, fn, *a):
             if holder["ev"] is None:
@@ -254,7 +363,7 @@ def main():
             st = torch.cuda.current_stream()
             for l in range(L):
                 s = slices[l]
-                timed("agg_fwd f=%d" % s, ntp.ntp_aggregate_fwd, g, xs[l], ys[l], s, s, s, ntp.NTP_F32, st)
+                timed("agg_fwd f=%d" % s, agg_fwd, g, xs[l], ys[l], s, s, s, ntp.NTP_F32, st)
                 act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
                 timed("nn_fwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_fwd, A[l], Ws[l], H[l], n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, st)
             for l in range(L - 1, -1, -1):
@@ -263,7 +372,7 @@ def main():
                       n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, ws, wsb, st)
                 if l > 0:
                     s = slices[l]
-                    timed("agg_bwd f=%d" % s, ntp.ntp_aggregate_bwd, g, ys[l], xs[l], s, s, s, ntp.NTP_F32, st)
+                    timed("agg_bwd f=%d" % s, agg_bwd, g, ys[l], xs[l], s, s, s, ntp.NTP_F32, st)
 
         def set_events(lst):
             holder["ev"] = lst
@@ -323,26 +432,26 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         t0 = time.time()
-        og = oracle.build_graph(n, src, dst)
         fo = fdom
         xo = gen.normal_features(n, fo, args.seed)
-        rows = None
-        sample = "one forward aggregation of the whole graph at F_slice=%d" % fo
-        if og.nnz * fo > 3e9:      # bound the CPU work: a uniform row sample
-            k = max(1000, int(n * 3e9 / (og.nnz * fo)))
+        if nnz * fo <= 3e9:
+            og = oracle.build_graph(n, src, dst)
+            m = og.csr
+            done = og.nnz * fo
+            sample = "one forward aggregation of the whole graph at F_slice=%d" % fo
+        else:
+            # bound the CPU work: a uniform sample of rows, built one by one from the edge list
+            k = max(1000, int(n * 3e9 / (nnz * fo)))
             rows = np.sort(gen.stream_rng(args.seed, 99).choice(n, size=min(k, n), replace=False)).astype(np.int64)
-            sample = "forward aggregation of %d uniformly sampled rows at F_slice=%d" % (rows.size, fo)
+            m = oracle.rows_from_undirected_edges(n, src, dst, rows)
+            done = m.nnz * fo
+            sample = "forward aggregation of %d uniformly sampled rows (%d entries) at F_slice=%d" % (rows.size, m.nnz, fo)
         best = None
-        done = 0
         for _ in range(3):
             t1 = time.perf_counter()
-            oracle.aggregate_fwd(og, xo, rows=rows)
+            oracle.aggregate(m, xo)
             dt = time.perf_counter() - t1
             best = dt if best is None else min(best, dt)
-        if rows is None:
-            done = og.nnz * fo
-        else:
-            done = int((og.csr.rowptr[rows + 1] - og.csr.rowptr[rows]).sum()) * fo
         cpu_baseline = dict(value=done / best / 1e9, unit="GEPS", cores=oracle.num_threads(), kind="oracle",
                             sample=sample + ", fp64, best of 3 (%.3fs)" % best)
         log("oracle baseline: %.2f GEPS on %d threads (%.1fs incl. graph build)" % (cpu_baseline["value"], cpu_baseline["cores"], time.time() - t0))

@@ -92,36 +92,76 @@ def _rmat_draw(seed: int, first_batch: int, n_batches: int, n: int, scale: int, 
         return list(ex.map(lambda b: _rmat_batch(seed, b, bsz, n, scale, *abc), ids))
 
 
+def _bucket_unique(parts, n: int, n_buckets: int = 256):
+    """Distinct keys of the concatenation of `parts` (int64 keys lo * n + hi), found
+    bucket by bucket: keys are first grouped by an 8-bit multiplicative hash (a counting
+    sort on one byte), then each bucket is made unique on its own thread.  Same set as
+    np.unique of the concatenation, without one global sort; the order is by bucket, then
+    ascending, and does not depend on the number of threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    if not parts:
+        return np.empty(0, dtype=np.int64)
+    total = sum(p.size for p in parts)
+    if total < (1 << 22):
+        return np.unique(np.concatenate(parts))
+    mult = np.uint64(0x9E3779B97F4A7C15)
+
+    def split(p):
+        b = ((p.view(np.uint64) * mult) >> np.uint64(56)).astype(np.uint8)
+        order = np.argsort(b, kind="stable")        # radix sort on one byte
+        counts = np.bincount(b, minlength=n_buckets)
+        return p[order], counts
+
+    workers = min(16, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        grouped = list(ex.map(split, parts))
+
+        def uniq(k):
+            segs = []
+            for p, counts in grouped:
+                off = int(counts[:k].sum())
+                segs.append(p[off:off + int(counts[k])])
+            return np.unique(np.concatenate(segs)) if segs else np.empty(0, np.int64)
+
+        out = list(ex.map(uniq, range(n_buckets)))
+    return np.concatenate(out)
+
+
 def rmat_edges(n: int, m: int, seed: int = 0, abcd=(0.57, 0.19, 0.19, 0.05),
                exact: bool = True, permute: bool = True):
     """R-MAT undirected edges on n vertices.
 
     Recursion depth ceil(log2 n); an edge with an endpoint >= n or with equal
     endpoints is rejected; (u, v) and (v, u) are the same edge.  Draws come in
-    batches of min(2^22, max(2^12, 2^ceil(log2 m))), batch b from sub-stream b.  Batches are added until at
-    least m distinct edges exist.  With ``exact`` the first m distinct edges in
-    draw order are kept; otherwise all distinct edges of the batches drawn are
-    kept (a little more than m).  Vertex ids are then relabelled by a seeded
-    random permutation unless ``permute`` is False.
+    batches of min(2^22, max(2^12, 2^ceil(log2 m))), batch b from sub-stream b.
+    Batches are added until at least m distinct edges exist.  With ``exact`` the
+    first m distinct edges in draw order are kept; otherwise all distinct edges
+    of the batches drawn are kept (a little more than m), in hash-bucket order.
+    Vertex ids are then relabelled by a seeded random permutation unless
+    ``permute`` is False.
     """
     a, b, c, _ = abcd
     scale = max(1, int(np.ceil(np.log2(n))))
-    drawn = []            # per-batch keys in draw order (exact mode)
-    keys = np.empty(0, dtype=np.int64)
+    drawn = []            # per-batch keys in draw order
+    n_unique = 0
+    keys = None
     next_batch = 0
     bsz = min(_RMAT_BATCH, max(1 << 12, 1 << int(np.ceil(np.log2(max(2, m))))))
-    while keys.size < m:
-        deficit = m - keys.size
-        nb = max(1, int(np.ceil(deficit * 1.25 / bsz)))
-        parts = _rmat_draw(seed, next_batch, nb, n, scale, (a, b, c), bsz)
+    while n_unique < m:
+        deficit = m - n_unique
+        # first round: as many draws as edges wanted; later rounds oversample the deficit
+        nb = max(1, int(np.ceil(deficit * (1.0 if next_batch == 0 else 1.2) / bsz)))
+        drawn.extend(_rmat_draw(seed, next_batch, nb, n, scale, (a, b, c), bsz))
         next_batch += nb
-        if exact:
-            drawn.extend(parts)
-        keys = np.unique(np.concatenate([keys] + parts))
+        keys = _bucket_unique(drawn, n)
+        n_unique = keys.size
     if exact:
         keys = _first_unique(np.concatenate(drawn), m)
+    del drawn
     src = (keys // n).astype(np.int32)
     dst = (keys % n).astype(np.int32)
+    del keys
     if permute:
         src, dst = _permute_ids(n, src, dst, seed)
     return src, dst
