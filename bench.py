@@ -325,7 +325,9 @@ def main():
         # timing only: the big dense operands are drawn on the device (seeded)
         tg = torch.Generator(device=dev)
         tg.manual_seed(args.seed)
-        xs = [torch.randn(n, s, generator=tg, **f32) for s in slices]
+        # odd slice widths are held with their row stride padded to 4 elements (vector path)
+        lds = [-(-s // 4) * 4 for s in slices]
+        xs = [torch.randn(n, ld, generator=tg, **f32) for ld in lds]
         ys = [torch.empty_like(x) for x in xs]
         A = [torch.randn(n_share, dims[l], generator=tg, **f32) for l in range(L)]
         Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev) for l in range(L)]
@@ -363,7 +365,7 @@ def main():
             st = torch.cuda.current_stream()
             for l in range(L):
                 s = slices[l]
-                timed("agg_fwd f=%d" % s, agg_fwd, g, xs[l], ys[l], s, s, s, ntp.NTP_F32, st)
+                timed("agg_fwd f=%d" % s, agg_fwd, g, xs[l], ys[l], s, lds[l], lds[l], ntp.NTP_F32, st)
                 act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
                 timed("nn_fwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_fwd, A[l], Ws[l], H[l], n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, st)
             for l in range(L - 1, -1, -1):
@@ -372,7 +374,7 @@ def main():
                       n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, ws, wsb, st)
                 if l > 0:
                     s = slices[l]
-                    timed("agg_bwd f=%d" % s, agg_bwd, g, ys[l], xs[l], s, s, s, ntp.NTP_F32, st)
+                    timed("agg_bwd f=%d" % s, agg_bwd, g, ys[l], xs[l], s, lds[l], lds[l], ntp.NTP_F32, st)
 
         def set_events(lst):
             holder["ev"] = lst

@@ -15,7 +15,12 @@
  *    of the current device.  The library never frees or keeps caller buffers: pointers
  *    are used only by the work enqueued during the call.
  *  - Feature / gradient matrices are row-major; ld* are row strides in ELEMENTS (>= the
- *    slice width).  Input and output of one call must not overlap.
+ *    slice width).  Input and output of one call must not overlap.  Rows are read and
+ *    written in aligned vectors of up to 16 bytes; the vector width is the largest that
+ *    divides both row strides and the alignment of both base pointers.  When the slice
+ *    width is not a multiple of it, the last vector of an input row is read whole, i.e.
+ *    up to 15 bytes past the slice but inside the row stride (never written), so padding
+ *    the stride of an odd-width slice to a multiple of 4 elements buys the fast path.
  *  - stream arguments are hipStream_t passed as void* (NULL = the null stream).  The
  *    aggregate and nn calls only enqueue work; they do not synchronise with the host,
  *    except that the first call needing a larger scratch buffer allocates it.

@@ -5,7 +5,8 @@
 // Mapping.  A wavefront (64 lanes) is cut into R = 64/L groups of L lanes; the L lanes
 // of a group cover one feature row with one 4/8/16-byte vector load each, so a gather of
 // one neighbour row is one coalesced access.  Rows are binned by entry count on the host:
-//   - short rows:  one group per row, R rows per wavefront (no cross-lane reduction);
+//   - rows of up to 32 entries: one group per row, R rows per wavefront (no cross-lane
+//     reduction);
 //   - longer rows: one wavefront per row; 64 (index, weight) pairs are fetched with one
 //     coalesced load per lane, handed to the groups through the cross-lane network, the R
 //     groups gather R neighbour rows at a time and their sums are combined by a butterfly;
@@ -56,6 +57,7 @@ template <int VEC> struct IoF32 {
         else if constexpr (VEC == 2) { *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]); }
         else { *p = v[0]; }
     }
+    static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
 };
 
 // VEC fp32 partial sums to scratch (VEC may be 8 for bf16 features)
@@ -92,6 +94,7 @@ template <int VEC> struct IoBf16 {
         else if constexpr (VEC == 2) { *reinterpret_cast<unsigned*>(p) = pack(v[0], v[1]); }
         else { *p = (unsigned short)f32_to_bf16_rne(v[0]); }
     }
+    static __device__ __forceinline__ void store1(unsigned short* p, float v) { *p = (unsigned short)f32_to_bf16_rne(v); }
 };
 
 // ---- the aggregation kernel -----------------------------------------------------------
@@ -127,13 +130,17 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
     const int l = lane % L;
     const int colbase = (int)blockIdx.y * PASS_W + l * VEC;
 
-    bool act[NACC];
-    int coff[NACC];            // column offset read by this lane (0 when the column is outside the slice)
+    int nval[NACC];            // elements of vector j that lie inside the slice (0..VEC)
+    int coff[NACC];            // column offset read by this lane (0 when the vector is outside the slice)
 #pragma unroll
     for (int j = 0; j < NACC; ++j) {
-        act[j] = colbase + j * L * VEC < a.f;
-        coff[j] = act[j] ? colbase + j * L * VEC : 0;
+        const int c = colbase + j * L * VEC;
+        nval[j] = a.f - c < 0 ? 0 : (a.f - c > VEC ? VEC : a.f - c);
+        coff[j] = nval[j] > 0 ? c : 0;
     }
+    // a vector that straddles the end of the slice is read whole (the row stride is a
+    // multiple of the vector width, so the read stays inside the row) and stored element
+    // by element (store_row below)
 
     const T* __restrict__ X = static_cast<const T*>(a.X);
     const int64_t ldx = a.ldx;
@@ -142,6 +149,17 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
     for (int j = 0; j < NACC; ++j)
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[j][i] = 0.f;
+    auto store_row = [&](T* y) {
+#pragma unroll
+        for (int j = 0; j < NACC; ++j) {
+            if (nval[j] == VEC) IO::store(y + j * L * VEC, acc[j]);
+            else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+                    if (i < nval[j]) IO::store1(y + j * L * VEC + i, acc[j][i]);
+            }
+        }
+    };
 
     // acc += sum over u < U of w[u] * X[c[u], columns of this lane]; all loads first
     auto gather_u = [&](const int (&c)[U], const float (&w)[U]) {
@@ -209,12 +227,7 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
                 gather_u_if(on, cj, wj);
             }
         }
-        if (valid) {
-            T* y = static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase;
-#pragma unroll
-            for (int j = 0; j < NACC; ++j)
-                if (act[j]) IO::store(y + j * L * VEC, acc[j]);
-        }
+        if (valid) store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase);
         return;
     }
 
@@ -227,7 +240,7 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
         row = __builtin_amdgcn_readfirstlane(sp->row);
         beg = uniform64(sp->e_begin);
         end = beg + __builtin_amdgcn_readfirstlane(sp->len);
-        pout = a.partial + (int64_t)__builtin_amdgcn_readfirstlane(sp->slot) * a.f + colbase;
+        pout = a.partial + (int64_t)__builtin_amdgcn_readfirstlane(sp->slot) * a.fp + colbase;
     } else {
         row = __builtin_amdgcn_readfirstlane(a.rows[a.item_off[grp] + item0]);
         beg = uniform64(a.rowptr[row - a.row_base]);
@@ -292,15 +305,12 @@ __global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
             for (int i = 0; i < VEC; ++i) acc[j][i] += bperm_f(lane ^ off, acc[j][i]);
 
     if (g == 0) {
-        if (mode == MODE_SEGMENT) {
+        if (mode == MODE_SEGMENT) {     // scratch rows are padded to whole vectors
 #pragma unroll
             for (int j = 0; j < NACC; ++j)
-                if (act[j]) store_partial<VEC>(pout + j * L * VEC, acc[j]);
+                if (nval[j] > 0) store_partial<VEC>(pout + j * L * VEC, acc[j]);
         } else {
-            T* y = static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase;
-#pragma unroll
-            for (int j = 0; j < NACC; ++j)
-                if (act[j]) IO::store(y + j * L * VEC, acc[j]);
+            store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase);
         }
     }
 }
@@ -319,14 +329,14 @@ __global__ void __launch_bounds__(256) reduce_kernel(const ReduceArgs a) {
         const int col = col0 + lane;
         float s = 0.f;
         if (col < a.f) {
-            const float* p = a.partial + (int64_t)it.first_slot * a.f + col;
+            const float* p = a.partial + (int64_t)it.first_slot * a.fp + col;
             int k = w;
             for (; k + 12 < it.n_slots; k += 16) {
-                const float t0 = p[(int64_t)k * a.f], t1 = p[(int64_t)(k + 4) * a.f];
-                const float t2 = p[(int64_t)(k + 8) * a.f], t3 = p[(int64_t)(k + 12) * a.f];
+                const float t0 = p[(int64_t)k * a.fp], t1 = p[(int64_t)(k + 4) * a.fp];
+                const float t2 = p[(int64_t)(k + 8) * a.fp], t3 = p[(int64_t)(k + 12) * a.fp];
                 s += t0; s += t1; s += t2; s += t3;
             }
-            for (; k < it.n_slots; k += 4) s += p[(int64_t)k * a.f];
+            for (; k < it.n_slots; k += 4) s += p[(int64_t)k * a.fp];
         }
         part[w][lane] = s;
         __syncthreads();
@@ -388,7 +398,8 @@ int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t l
     const int es = dtype == NTP_BF16 ? 2 : 4;
     int vec = 16 / es;
     const uintptr_t px = (uintptr_t)X, py = (uintptr_t)Y;
-    while (vec > 1 && (f % vec || ldx % vec || ldy % vec || px % (uintptr_t)(vec * es) || py % (uintptr_t)(vec * es))) vec >>= 1;
+    (void)f;   // the slice width need not be a multiple: a straddling vector is read whole, stored by element
+    while (vec > 1 && (ldx % vec || ldy % vec || px % (uintptr_t)(vec * es) || py % (uintptr_t)(vec * es))) vec >>= 1;
     return vec;
 }
 

@@ -103,6 +103,7 @@ int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void
     a.ldx = ldx;
     a.ldy = ldy;
     a.f = (int32_t)f;
+    a.fp = (int32_t)((f + 7) / 8 * 8);
 
     const int vec = agg_pick_vec(X, Y, f, ldx, ldy, dtype);
     int L, nacc, passes;
@@ -124,7 +125,8 @@ int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void
     for (int b = NBINS - 1; b >= 0; --b) {
         const int cnt = c.bin_count[b];
         if (cnt == 0) continue;
-        const bool per_group = R > 1 && bin_max_degree(b) <= 2 * R;
+        // rows of up to 32 entries: one lane group per row (measured best for every group count)
+        const bool per_group = R > 1 && bin_max_degree(b) <= 32;
         if (per_group) add_group(MODE_GROUP_PER_ROW, c.bin_row_off[b], cnt, (cnt + R - 1) / R);
         else add_group(MODE_WAVE_PER_ROW, c.bin_row_off[b], cnt, cnt);
     }
@@ -142,6 +144,7 @@ int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void
         r.Y = Y;
         r.ldy = ldy;
         r.f = (int32_t)f;
+        r.fp = (int32_t)((f + 7) / 8 * 8);
         r.n_items = c.n_reduce;
         const int rc = launch_reduce(r, dtype, st);
         if (rc != NTP_OK) return rc;
@@ -150,7 +153,7 @@ int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void
 }
 
 int ensure_partial(ntp_graph* G, const Form& F, int64_t f) {
-    const size_t need = (size_t)F.plan.n_slots * (size_t)f * sizeof(float);
+    const size_t need = (size_t)F.plan.n_slots * (size_t)((f + 7) / 8 * 8) * sizeof(float);
     if (need <= G->partial_bytes) return NTP_OK;
     if (G->partial) {
         HIP_TRY(hipDeviceSynchronize());       // earlier calls may still read the old buffer

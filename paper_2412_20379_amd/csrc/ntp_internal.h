@@ -127,11 +127,12 @@ struct AggArgs {
     const Segment* segs;
     const void* X;
     void* Y;
-    float* partial;            // [n_slots x f] partial sums of split rows
+    float* partial;            // [n_slots x fp] partial sums of split rows
     int64_t row_base;
     int64_t e_base;
     int64_t ldx, ldy;
     int32_t f;                 // slice width
+    int32_t fp;                // row stride of `partial` in floats: f rounded up to 8
     int32_t n_groups;          // entries used in the tables below
     int32_t wave_start[NGROUPS + 1];   // first wavefront of each group; last = total
     int32_t item_off[NGROUPS];         // offset into rows[] (bins) or segs[] (segment group)
@@ -146,6 +147,7 @@ struct ReduceArgs {
     void* Y;
     int64_t ldy;
     int32_t f;
+    int32_t fp;                // row stride of `partial` in floats
     int32_t n_items;
 };
 
