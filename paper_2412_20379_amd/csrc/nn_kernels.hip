@@ -38,6 +38,12 @@ struct GemmArgs {
     int64_t k_per_split;          // contraction range per blockIdx.z (multiple of BK)
     int64_t c_split_stride;       // elements between the outputs of consecutive splits
     int relu;
+    // block id -> tile: blocks that read the same rows of the streamed operand ("major":
+    // the row tile of C, or the split for dW) differ by 8 in block id, so the hardware's
+    // round-robin puts them on the same XCD at about the same time and the second reader
+    // finds the rows in that XCD's L2.
+    int tiles_m, tiles_n, n_splits;
+    int share_splits;             // 1: major = split (dW), 0: major = row tile of C
 };
 
 __device__ __forceinline__ float elem_to_f32(float v) { return v; }
@@ -146,9 +152,20 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(const GemmArgs g) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
-    const int64_t n0 = (int64_t)blockIdx.y * BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+    int bx, by, bz;
+    {
+        const int n_major = g.share_splits ? g.n_splits : g.tiles_m;
+        const int n_minor = g.share_splits ? g.tiles_m * g.tiles_n : g.tiles_n;
+        const int id = (int)blockIdx.x;
+        const int grp = id / (8 * n_minor), r = id % (8 * n_minor);
+        const int minor = r / 8, major = grp * 8 + r % 8;
+        if (major >= n_major) return;              // padding of the last group of eight
+        if (g.share_splits) { bz = major; bx = minor % g.tiles_m; by = minor / g.tiles_m; }
+        else { bz = 0; bx = major; by = minor; }
+    }
+    const int64_t m0 = (int64_t)bx * BM;
+    const int64_t n0 = (int64_t)by * BN;
+    const int64_t kbeg = (int64_t)bz * g.k_per_split;
     const int64_t kend = kbeg + g.k_per_split < g.Kdim ? kbeg + g.k_per_split : g.Kdim;
 
     const TA* A = static_cast<const TA*>(g.A);
@@ -199,7 +216,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(const GemmArgs g) {
     }
 
     // epilogue: element e of a 32x32 accumulator sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
-    TC* C = static_cast<TC*>(g.C) + (int64_t)blockIdx.z * g.c_split_stride;
+    TC* C = static_cast<TC*>(g.C) + (int64_t)bz * g.c_split_stride;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -242,18 +259,29 @@ __global__ void __launch_bounds__(256) sum_splits_kernel(const float* __restrict
     if (w == 0 && i < count) out[i] = (tmp[0][lane] + tmp[1][lane]) + (tmp[2][lane] + tmp[3][lane]);
 }
 
+template <class TA, class TB, class TC, bool AK, bool BKC, bool MA, bool MB, int BM, int BN, int WM, int WN>
+void launch_tiles(GemmArgs g, int n_splits, hipStream_t st) {
+    g.tiles_m = (int)((g.Mdim + BM - 1) / BM);
+    g.tiles_n = (int)((g.Ndim + BN - 1) / BN);
+    g.n_splits = n_splits;
+    g.share_splits = n_splits > 1 ? 1 : 0;
+    const int64_t n_major = g.share_splits ? n_splits : g.tiles_m;
+    const int64_t n_minor = g.share_splits ? (int64_t)g.tiles_m * g.tiles_n : g.tiles_n;
+    const int64_t blocks = (n_major + 7) / 8 * 8 * n_minor;
+    hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>), dim3((unsigned)blocks), dim3(NTHREADS), 0, st, g);
+}
+
 template <class TA, class TB, class TC, bool AK, bool BKC, bool MA, bool MB>
 int launch_gemm(const GemmArgs& g, int n_splits, hipStream_t st) {
     hipError_t e;
     if (g.Ndim > 64) {
-        dim3 grid((unsigned)((g.Mdim + 127) / 128), (unsigned)((g.Ndim + 127) / 128), (unsigned)n_splits);
-        hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, 128, 128, 2, 2>), grid, dim3(NTHREADS), 0, st, g);
+        launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 128, 128, 2, 2>(g, n_splits, st);
     } else if (g.Ndim > 32) {
-        dim3 grid((unsigned)((g.Mdim + 255) / 256), (unsigned)((g.Ndim + 63) / 64), (unsigned)n_splits);
-        hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, 256, 64, 4, 1>), grid, dim3(NTHREADS), 0, st, g);
-    } else {
-        dim3 grid((unsigned)((g.Mdim + 255) / 256), 1, (unsigned)n_splits);
-        hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, 256, 32, 4, 1>), grid, dim3(NTHREADS), 0, st, g);
+        launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 256, 64, 4, 1>(g, n_splits, st);
+    } else if ((g.Mdim + 255) / 256 * n_splits >= 256) {
+        launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 256, 32, 4, 1>(g, n_splits, st);
+    } else {     // few rows: smaller tiles so that more compute units get a block
+        launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 128, 32, 4, 1>(g, n_splits, st);
     }
     e = hipGetLastError();
     if (e != hipSuccess) { set_error("transform kernel launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
@@ -265,7 +293,8 @@ int dw_splits(int64_t n, int64_t k, int64_t m) {
     const int64_t bm = m > 64 ? 128 : 256;
     const int64_t bn = m > 64 ? 128 : (m > 32 ? 64 : 32);
     const int64_t tiles = ((k + bm - 1) / bm) * ((m + bn - 1) / bn);
-    int64_t s = (1024 + tiles - 1) / tiles;
+    // one round of blocks at three blocks per compute unit (256 CUs): no partial last round
+    int64_t s = std::max<int64_t>(1, 768 / tiles);
     const int64_t max_s = std::max<int64_t>(1, n / (BK * 8));
     s = std::max<int64_t>(1, std::min(s, max_s));
     return (int)std::min<int64_t>(s, 1024);
