@@ -249,6 +249,24 @@ def main():
         assert torch.equal(y, ref)
         out["cold_pcie_bytes"] = b_pcie
         out["cold_floor_ms"] = max(t_inmem, b_pcie / (pcie_gbs * 1e9) * 1e3)
+        # four column slices against one streamed pass over the topology
+        xs4 = [torch.randn_like(x) for _ in range(4)]
+        ys4 = [torch.empty_like(x) for _ in range(4)]
+
+        def four_separate():
+            for a_, b_ in zip(xs4, ys4):
+                ntp.ntp_chunked_aggregate(g_cold, ntp.NTP_FWD, a_, b_, f, f, f, ntp.NTP_F32, cs, xs)
+
+        def four_multi():
+            ntp.ntp_chunked_aggregate_multi(g_cold, ntp.NTP_FWD, xs4, ys4, f, f, f, ntp.NTP_F32, cs, xs)
+        for fn, key in ((four_separate, "t_cold_4_slices_separate_ms"), (four_multi, "t_cold_4_slices_one_pass_ms")):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            out[key] = (time.perf_counter() - t0) * 1e3 / args.steps
         out["cold_over_floor"] = out["t_cold_ms"] / out["cold_floor_ms"]
         out["warm_over_floor"] = out["t_warm_ms"] / out["warm_floor_ms"]
         out["all_resident_over_inmem"] = out["t_chunked_all_resident_ms"] / t_inmem

@@ -155,6 +155,21 @@ int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y,
                           void* compute_stream, void* copy_stream);
 
 /*
+ * The same schedule for several right-hand sides (several column slices held by one
+ * worker, or the slices of several workers run one after the other on one GPU): every
+ * chunk is brought to the device ONCE and applied to all n_rhs inputs before the next
+ * chunk is touched, so the host-link traffic of a streamed pass is paid once instead of
+ * n_rhs times (the backward sums of Section 4.2.1 stay independent per right-hand side).
+ * X and Y are host arrays of n_rhs device pointers (1 <= n_rhs <= 64); all right-hand
+ * sides share f_slice, the strides and the dtype; no output may alias any input or other
+ * output.  Results are bit-identical to n_rhs separate ntp_chunked_aggregate calls.
+ */
+int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
+                                const void* const* X, void* const* Y,
+                                int64_t f_slice, int64_t ldx, int64_t ldy, int dtype,
+                                void* compute_stream, void* copy_stream);
+
+/*
  * Dense transform, UPDATE of eq. (4):  H = act(A W),  A [n x k] (ld k), W [k x m] (ld m),
  * H [n x m] (ld m), all device, row-major, dtype NTP_F32 (fp32 MFMA) or NTP_BF16 (bf16
  * MFMA, fp32 accumulate, bf16 output).  act = NTP_ACT_NONE or NTP_ACT_RELU.

@@ -20,6 +20,7 @@ NTP_ACT_NONE, NTP_ACT_RELU = 0, 1
 EXPORTED_SYMBOLS = [
     "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_chunks",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
+    "ntp_chunked_aggregate_multi",
     "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_graph_free", "ntp_last_error",
 ]
 
@@ -56,6 +57,7 @@ def lib():
     L.ntp_aggregate_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_aggregate_bwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_chunked_aggregate.argtypes = [vp, ctypes.c_int, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
+    L.ntp_chunked_aggregate_multi.argtypes = [vp, ctypes.c_int, i32, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_nn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp]
     L.ntp_nn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, i64, vp]
     L.ntp_nn_bwd_workspace_bytes.argtypes = [i64, i64, i64]
@@ -185,6 +187,17 @@ def ntp_chunked_aggregate(g: Graph, direction, X, Y, f_slice, ldx, ldy, dtype=NT
                           compute_stream=None, copy_stream=None):
     _check(lib().ntp_chunked_aggregate(g.handle, int(direction), _ptr(X), _ptr(Y), int(f_slice), int(ldx), int(ldy),
                                        int(dtype), _stream(compute_stream), _stream(copy_stream)))
+
+
+def ntp_chunked_aggregate_multi(g: Graph, direction, Xs, Ys, f_slice, ldx, ldy, dtype=NTP_F32,
+                                compute_stream=None, copy_stream=None):
+    if len(Xs) != len(Ys) or not Xs:
+        raise ValueError("Xs and Ys must be non-empty lists of equal length")
+    k = len(Xs)
+    xa = (ctypes.c_void_p * k)(*[_ptr(x) for x in Xs])
+    ya = (ctypes.c_void_p * k)(*[_ptr(y) for y in Ys])
+    _check(lib().ntp_chunked_aggregate_multi(g.handle, int(direction), k, xa, ya, int(f_slice), int(ldx), int(ldy),
+                                             int(dtype), _stream(compute_stream), _stream(copy_stream)))
 
 
 def ntp_nn_fwd(A, W, H, n, k, m, act=NTP_ACT_NONE, dtype=NTP_F32, stream=None):

@@ -17,7 +17,8 @@ HEADERS = [os.path.join(CSRC, "ntp_internal.h"), os.path.join(ROOT, "include", "
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
           "-ffp-contract=off", "-Wall", "-Wno-unused-function"]
-# packed fp32 instructions are switched off for device code
+# packed fp32 instructions (v_pk_*_f32) are switched off for device code: the compiler must
+# not form them from ordinary float arithmetic
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -6,6 +6,7 @@
 #include <climits>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <new>
 
 #include "ntp_internal.h"
@@ -86,7 +87,7 @@ int upload_chunk(const HostSparse& m, Chunk& c, char* dst, hipStream_t st, bool 
 inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX : (1 << b)); }
 
 // Enqueue the kernels of one chunk whose image lives at `img` on the device.
-int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void* Y,
+int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* partial,
               int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st) {
     AggArgs a;
     memset(&a, 0, sizeof a);
@@ -97,7 +98,7 @@ int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void
     a.val = reinterpret_cast<const float*>(img + c.img_off_val);
     a.X = X;
     a.Y = Y;
-    a.partial = G->partial;
+    a.partial = partial;
     a.row_base = c.row_begin;
     a.e_base = c.e_begin;
     a.ldx = ldx;
@@ -140,7 +141,7 @@ int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void
     if (c.n_reduce > 0) {
         ReduceArgs r;
         r.items = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
-        r.partial = G->partial;
+        r.partial = partial;
         r.Y = Y;
         r.ldy = ldy;
         r.f = (int32_t)f;
@@ -152,8 +153,11 @@ int run_chunk(ntp_graph* G, const Chunk& c, const char* img, const void* X, void
     return NTP_OK;
 }
 
-int ensure_partial(ntp_graph* G, const Form& F, int64_t f) {
-    const size_t need = (size_t)F.plan.n_slots * (size_t)((f + 7) / 8 * 8) * sizeof(float);
+// floats of scratch one right-hand side needs for the partial sums of split rows
+size_t partial_floats(const Form& F, int64_t f) { return (size_t)F.plan.n_slots * (size_t)((f + 7) / 8 * 8); }
+
+int ensure_partial(ntp_graph* G, const Form& F, int64_t f, int n_rhs = 1) {
+    const size_t need = partial_floats(F, f) * sizeof(float) * (size_t)n_rhs;
     if (need <= G->partial_bytes) return NTP_OK;
     if (G->partial) {
         HIP_TRY(hipDeviceSynchronize());       // earlier calls may still read the old buffer
@@ -210,9 +214,9 @@ extern "C" {
 
 const char* ntp_last_error(void) { return last_error(); }
 
-int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
-                    const float* edge_weight, uint32_t flags, int64_t budget, int64_t chunk_edges,
-                    ntp_graph_t** out) {
+static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
+                            const float* edge_weight, uint32_t flags, int64_t budget, int64_t chunk_edges,
+                            ntp_graph_t** out) {
     if (!out) { set_error("out is NULL"); return NTP_EINVAL; }
     *out = nullptr;
     if (n < 0 || n > INT_MAX - 1) { set_error("n_vertices %lld out of range", (long long)n); return NTP_EINVAL; }
@@ -224,6 +228,7 @@ int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_
 
     ntp_graph* G = new (std::nothrow) ntp_graph();
     if (!G) { set_error("out of host memory"); return NTP_ENOMEM; }
+    std::unique_ptr<ntp_graph, void (*)(ntp_graph*)> guard(G, destroy);   // frees everything on any early return
     G->host_only = flags & NTP_HOST_ONLY;
     const bool force_stream = flags & NTP_FORCE_STREAM;
     // entries go to pinned memory whenever chunks may have to be streamed
@@ -231,7 +236,7 @@ int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_
     EntryAllocator alloc{G->pinned_entries ? alloc_pinned : alloc_plain, nullptr};
 
     int rc = build_host_graph(n, n_edges, src, dst, edge_weight, flags, alloc, &G->g);
-    if (rc != NTP_OK) { destroy(G); return rc; }
+    if (rc != NTP_OK) { return rc; }
     if (G->g.symmetric && G->g.csc.colidx) { free_entries(G->g.csc, G->pinned_entries); G->g.csc = HostSparse(); }
 
     const int n_forms = G->g.symmetric ? 1 : 2;
@@ -254,7 +259,6 @@ int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_
         for (auto& c : G->form[k].plan.chunks)
             if (c.e_end - c.e_begin > INT_MAX || G->form[k].plan.n_slots > INT_MAX / 2) {
                 set_error("a chunk holds more than 2^31 entries: pass a chunk_edges below that");
-                destroy(G);
                 return NTP_EUNSUPPORTED;
             }
 
@@ -269,18 +273,17 @@ int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_
         if (!fits) {
             if (budget > 0 && (int64_t)(2 * max_img) > budget) {
                 set_error("device budget %lld cannot hold two staging buffers of %zu bytes", (long long)budget, max_img);
-                destroy(G);
                 return NTP_EBUDGET;
             }
             G->stage_bytes = max_img;
             for (int b = 0; b < 2; ++b) {
                 void* p = nullptr;
-                if (hipMalloc(&p, max_img) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of a %zu-byte staging buffer failed", max_img); destroy(G); return NTP_ENOMEM; }
+                if (hipMalloc(&p, max_img) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of a %zu-byte staging buffer failed", max_img); return NTP_ENOMEM; }
                 G->stage[b] = (char*)p;
                 G->device_bytes += (int64_t)max_img;
                 if (hipEventCreateWithFlags(&G->ev_ready[b], hipEventDisableTiming) != hipSuccess ||
                     hipEventCreateWithFlags(&G->ev_free[b], hipEventDisableTiming) != hipSuccess) {
-                    set_error("hipEventCreate failed"); destroy(G); return NTP_EHIP;
+                    set_error("hipEventCreate failed"); return NTP_EHIP;
                 }
             }
             left = force_stream ? 0 : budget - (int64_t)(2 * max_img);
@@ -297,12 +300,12 @@ int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_
                 const bool resident = fits || (int64_t)c.img_bytes <= left;
                 if (resident) {
                     void* p = nullptr;
-                    if (hipMalloc(&p, c.img_bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of a %zu-byte chunk failed", c.img_bytes); destroy(G); return NTP_ENOMEM; }
+                    if (hipMalloc(&p, c.img_bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of a %zu-byte chunk failed", c.img_bytes); return NTP_ENOMEM; }
                     c.d_image = (char*)p;
                     G->device_bytes += (int64_t)c.img_bytes;
                     if (!fits) left -= (int64_t)c.img_bytes;
                     rc = upload_chunk(*G->form[k].m, c, c.d_image, nullptr, false, c.meta.data());
-                    if (rc != NTP_OK) { destroy(G); return rc; }
+                    if (rc != NTP_OK) { return rc; }
                 } else {
                     pinned_meta_bytes += c.meta.size();
                 }
@@ -314,7 +317,7 @@ int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_
         }
         if (pinned_meta_bytes) {
             void* p = nullptr;
-            if (hipHostMalloc(&p, pinned_meta_bytes, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); set_error("pinned allocation of %zu bytes failed", pinned_meta_bytes); destroy(G); return NTP_ENOMEM; }
+            if (hipHostMalloc(&p, pinned_meta_bytes, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); set_error("pinned allocation of %zu bytes failed", pinned_meta_bytes); return NTP_ENOMEM; }
             G->pinned_meta = (char*)p;
             size_t off = 0;
             for (int k = 0; k < n_forms; ++k)
@@ -326,10 +329,26 @@ int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_
                     }
         }
         const hipError_t se = hipDeviceSynchronize();
-        if (se != hipSuccess) { set_error("hipDeviceSynchronize failed: %s", hipGetErrorString(se)); destroy(G); return NTP_EHIP; }
+        if (se != hipSuccess) { set_error("hipDeviceSynchronize failed: %s", hipGetErrorString(se)); return NTP_EHIP; }
     }
-    *out = G;
+    *out = guard.release();
     return NTP_OK;
+}
+
+int ntp_graph_build(int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
+                    const float* edge_weight, uint32_t flags, int64_t budget, int64_t chunk_edges,
+                    ntp_graph_t** out) {
+    try {       // no C++ exception may cross the C boundary
+        return graph_build_impl(n, n_edges, src, dst, edge_weight, flags, budget, chunk_edges, out);
+    } catch (const std::bad_alloc&) {
+        set_error("out of host memory while building the graph");
+        if (out) *out = nullptr;
+        return NTP_ENOMEM;
+    } catch (...) {
+        set_error("unexpected failure while building the graph");
+        if (out) *out = nullptr;
+        return NTP_EINVAL;
+    }
 }
 
 int ntp_graph_info(const ntp_graph_t* g, int64_t* n, int64_t* nnz, int32_t* n_chunks,
@@ -385,7 +404,7 @@ static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y,
     rc = ensure_partial(g, F, f);
     if (rc != NTP_OK) return rc;
     for (auto& c : F.plan.chunks) {
-        rc = run_chunk(g, c, c.d_image, X, Y, f, ldx, ldy, dtype, (hipStream_t)stream);
+        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream);
         if (rc != NTP_OK) return rc;
     }
     return NTP_OK;
@@ -401,20 +420,39 @@ int ntp_aggregate_bwd(ntp_graph_t* g, const void* Gout, void* Gin, int64_t f, in
     return aggregate_resident(g, NTP_CSC, Gout, Gin, f, ldo, ldi, dtype, stream);
 }
 
-int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y, int64_t f,
-                          int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream) {
-    int rc = check_agg_args(g, X, Y, f, ldx, ldy, dtype);
-    if (rc != NTP_OK) return rc;
+int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
+                                const void* const* X, void* const* Y, int64_t f,
+                                int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream) {
+    if (n_rhs < 1 || n_rhs > 64) { set_error("n_rhs must be in 1..64"); return NTP_EINVAL; }
+    if (!X || !Y) { set_error("X or Y is NULL"); return NTP_EINVAL; }
+    int rc;
+    for (int r = 0; r < n_rhs; ++r) {
+        rc = check_agg_args(g, X[r], Y[r], f, ldx, ldy, dtype);
+        if (rc != NTP_OK) return rc;
+        for (int q = 0; q < n_rhs; ++q)
+            if (g->g.n > 0 && Y[r] == X[q]) { set_error("an output aliases an input"); return NTP_EINVAL; }
+        for (int q = 0; q < r; ++q)
+            if (g->g.n > 0 && Y[r] == Y[q]) { set_error("two outputs alias"); return NTP_EINVAL; }
+    }
     if (direction != NTP_FWD && direction != NTP_BWD) { set_error("direction must be NTP_FWD or NTP_BWD"); return NTP_EINVAL; }
     Form& F = g->f(direction == NTP_FWD ? NTP_CSR : NTP_CSC);
     if (g->g.n == 0) return NTP_OK;
     hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
     if (!F.all_resident && cs == xs) { set_error("copy_stream must differ from compute_stream when chunks are streamed"); return NTP_EINVAL; }
-    rc = ensure_partial(g, F, f);
+    rc = ensure_partial(g, F, f, n_rhs);
     if (rc != NTP_OK) return rc;
+    const size_t pstride = partial_floats(F, f);
+    // every chunk is brought in once and applied to all right-hand sides before the next one
+    auto run_all = [&](const Chunk& c, const char* img) -> int {
+        for (int r = 0; r < n_rhs; ++r) {
+            const int e = run_chunk(c, img, X[r], Y[r], g->partial + (size_t)r * pstride, f, ldx, ldy, dtype, cs);
+            if (e != NTP_OK) return e;
+        }
+        return NTP_OK;
+    };
     for (auto& c : F.plan.chunks) {
         if (c.d_image) {
-            rc = run_chunk(g, c, c.d_image, X, Y, f, ldx, ldy, dtype, cs);
+            rc = run_all(c, c.d_image);
             if (rc != NTP_OK) return rc;
             continue;
         }
@@ -426,12 +464,17 @@ int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y,
         if (rc != NTP_OK) return rc;
         HIP_TRY(hipEventRecord(g->ev_ready[b], xs));
         HIP_TRY(hipStreamWaitEvent(cs, g->ev_ready[b], 0));
-        rc = run_chunk(g, c, g->stage[b], X, Y, f, ldx, ldy, dtype, cs);
+        rc = run_all(c, g->stage[b]);
         if (rc != NTP_OK) return rc;
         HIP_TRY(hipEventRecord(g->ev_free[b], cs));
         g->stage_used[b] = true;
     }
     return NTP_OK;
+}
+
+int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y, int64_t f,
+                          int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream) {
+    return ntp_chunked_aggregate_multi(g, direction, 1, &X, &Y, f, ldx, ldy, dtype, compute_stream, copy_stream);
 }
 
 int ntp_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,

@@ -95,3 +95,37 @@ def test_chunked_config2_budget():
     check_agg(g, og, x, "fwd", "f32", "cfg2 chunked", chunked=True)
     check_agg(g, og, x, "bwd", "f32", "cfg2 chunked bwd", chunked=True)
     g.close()
+
+
+@pytest.mark.parametrize("chunk_edges,mode", [(101, "stream"), (5003, "stream"), (5003, "partial"), (20000, "resident")])
+@pytest.mark.parametrize("direction", ["fwd", "bwd"])
+def test_multi_rhs_equals_separate_calls(inputs, chunk_edges, mode, direction):
+    """several right-hand sides per chunk visit: same bits as one call per right-hand side"""
+    import torch
+    from gpu_util import dev_f32
+    from helpers import assert_close, TOL_F32
+    n, src, dst, og = inputs
+    flags = ntp.NTP_DIRECTED_GCN_FLAGS | (ntp.NTP_FORCE_STREAM if mode == "stream" else 0)
+    budget = 700_000 if mode == "partial" else 0
+    g = ntp.ntp_graph_build(n, src, dst, flags=flags, device_budget_bytes=budget, chunk_edges=chunk_edges)
+    f, k = 24, 3
+    d = ntp.NTP_FWD if direction == "fwd" else ntp.NTP_BWD
+    xs_np = [gen.normal_features(n, f, seed=50 + i) for i in range(k)]
+    xs = [dev_f32(x) for x in xs_np]
+    ys = [torch.full((n, f), float("nan"), device="cuda:0") for _ in range(k)]
+    cs, cp = torch.cuda.Stream(), torch.cuda.Stream()
+    ntp.ntp_chunked_aggregate_multi(g, d, xs, ys, f, f, f, ntp.NTP_F32, cs, cp)
+    torch.cuda.synchronize()
+    m = og.csr if direction == "fwd" else og.csc
+    for i in range(k):
+        one = torch.empty(n, f, device="cuda:0")
+        ntp.ntp_chunked_aggregate(g, d, xs[i], one, f, f, f, ntp.NTP_F32, cs, cp)
+        torch.cuda.synchronize()
+        assert torch.equal(one, ys[i]), "right-hand side %d differs from its separate call" % i
+        ref, ref_abs = oracle.aggregate(m, xs_np[i], with_abs=True)
+        assert_close(ys[i].cpu().numpy(), ref, ref_abs, TOL_F32, "multi rhs %d" % i)
+    with pytest.raises(ntp.NtpError):            # an output that is also an input
+        ntp.ntp_chunked_aggregate_multi(g, d, xs, [ys[0], xs[1], ys[2]], f, f, f, ntp.NTP_F32, cs, cp)
+    with pytest.raises(ntp.NtpError):            # two outputs alias
+        ntp.ntp_chunked_aggregate_multi(g, d, xs, [ys[0], ys[0], ys[2]], f, f, f, ntp.NTP_F32, cs, cp)
+    g.close()
