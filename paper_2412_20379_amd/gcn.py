@@ -17,13 +17,19 @@ class GcnEpoch:
 
     layer-wise (Section 3.1):  A_l = A_hat H_{l-1};  H_l = relu(A_l W_l), logits = A_L W_L
     decoupled (Section 4.1):   H = MLP(X);  Z = A_hat^L H
+    reordered:                 layer-wise, but the last layer (no activation) is evaluated as
+                               A_hat (H_{L-1} W_L) when that is the narrower side, so its forward
+                               and backward aggregations run at the output width; same function
+                               and gradients as layer-wise, fewer edge-feature products.
     """
 
     def __init__(self, graph: ntp.Graph, n: int, dims, device="cuda:0", order="layerwise", chunked=False):
         self.g, self.n, self.dims, self.order, self.chunked = graph, n, tuple(dims), order, chunked
         L = len(dims) - 1
         f32 = dict(dtype=torch.float32, device=device)
-        self.aggs = [torch.empty(n, dims[l], **f32) for l in range(L)] if order == "layerwise" else []
+        self.reorder_last = order == "reordered" and dims[-1] < dims[-2]
+        self.aggs = [torch.empty(n, dims[l], **f32) for l in range(L)] if order in ("layerwise", "reordered") else []
+        self.last_t = torch.empty(n, dims[-1], **f32) if self.reorder_last else None
         self.hid = [torch.empty(n, dims[l + 1], **f32) for l in range(L)]
         self.dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
         wmax = max(dims)
@@ -77,7 +83,9 @@ class GcnEpoch:
         return dZ
 
     def run(self, X, weights, labels):
-        return self._layerwise(X, weights, labels) if self.order == "layerwise" else self._decoupled(X, weights, labels)
+        if self.order in ("layerwise", "reordered"):
+            return self._layerwise(X, weights, labels)
+        return self._decoupled(X, weights, labels)
 
     def _layerwise(self, X, Ws, labels):
         n, d = self.n, self.dims
@@ -85,6 +93,13 @@ class GcnEpoch:
         st = torch.cuda.current_stream()
         H = X
         for l in range(L):
+            if l == L - 1 and self.reorder_last:
+                # logits = A_hat (H W): transform first, aggregate at the output width
+                self._nn_fwd(H, Ws[l], self.last_t, n, d[l], d[l + 1], ntp.NTP_ACT_NONE, ntp.NTP_F32, st)
+                self._agg(ntp.NTP_FWD, self.last_t, self.hid[l], d[l + 1])
+                H_in_last = H
+                H = self.hid[l]
+                continue
             self._agg(ntp.NTP_FWD, H, self.aggs[l], d[l])
             act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
             self._nn_fwd(self.aggs[l], Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
@@ -93,6 +108,15 @@ class GcnEpoch:
         dH = self._loss_grad(H, labels)
         for l in range(L - 1, -1, -1):
             act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+            if l == L - 1 and self.reorder_last:
+                # dT = A_hat^T dZ at the output width; then dW = H^T dT and dH = dT W^T
+                dT = self.last_t
+                self._agg(ntp.NTP_BWD, dH, dT, d[l + 1])
+                dHprev = self._view(1, d[l]) if l > 0 else None
+                self._nn_bwd(H_in_last, Ws[l], self.hid[l], dT, dHprev, self.dW[l], n, d[l], d[l + 1],
+                             ntp.NTP_ACT_NONE, ntp.NTP_F32, self.ws, self.ws_bytes, st)
+                dH = dHprev
+                continue
             dA = self._view(0, d[l]) if l > 0 else None
             self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
                          ntp.NTP_F32, self.ws, self.ws_bytes, st)

@@ -35,7 +35,7 @@ def _run(cfg, order, scale=1, chunked=False, directed=False):
     ep = GcnEpoch(g, n, dims, order=order, chunked=chunked)
     loss = ep.run(dev_f32(X), [dev_f32(w) for w in Ws], torch.from_numpy(labels.astype(np.int64)).to("cuda:0"))
     torch.cuda.synchronize()
-    fn = ogcn.epoch_layerwise if order == "layerwise" else ogcn.epoch_decoupled
+    fn = ogcn.epoch_decoupled if order == "decoupled" else ogcn.epoch_layerwise
     # The ReLU keeps or zeroes a pre-activation by its sign.  Where the pre-activation is
     # zero to rounding, fp32 and fp64 may decide differently, and one such entry on a hub
     # vertex moves dW by far more than rounding.  Both sides therefore take the device's
@@ -81,11 +81,12 @@ def test_epoch_config1(order):
 
 
 def test_epoch_config1_directed():
+    _run(1, "reordered", directed=True)
     _run(1, "layerwise", directed=True)
     _run(1, "decoupled", directed=True)
 
 
-@pytest.mark.parametrize("order", ["layerwise", "decoupled"])
+@pytest.mark.parametrize("order", ["layerwise", "decoupled", "reordered"])
 def test_epoch_config2(order):
     _run(2, order)
 
