@@ -45,7 +45,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--scale-down", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled"])
+    ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled", "reordered", "auto"])
+    ap.add_argument("--full-width", action="store_true",
+                    help="configs 3, 4: the whole model at full width on this GPU instead of one worker's share")
     ap.add_argument("--mode", default="step", choices=["step", "agg", "chunk", "budget"],
                     help="agg: time only aggregation calls at --widths (kernel tuning / profiling); "
                          "chunk: chunk-streamed vs in-memory aggregation; "
@@ -318,7 +320,7 @@ def main():
     edge_feats = 0            # stored entries x width, summed over aggregation calls of a step
     flops_nn = 0
 
-    if args.config in (1, 2):
+    if args.config in (1, 2) or args.full_width:
         X = torch.from_numpy(gen.make_features(args.config, dims[0], args.seed, args.scale_down)).to(dev)
         Ws = [torch.from_numpy(gen.glorot_weight(dims[i], dims[i + 1], args.seed, i)).to(dev) for i in range(L)]
         labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)).to(dev)
@@ -329,10 +331,13 @@ def main():
 
         def set_events(lst):
             ep.events = lst
-        if args.order == "layerwise":
-            edge_feats = nnz * (sum(dims[:-1]) + sum(dims[1:-1]))
-        else:
+        if args.order == "decoupled":
             edge_feats = nnz * dims[-1] * 2 * L
+        else:       # per layer: aggregation at the input width, or at the output width when transform-first
+            tf = ep.transform_first
+            fwd_w = sum(dims[l + 1] if tf[l] else dims[l] for l in range(L))
+            bwd_w = sum(dims[l + 1] if tf[l] else (dims[l] if l > 0 else 0) for l in range(L))
+            edge_feats = nnz * (fwd_w + bwd_w)
         flops_nn = sum(2 * n * dims[i] * dims[i + 1] * (3 if i > 0 else 2) for i in range(L))
         workload = "%s: %s GCN epoch fwd+bwd, %s, full width" % (spec.name, args.order, "->".join(map(str, dims)))
     else:
@@ -452,7 +457,7 @@ def main():
     # (all transforms first, then L aggregations at the output width, Section 4.1)
     other_order_ms = None
     reordered_ms = None
-    if args.config in (1, 2) and args.order == "layerwise":
+    if args.config in (1, 2) and args.order == "layerwise" and not args.full_width:
         ep2 = GcnEpoch(g, n, dims, order="decoupled")
         for _ in range(3):
             ep2.run(X, Ws, labels)

@@ -190,6 +190,17 @@ int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH,
 
 int64_t ntp_nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m);
 
+/*
+ * The activation sigma of eq. (4) on its own, for a layer evaluated as sigma(A_hat (H W))
+ * (transform first, aggregate at the narrower output width, then activate), where it cannot
+ * be fused into the transform.  ntp_relu_fwd: H = max(H, 0) in place.  ntp_relu_bwd:
+ * dZ = dH where H > 0, else 0 (dZ may be dH itself).  H, dH, dZ: device, [n x f], common row
+ * stride ld (elements), dtype NTP_F32 or NTP_BF16.  Asynchronous on `stream`.
+ */
+int ntp_relu_fwd(void* H, int64_t n, int64_t f, int64_t ld, int dtype, void* stream);
+int ntp_relu_bwd(const void* dH, const void* H, void* dZ, int64_t n, int64_t f, int64_t ld,
+                 int dtype, void* stream);
+
 /* Release a graph: waits for the device, frees device, pinned and host memory. NULL ok. */
 void ntp_graph_free(ntp_graph_t* g);
 

@@ -21,7 +21,8 @@ EXPORTED_SYMBOLS = [
     "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_chunks",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
     "ntp_chunked_aggregate_multi",
-    "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_graph_free", "ntp_last_error",
+    "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_relu_fwd", "ntp_relu_bwd",
+    "ntp_graph_free", "ntp_last_error",
 ]
 
 
@@ -60,6 +61,8 @@ def lib():
     L.ntp_chunked_aggregate_multi.argtypes = [vp, ctypes.c_int, i32, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_nn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp]
     L.ntp_nn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, i64, vp]
+    L.ntp_relu_fwd.argtypes = [vp, i64, i64, i64, ctypes.c_int, vp]
+    L.ntp_relu_bwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_nn_bwd_workspace_bytes.argtypes = [i64, i64, i64]
     L.ntp_nn_bwd_workspace_bytes.restype = i64
     L.ntp_graph_free.argtypes = [vp]
@@ -212,3 +215,11 @@ def ntp_nn_bwd(A, W, H, dH, dA, dW, n, k, m, act=NTP_ACT_NONE, dtype=NTP_F32,
                workspace=None, workspace_bytes=0, stream=None):
     _check(lib().ntp_nn_bwd(_ptr(A), _ptr(W), _ptr(H), _ptr(dH), _ptr(dA), _ptr(dW), int(n), int(k), int(m),
                             int(act), int(dtype), _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def ntp_relu_fwd(H, n, f, ld, dtype=NTP_F32, stream=None):
+    _check(lib().ntp_relu_fwd(_ptr(H), int(n), int(f), int(ld), int(dtype), _stream(stream)))
+
+
+def ntp_relu_bwd(dH, H, dZ, n, f, ld, dtype=NTP_F32, stream=None):
+    _check(lib().ntp_relu_bwd(_ptr(dH), _ptr(H), _ptr(dZ), int(n), int(f), int(ld), int(dtype), _stream(stream)))

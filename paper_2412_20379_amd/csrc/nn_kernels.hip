@@ -259,6 +259,24 @@ __global__ void __launch_bounds__(256) sum_splits_kernel(const float* __restrict
     if (w == 0 && i < count) out[i] = (tmp[0][lane] + tmp[1][lane]) + (tmp[2][lane] + tmp[3][lane]);
 }
 
+// ---- activation alone (for layers evaluated as act(A_hat (H W)): the activation follows the
+// aggregation, so it cannot ride on the transform's epilogue) ----------------------------
+// FWD: h = max(h, 0) in place.  BWD: dz = dh where h > 0, else 0.  Rows of f elements, stride ld.
+template <class T, bool BWD>
+__global__ void __launch_bounds__(256) relu_kernel(const T* __restrict__ dh, T* __restrict__ h_or_dz,
+                                                   const T* __restrict__ h, int64_t n, int64_t f, int64_t ld) {
+    const int64_t total = n * f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / f, c = i - r * f;
+        const int64_t o = r * ld + c;
+        if constexpr (BWD) {
+            h_or_dz[o] = elem_to_f32(h[o]) > 0.f ? dh[o] : (T)0;
+        } else {
+            if (!(elem_to_f32(h_or_dz[o]) > 0.f)) h_or_dz[o] = (T)0;      // NaN becomes 0 as well, like max(x, 0)
+        }
+    }
+}
+
 template <class TA, class TB, class TC, bool AK, bool BKC, bool MA, bool MB, int BM, int BN, int WM, int WN>
 void launch_tiles(GemmArgs g, int n_splits, hipStream_t st) {
     g.tiles_m = (int)((g.Mdim + BM - 1) / BM);
@@ -355,6 +373,26 @@ int nn_bwd_t(const void* A, const void* W, const void* H, const void* dH, void* 
 int64_t nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m) {
     const int S = dw_splits(n, k, m);
     return S > 1 ? (int64_t)S * k * m * 4 : 0;
+}
+
+int launch_relu(const void* dH, const void* H, void* out, int64_t n, int64_t f, int64_t ld, int dtype,
+                bool backward, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t total = n * f;
+    if (total == 0) return NTP_OK;
+    const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 256 * 32);
+    if (dtype == NTP_BF16) {
+        using T = unsigned short;
+        if (backward) hipLaunchKernelGGL((relu_kernel<T, true>), dim3(blocks), dim3(256), 0, st, (const T*)dH, (T*)out, (const T*)H, n, f, ld);
+        else hipLaunchKernelGGL((relu_kernel<T, false>), dim3(blocks), dim3(256), 0, st, (const T*)nullptr, (T*)out, (const T*)nullptr, n, f, ld);
+    } else {
+        using T = float;
+        if (backward) hipLaunchKernelGGL((relu_kernel<T, true>), dim3(blocks), dim3(256), 0, st, (const T*)dH, (T*)out, (const T*)H, n, f, ld);
+        else hipLaunchKernelGGL((relu_kernel<T, false>), dim3(blocks), dim3(256), 0, st, (const T*)nullptr, (T*)out, (const T*)nullptr, n, f, ld);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("activation kernel launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
+    return NTP_OK;
 }
 
 int launch_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,

@@ -502,6 +502,20 @@ int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH, void
     return launch_nn_bwd(A, W, H, dH, dA, dW, n, k, m, act, dtype, workspace, workspace_bytes, stream);
 }
 
+int ntp_relu_fwd(void* H, int64_t n, int64_t f, int64_t ld, int dtype, void* stream) {
+    if (n < 0 || f < 1 || ld < f) { set_error("bad activation shape n=%lld f=%lld ld=%lld", (long long)n, (long long)f, (long long)ld); return NTP_EINVAL; }
+    if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
+    if (n > 0 && !H) { set_error("NULL buffer"); return NTP_EINVAL; }
+    return launch_relu(nullptr, nullptr, H, n, f, ld, dtype, false, stream);
+}
+
+int ntp_relu_bwd(const void* dH, const void* H, void* dZ, int64_t n, int64_t f, int64_t ld, int dtype, void* stream) {
+    if (n < 0 || f < 1 || ld < f) { set_error("bad activation shape n=%lld f=%lld ld=%lld", (long long)n, (long long)f, (long long)ld); return NTP_EINVAL; }
+    if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
+    if (n > 0 && (!dH || !H || !dZ)) { set_error("NULL buffer"); return NTP_EINVAL; }
+    return launch_relu(dH, H, dZ, n, f, ld, dtype, true, stream);
+}
+
 int64_t ntp_nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m) { return nn_bwd_workspace_bytes(n, k, m); }
 
 void ntp_graph_free(ntp_graph_t* g) { destroy(g); }

@@ -164,5 +164,7 @@ int launch_nn_bwd(const void* A, const void* W, const void* H, const void* dH, v
                   int64_t n, int64_t k, int64_t m, int act, int dtype,
                   void* workspace, int64_t workspace_bytes, void* stream);
 int64_t nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m);
+int launch_relu(const void* dH, const void* H, void* out, int64_t n, int64_t f, int64_t ld, int dtype,
+                bool backward, void* stream);
 
 }  // namespace ntp

@@ -21,15 +21,26 @@ class GcnEpoch:
                                A_hat (H_{L-1} W_L) when that is the narrower side, so its forward
                                and backward aggregations run at the output width; same function
                                and gradients as layer-wise, fewer edge-feature products.
+    auto:                      every layer whose output is narrower than its input is evaluated
+                               as sigma(A_hat (H W)) (ntp_relu_fwd / ntp_relu_bwd supply the
+                               activation); the others stay aggregate-first.
     """
 
     def __init__(self, graph: ntp.Graph, n: int, dims, device="cuda:0", order="layerwise", chunked=False):
         self.g, self.n, self.dims, self.order, self.chunked = graph, n, tuple(dims), order, chunked
         L = len(dims) - 1
         f32 = dict(dtype=torch.float32, device=device)
-        self.reorder_last = order == "reordered" and dims[-1] < dims[-2]
-        self.aggs = [torch.empty(n, dims[l], **f32) for l in range(L)] if order in ("layerwise", "reordered") else []
-        self.last_t = torch.empty(n, dims[-1], **f32) if self.reorder_last else None
+        # per layer: evaluate as sigma(A_hat (H W)) instead of sigma((A_hat H) W)?
+        narrower = [dims[l + 1] < dims[l] for l in range(L)]
+        if order == "auto":
+            self.transform_first = narrower
+        elif order == "reordered":
+            self.transform_first = [False] * (L - 1) + [narrower[-1]]
+        else:
+            self.transform_first = [False] * L
+        lw = order in ("layerwise", "reordered", "auto")
+        self.aggs = [None if self.transform_first[l] else torch.empty(n, dims[l], **f32) for l in range(L)] if lw else []
+        self.tbuf = [torch.empty(n, dims[l + 1], **f32) if self.transform_first[l] else None for l in range(L)] if lw else []
         self.hid = [torch.empty(n, dims[l + 1], **f32) for l in range(L)]
         self.dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
         wmax = max(dims)
@@ -83,46 +94,57 @@ class GcnEpoch:
         return dZ
 
     def run(self, X, weights, labels):
-        if self.order in ("layerwise", "reordered"):
+        if self.order in ("layerwise", "reordered", "auto"):
             return self._layerwise(X, weights, labels)
         return self._decoupled(X, weights, labels)
+
+    def _other_view(self, t, f):
+        """a scratch view of width f that does not share memory with tensor t"""
+        i = 1 if (t is not None and t.data_ptr() == self.tmp[0].data_ptr()) else 0
+        return self._view(i, f)
 
     def _layerwise(self, X, Ws, labels):
         n, d = self.n, self.dims
         L = len(Ws)
         st = torch.cuda.current_stream()
+        tf = self.transform_first
+        ins = []
         H = X
         for l in range(L):
-            if l == L - 1 and self.reorder_last:
-                # logits = A_hat (H W): transform first, aggregate at the output width
-                self._nn_fwd(H, Ws[l], self.last_t, n, d[l], d[l + 1], ntp.NTP_ACT_NONE, ntp.NTP_F32, st)
-                self._agg(ntp.NTP_FWD, self.last_t, self.hid[l], d[l + 1])
-                H_in_last = H
-                H = self.hid[l]
-                continue
-            self._agg(ntp.NTP_FWD, H, self.aggs[l], d[l])
-            act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
-            self._nn_fwd(self.aggs[l], Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
+            ins.append(H)
+            last = l == L - 1
+            if tf[l]:
+                # sigma(A_hat (H W)): transform first, aggregate at the output width, then activate
+                self._nn_fwd(H, Ws[l], self.tbuf[l], n, d[l], d[l + 1], ntp.NTP_ACT_NONE, ntp.NTP_F32, st)
+                self._agg(ntp.NTP_FWD, self.tbuf[l], self.hid[l], d[l + 1])
+                if not last:
+                    self._timed("relu_fwd %d" % d[l + 1], ntp.ntp_relu_fwd, self.hid[l], n, d[l + 1], d[l + 1], ntp.NTP_F32, st)
+            else:
+                self._agg(ntp.NTP_FWD, H, self.aggs[l], d[l])
+                act = ntp.NTP_ACT_NONE if last else ntp.NTP_ACT_RELU
+                self._nn_fwd(self.aggs[l], Ws[l], self.hid[l], n, d[l], d[l + 1], act, ntp.NTP_F32, st)
             H = self.hid[l]
         self.logits = H
         dH = self._loss_grad(H, labels)
         for l in range(L - 1, -1, -1):
-            act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
-            if l == L - 1 and self.reorder_last:
-                # dT = A_hat^T dZ at the output width; then dW = H^T dT and dH = dT W^T
-                dT = self.last_t
+            last = l == L - 1
+            if tf[l]:
+                if not last:       # dZ = dH * 1[H > 0], in place
+                    self._timed("relu_bwd %d" % d[l + 1], ntp.ntp_relu_bwd, dH, self.hid[l], dH, n, d[l + 1], d[l + 1], ntp.NTP_F32, st)
+                dT = self.tbuf[l]  # dT = A_hat^T dZ at the output width; then dW = H_in^T dT, dH_in = dT W^T
                 self._agg(ntp.NTP_BWD, dH, dT, d[l + 1])
-                dHprev = self._view(1, d[l]) if l > 0 else None
-                self._nn_bwd(H_in_last, Ws[l], self.hid[l], dT, dHprev, self.dW[l], n, d[l], d[l + 1],
+                dHin = self._view(0, d[l]) if l > 0 else None
+                self._nn_bwd(ins[l], Ws[l], self.hid[l], dT, dHin, self.dW[l], n, d[l], d[l + 1],
                              ntp.NTP_ACT_NONE, ntp.NTP_F32, self.ws, self.ws_bytes, st)
-                dH = dHprev
-                continue
-            dA = self._view(0, d[l]) if l > 0 else None
-            self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
-                         ntp.NTP_F32, self.ws, self.ws_bytes, st)
-            if l > 0:
-                dH = self._view(1, d[l])
-                self._agg(ntp.NTP_BWD, dA, dH, d[l])
+                dH = dHin
+            else:
+                act = ntp.NTP_ACT_NONE if last else ntp.NTP_ACT_RELU
+                dA = self._other_view(dH, d[l]) if l > 0 else None
+                self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
+                             ntp.NTP_F32, self.ws, self.ws_bytes, st)
+                if l > 0:
+                    dH = self._other_view(dA, d[l])
+                    self._agg(ntp.NTP_BWD, dA, dH, d[l])
         return self.loss
 
     def _decoupled(self, X, Ws, labels):

@@ -81,14 +81,45 @@ def test_epoch_config1(order):
 
 
 def test_epoch_config1_directed():
+    _run(1, "auto", directed=True)
     _run(1, "reordered", directed=True)
     _run(1, "layerwise", directed=True)
     _run(1, "decoupled", directed=True)
 
 
-@pytest.mark.parametrize("order", ["layerwise", "decoupled", "reordered"])
+@pytest.mark.parametrize("order", ["layerwise", "decoupled", "reordered", "auto"])
 def test_epoch_config2(order):
     _run(2, order)
+
+
+def test_epoch_auto_order_mixed_widths():
+    """widths that go down, up and down again: both evaluation orders inside one model"""
+    import torch
+    from paper_2412_20379_amd.gcn import GcnEpoch
+    from gpu_util import dev_f32
+    n, src, dst = gen.make_graph(2, seed=1, scale_down=8)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    dims = (48, 24, 64, 10)
+    X = gen.normal_features(n, dims[0], 1)
+    Ws = [gen.glorot_weight(dims[i], dims[i + 1], 1, i) for i in range(3)]
+    labels = gen.uniform_labels(n, dims[-1], 1)
+    ep = GcnEpoch(g, n, dims, order="auto")
+    assert ep.transform_first == [True, False, True]
+    loss = ep.run(dev_f32(X), [dev_f32(w) for w in Ws], torch.from_numpy(labels.astype(np.int64)).to("cuda:0"))
+    torch.cuda.synchronize()
+    own = ogcn.epoch_layerwise(og, X, Ws, labels)
+    masks = [h.cpu().numpy() > 0 for h in ep.hid[:-1]]
+    ref = ogcn.epoch_layerwise(og, X, Ws, labels, relu_masks=masks)
+    for l, mk in enumerate(masks):
+        assert (mk != (own["hidden"][l] > 0)).mean() <= 1e-4
+    assert abs(float(loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    for l in range(3):
+        got = ep.dW[l].cpu().numpy().astype(np.float64)
+        dZ = ref["dH"][l] * (ref["hidden"][l] > 0) if l < 2 else ref["dH"][l]
+        scale = np.abs(ref["nn_in"][l]).T @ np.abs(dZ)
+        assert (np.abs(got - ref["dW"][l]) / scale).max() <= 5e-5, "dW[%d]" % l
+    g.close()
 
 
 def test_epoch_config2_chunked():

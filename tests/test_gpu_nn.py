@@ -111,3 +111,32 @@ def test_nn_deterministic():
         torch.cuda.synchronize()
         outs.append(dW.cpu().numpy())
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
+@pytest.mark.parametrize("n,f,ld", [(1, 1, 1), (1000, 7, 7), (777, 40, 48), (5000, 128, 128)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_relu_alone(n, f, ld, dtype):
+    """ntp_relu_fwd / ntp_relu_bwd against max(x, 0) and the 1[h > 0] mask; exact"""
+    import torch
+    from gpu_util import dev_f32, dev_bf16_bits, host_bf16
+    h = gen.normal_features(n, ld, seed=n)
+    h[::7, 0] = 0.0                                   # exact zeros are not kept
+    dh = gen.normal_features(n, ld, seed=n + 1, stream=6)
+    if dtype == "f32":
+        H, dH = dev_f32(h), dev_f32(dh)
+        code, hv, dhv = ntp.NTP_F32, h, dh
+        back = lambda t: t.cpu().numpy()
+    else:
+        (H, hv), (dH, dhv) = dev_bf16_bits(h), dev_bf16_bits(dh)
+        code = ntp.NTP_BF16
+        back = host_bf16
+    dZ = torch.zeros_like(dH)
+    ntp.ntp_relu_bwd(dH, H, dZ, n, f, ld, code)
+    ntp.ntp_relu_fwd(H, n, f, ld, code)
+    torch.cuda.synchronize()
+    want_h = hv.copy()
+    want_h[:, :f] = np.maximum(hv[:, :f], 0)          # columns beyond f untouched
+    assert np.array_equal(back(H), want_h)
+    want_dz = np.zeros_like(dhv)
+    want_dz[:, :f] = np.where(hv[:, :f] > 0, dhv[:, :f], 0)
+    assert np.array_equal(back(dZ), want_dz)
