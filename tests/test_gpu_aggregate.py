@@ -228,3 +228,36 @@ def test_configs_full_size_sampled_rows(cfg, f, dtypes):
             got = run_agg(g, x, direction, dt)[rows]
             assert_close(got, ref, ref_abs, TOL_F32 if dt == "f32" else TOL_BF16, "cfg%d full %s %s" % (cfg, dt, direction))
     g.close()
+
+
+def test_degenerate_graphs_on_device():
+    """no vertices, no edges, one vertex, one giant row: the calls succeed and give the defined result"""
+    import torch
+    from gpu_util import check_agg, DEV
+    g = ntp.ntp_graph_build(0, [], [])
+    ntp.ntp_aggregate_fwd(g, None, None, 4, 4, 4)                 # nothing to do, no buffers needed
+    ntp.ntp_chunked_aggregate(g, ntp.NTP_BWD, None, None, 4, 4, 4)
+    g.close()
+    for n in (1, 5):
+        og = oracle.build_graph(n, [], [])
+        g = ntp.ntp_graph_build(n, [], [])
+        x = gen.normal_features(n, 9, 1)
+        got = check_agg(g, og, x, "fwd", "f32", "edgeless")
+        assert np.array_equal(got, x)                              # A_hat = I
+        check_agg(g, og, x, "bwd", "bf16", "edgeless bf16")
+        g.close()
+    # a star: one row holds every vertex (split into segments), every other row has two entries
+    n = 70000
+    src = np.zeros(n - 1, dtype=np.int32)
+    dst = np.arange(1, n, dtype=np.int32)
+    og = oracle.build_graph(n, src, dst)
+    g = ntp.ntp_graph_build(n, src, dst)
+    assert ntp.ntp_graph_info(g)["max_degree"] == n
+    x = gen.normal_features(n, 40, 2)
+    check_agg(g, og, x, "fwd", "f32", "star")
+    check_agg(g, og, x, "bwd", "bf16", "star bf16")
+    g.close()
+    # the same star under a chunk size smaller than its centre row, streamed
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | ntp.NTP_FORCE_STREAM, chunk_edges=9000)
+    check_agg(g, og, x, "fwd", "f32", "star streamed", chunked=True)
+    g.close()
