@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--scale-down", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the extra epochs in other evaluation orders (keeps a profile to the step's own kernels)")
     ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled", "reordered", "auto"])
     ap.add_argument("--full-width", action="store_true",
                     help="configs 3, 4: the whole model at full width on this GPU instead of one worker's share")
@@ -457,7 +459,7 @@ def main():
     # (all transforms first, then L aggregations at the output width, Section 4.1)
     other_order_ms = None
     reordered_ms = None
-    if args.config in (1, 2) and args.order == "layerwise" and not args.full_width:
+    if args.config in (1, 2) and args.order == "layerwise" and not args.full_width and not args.no_context:
         ep2 = GcnEpoch(g, n, dims, order="decoupled")
         for _ in range(3):
             ep2.run(X, Ws, labels)
