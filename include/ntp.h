@@ -55,6 +55,13 @@ extern "C" {
 #define NTP_FORCE_STREAM   32u   /* keep no chunk resident: every chunk is copied from pinned
                                     host memory on every chunked call (cold streaming) */
 
+#define NTP_SCATTER_BWD    64u   /* do not store the by-source form: the backward aggregation
+                                    scatter-adds along the by-destination rows with fp32 atomics
+                                    (the paper's formulation, Section 4.2.1).  Halves topology
+                                    memory and host-link traffic of a directed graph; the order of
+                                    the additions, hence the last bits, vary from run to run; fp32
+                                    buffers only.  No effect when the adjacency is symmetric. */
+
 /* which compressed form */
 #define NTP_CSR 0   /* by destination: row v lists in-neighbours u ascending  (forward)  */
 #define NTP_CSC 1   /* by source:      row u lists out-neighbours v ascending (backward) */

@@ -10,6 +10,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 
 NTP_OK, NTP_EINVAL, NTP_ENOMEM, NTP_EHIP, NTP_EBUDGET, NTP_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 NTP_SYMMETRISE, NTP_DEDUP, NTP_ADD_SELF_LOOPS, NTP_NORM_GCN_SYM, NTP_HOST_ONLY, NTP_FORCE_STREAM = 1, 2, 4, 8, 16, 32
+NTP_SCATTER_BWD = 64
 NTP_GCN_FLAGS = NTP_SYMMETRISE | NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM
 NTP_DIRECTED_GCN_FLAGS = NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM
 NTP_CSR, NTP_CSC = 0, 1

@@ -173,9 +173,19 @@ int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32
     // degree arrays coincide, so the by-source form equals the by-destination form.
     const bool known_symmetric = symmetrise && edge_weight == nullptr;
 
+    // NTP_SCATTER_BWD: the backward pass scatters over the by-destination rows (Section 4.2.1),
+    // so the by-source form is not stored; its row lengths are still needed for the weights.
+    const bool want_csc = !(flags & NTP_SCATTER_BWD);
     HostSparse& C = out->csc;
     std::vector<int64_t> dout;          // by-source row lengths
-    if (!known_symmetric) {
+    if (!known_symmetric && !want_csc) {
+        dout.assign(n, 0);
+        parallel_for_threads(T, [&](int t, int nt) {
+            const int64_t lo = n * t / nt, hi = n * (t + 1) / nt;
+            for (int64_t e = 0; e < R.nnz; ++e) { const int32_t u = R.colidx[e]; if (u >= lo && u < hi) ++dout[u]; }
+        });
+    }
+    if (!known_symmetric && want_csc) {
         // ---- by-source form = transpose of the final entries, rows of C filled in CSR order
         std::vector<int64_t> ccnt(n, 0);
         parallel_for_threads(T, [&](int t, int nt) {
@@ -224,18 +234,19 @@ int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32
         };
         // CSR row v / column u: din(v) * dout(u);  CSC row u / column v: dout(u) * din(v)
         scale_rows(R, len, d_out);
-        if (!known_symmetric) scale_rows(C, dout, len);
+        if (!known_symmetric && want_csc) scale_rows(C, dout, len);
     }
 
     // ---- symmetric detection (bitwise)
     bool sym = known_symmetric;
-    if (!known_symmetric) {
+    if (!known_symmetric && want_csc) {
         sym = (C.nnz == R.nnz) && C.rowptr == R.rowptr &&
               memcmp(C.colidx, R.colidx, (size_t)R.nnz * 4) == 0 &&
               memcmp(C.val, R.val, (size_t)R.nnz * 4) == 0;
     }
     out->n = n;
     out->symmetric = sym;
+    out->has_csc = sym || want_csc;
     return NTP_OK;
 }
 

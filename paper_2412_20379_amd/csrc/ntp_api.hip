@@ -46,8 +46,10 @@ struct ntp_graph {
     size_t partial_bytes = 0;
     int64_t device_bytes = 0;
 
-    Form& f(int which) { return form[(which == NTP_CSC && !g.symmetric) ? 1 : 0]; }
-    const Form& f(int which) const { return form[(which == NTP_CSC && !g.symmetric) ? 1 : 0]; }
+    // the by-source product runs as a scatter over the by-destination form
+    bool scatter_bwd() const { return !g.has_csc; }
+    Form& f(int which) { return form[(which == NTP_CSC && !g.symmetric && g.has_csc) ? 1 : 0]; }
+    const Form& f(int which) const { return form[(which == NTP_CSC && !g.symmetric && g.has_csc) ? 1 : 0]; }
 };
 
 namespace {
@@ -87,8 +89,9 @@ int upload_chunk(const HostSparse& m, Chunk& c, char* dst, hipStream_t st, bool 
 inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX : (1 << b)); }
 
 // Enqueue the kernels of one chunk whose image lives at `img` on the device.
+// scatter: Y[colidx[k], :] += val[k] * X[row, :] instead of Y[row, :] = sum val[k] * X[colidx[k], :]
 int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* partial,
-              int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st) {
+              int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st, bool scatter = false) {
     AggArgs a;
     memset(&a, 0, sizeof a);
     a.rowptr = reinterpret_cast<const int64_t*>(img + c.off_rowptr);
@@ -106,9 +109,9 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
     a.f = (int32_t)f;
     a.fp = (int32_t)((f + 7) / 8 * 8);
 
-    const int vec = agg_pick_vec(X, Y, f, ldx, ldy, dtype);
     int L, nacc, passes;
-    agg_shape(f, vec, &L, &nacc, &passes);
+    if (scatter) L = scatter_lanes(f);
+    else agg_shape(f, agg_pick_vec(X, Y, f, ldx, ldy, dtype), &L, &nacc, &passes);
     const int R = 64 / L;
 
     int ng = 0;
@@ -135,10 +138,10 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
     a.wave_start[ng] = (int32_t)waves;
     a.n_groups = ng;
     if (ng > 0) {
-        const int rc = launch_aggregate(a, dtype, st);
+        const int rc = scatter ? launch_scatter(a, st) : launch_aggregate(a, dtype, st);
         if (rc != NTP_OK) return rc;
     }
-    if (c.n_reduce > 0) {
+    if (c.n_reduce > 0 && !scatter) {
         ReduceArgs r;
         r.items = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
         r.partial = partial;
@@ -223,7 +226,7 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
     if (n_edges < 0 || (n_edges > 0 && (!src || !dst))) { set_error("edge list missing"); return NTP_EINVAL; }
     if (budget < 0 || chunk_edges < 0) { set_error("negative budget or chunk size"); return NTP_EINVAL; }
     if (chunk_edges > INT_MAX) { set_error("chunk_edges must be below 2^31"); return NTP_EINVAL; }
-    const uint32_t known = NTP_SYMMETRISE | NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM | NTP_HOST_ONLY | NTP_FORCE_STREAM;
+    const uint32_t known = NTP_SYMMETRISE | NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM | NTP_HOST_ONLY | NTP_FORCE_STREAM | NTP_SCATTER_BWD;
     if (flags & ~known) { set_error("unknown flag bits 0x%x", flags & ~known); return NTP_EINVAL; }
 
     ntp_graph* G = new (std::nothrow) ntp_graph();
@@ -239,9 +242,9 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
     if (rc != NTP_OK) { return rc; }
     if (G->g.symmetric && G->g.csc.colidx) { free_entries(G->g.csc, G->pinned_entries); G->g.csc = HostSparse(); }
 
-    const int n_forms = G->g.symmetric ? 1 : 2;
+    const int n_forms = (G->g.symmetric || !G->g.has_csc) ? 1 : 2;
     G->form[0].m = &G->g.csr;
-    G->form[1].m = G->g.symmetric ? &G->g.csr : &G->g.csc;
+    G->form[1].m = n_forms == 1 ? &G->g.csr : &G->g.csc;
 
     // chunk size: caller's, else one chunk if everything fits, else half of what the
     // budget leaves per staging buffer
@@ -365,6 +368,7 @@ int ntp_graph_info(const ntp_graph_t* g, int64_t* n, int64_t* nnz, int32_t* n_ch
 int ntp_graph_export(const ntp_graph_t* g, int which, int64_t* rowptr, int32_t* colidx, float* val) {
     if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
     if (which != NTP_CSR && which != NTP_CSC) { set_error("which must be NTP_CSR or NTP_CSC"); return NTP_EINVAL; }
+    if (which == NTP_CSC && g->scatter_bwd()) { set_error("graph was built with NTP_SCATTER_BWD: no by-source form is stored"); return NTP_EUNSUPPORTED; }
     const HostSparse& m = *g->f(which).m;
     if (rowptr) memcpy(rowptr, m.rowptr.data(), (size_t)(m.n + 1) * 8);
     if (colidx && m.nnz) memcpy(colidx, m.colidx, (size_t)m.nnz * 4);
@@ -376,6 +380,7 @@ int ntp_graph_chunks(const ntp_graph_t* g, int which, int32_t* n_chunks, int64_t
                      int64_t* row_end, int64_t* entry_begin, int64_t* entry_end, int32_t* resident) {
     if (!g || !n_chunks) { set_error("graph handle or n_chunks is NULL"); return NTP_EINVAL; }
     if (which != NTP_CSR && which != NTP_CSC) { set_error("which must be NTP_CSR or NTP_CSC"); return NTP_EINVAL; }
+    if (which == NTP_CSC && g->scatter_bwd()) { set_error("graph was built with NTP_SCATTER_BWD: no by-source form is stored"); return NTP_EUNSUPPORTED; }
     const auto& chunks = g->f(which).plan.chunks;
     *n_chunks = (int32_t)chunks.size();
     for (size_t i = 0; i < chunks.size(); ++i) {
@@ -399,12 +404,15 @@ static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y,
     int rc = check_agg_args(g, X, Y, f, ldx, ldy, dtype);
     if (rc != NTP_OK) return rc;
     Form& F = g->f(which);
+    const bool scatter = which == NTP_CSC && g->scatter_bwd();
+    if (scatter && dtype != NTP_F32) { set_error("the scatter backward (NTP_SCATTER_BWD) takes fp32 buffers only"); return NTP_EUNSUPPORTED; }
     if (!F.all_resident) { set_error("topology is not fully device-resident: use ntp_chunked_aggregate"); return NTP_EBUDGET; }
     if (g->g.n == 0) return NTP_OK;
-    rc = ensure_partial(g, F, f);
+    if (scatter) rc = launch_zero_rows(Y, g->g.n, f, ldy, dtype, stream);
+    else rc = ensure_partial(g, F, f);
     if (rc != NTP_OK) return rc;
     for (auto& c : F.plan.chunks) {
-        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream);
+        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter);
         if (rc != NTP_OK) return rc;
     }
     return NTP_OK;
@@ -436,16 +444,22 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
     }
     if (direction != NTP_FWD && direction != NTP_BWD) { set_error("direction must be NTP_FWD or NTP_BWD"); return NTP_EINVAL; }
     Form& F = g->f(direction == NTP_FWD ? NTP_CSR : NTP_CSC);
+    const bool scatter = direction == NTP_BWD && g->scatter_bwd();
+    if (scatter && dtype != NTP_F32) { set_error("the scatter backward (NTP_SCATTER_BWD) takes fp32 buffers only"); return NTP_EUNSUPPORTED; }
     if (g->g.n == 0) return NTP_OK;
     hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
     if (!F.all_resident && cs == xs) { set_error("copy_stream must differ from compute_stream when chunks are streamed"); return NTP_EINVAL; }
-    rc = ensure_partial(g, F, f, n_rhs);
+    if (scatter) {
+        for (int r = 0; r < n_rhs && rc == NTP_OK; ++r) rc = launch_zero_rows(Y[r], g->g.n, f, ldy, dtype, cs);
+    } else {
+        rc = ensure_partial(g, F, f, n_rhs);
+    }
     if (rc != NTP_OK) return rc;
-    const size_t pstride = partial_floats(F, f);
+    const size_t pstride = scatter ? 0 : partial_floats(F, f);
     // every chunk is brought in once and applied to all right-hand sides before the next one
     auto run_all = [&](const Chunk& c, const char* img) -> int {
         for (int r = 0; r < n_rhs; ++r) {
-            const int e = run_chunk(c, img, X[r], Y[r], g->partial + (size_t)r * pstride, f, ldx, ldy, dtype, cs);
+            const int e = run_chunk(c, img, X[r], Y[r], scatter ? nullptr : g->partial + (size_t)r * pstride, f, ldx, ldy, dtype, cs, scatter);
             if (e != NTP_OK) return e;
         }
         return NTP_OK;

@@ -44,6 +44,7 @@ struct BuiltGraph {
     HostSparse csr;    // by destination
     HostSparse csc;    // by source (empty when symmetric: use csr)
     bool symmetric = false;
+    bool has_csc = true;    // false: built with NTP_SCATTER_BWD and not symmetric (backward = scatter over csr)
 };
 
 // allocator hooks so that graph_build.cpp stays free of HIP: returns nullptr on failure
@@ -154,6 +155,11 @@ struct ReduceArgs {
 // kernels (agg_kernels.hip / nn_kernels.hip); stream is a hipStream_t
 int launch_aggregate(const AggArgs& a, int dtype, void* stream);
 int launch_reduce(const ReduceArgs& a, int dtype, void* stream);
+// transposed product by scatter-add over the same rows: Y[colidx[k], :] += val[k] * X[row, :] (fp32 only)
+int launch_scatter(const AggArgs& a, void* stream);
+int scatter_lanes(int64_t f);      // lanes per feature row the scatter kernel uses for width f
+// Y[0:n, 0:f] = 0 (row stride ld); a fill kernel, not a memset node
+int launch_zero_rows(void* Y, int64_t n, int64_t f, int64_t ld, int dtype, void* stream);
 // lanes per row chosen for (f, vec): exposed for tests of the host logic
 void agg_shape(int64_t f, int vec, int* lanes_per_row, int* n_acc, int* n_passes);
 int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype);

@@ -71,6 +71,31 @@ def test_graph_build_every_flag_combination(flags, weighted):
     _assert_same(g, og)
 
 
+@pytest.mark.parametrize("flags", [0, 2, 4, 8, 14])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_graph_build_without_by_source_form(flags, weighted):
+    """NTP_SCATTER_BWD: the by-destination form is unchanged (its weights still use the
+    out-degrees), the by-source form is refused"""
+    n = 300
+    src, dst = gen.directed_random_edges(n, 2500, seed=40 + flags, hub=3, hub_in=150, hub_out=80)
+    w = gen.stream_rng(flags, 11).random(src.size).astype(np.float32) + 0.5 if weighted else None
+    g = ntp.ntp_graph_build(n, src, dst, w, flags=flags | HOST | ntp.NTP_SCATTER_BWD)
+    og = oracle.build_graph(n, src, dst, flags, w)
+    rowptr, colidx, val = ntp.ntp_graph_export(g, ntp.NTP_CSR)
+    assert np.array_equal(rowptr, og.csr.rowptr) and np.array_equal(colidx, og.csr.colidx)
+    assert np.array_equal(val.view(np.uint32), og.csr.val.view(np.uint32))
+    assert not ntp.ntp_graph_info(g)["is_symmetric"]
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_graph_export(g, ntp.NTP_CSC)
+    assert e.value.code == ntp.NTP_EUNSUPPORTED
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_graph_chunks(g, ntp.NTP_CSC)
+    # with SYMMETRISE and unit weights the flag changes nothing
+    gs = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | HOST | ntp.NTP_SCATTER_BWD)
+    assert ntp.ntp_graph_info(gs)["is_symmetric"]
+    _assert_same(gs, oracle.build_graph(n, src, dst, oracle.GCN_FLAGS))
+
+
 def test_symmetric_input_without_symmetrise_flag_is_detected():
     n = 500
     s, d = gen.erdos_renyi_edges(n, 2000, 3)

@@ -16,7 +16,7 @@ def say(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def _run(cfg, order, scale=1, chunked=False, directed=False):
+def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False):
     import torch
     from paper_2412_20379_amd.gcn import GcnEpoch
     from gpu_util import dev_f32
@@ -27,7 +27,7 @@ def _run(cfg, order, scale=1, chunked=False, directed=False):
         flags = oracle.DIRECTED_GCN_FLAGS
     og = oracle.build_graph(n, src, dst, flags)
     kw = dict(device_budget_bytes=8 << 20, chunk_edges=200_000) if chunked else {}
-    g = ntp.ntp_graph_build(n, src, dst, flags=flags, **kw)
+    g = ntp.ntp_graph_build(n, src, dst, flags=flags | (ntp.NTP_SCATTER_BWD if scatter else 0), **kw)
     dims = spec.layers
     X = gen.make_features(cfg, dims[0], seed=0, scale_down=scale)
     Ws = [gen.glorot_weight(dims[i], dims[i + 1], 0, i) for i in range(len(dims) - 1)]
@@ -85,6 +85,13 @@ def test_epoch_config1_directed():
     _run(1, "reordered", directed=True)
     _run(1, "layerwise", directed=True)
     _run(1, "decoupled", directed=True)
+
+
+def test_epoch_config1_directed_scatter_backward():
+    """same epoch with the by-source form left out: gradients flow back by scatter-add"""
+    _run(1, "layerwise", directed=True, scatter=True)
+    _run(1, "decoupled", directed=True, scatter=True)
+    _run(1, "auto", directed=True, scatter=True, chunked=True)
 
 
 @pytest.mark.parametrize("order", ["layerwise", "decoupled", "reordered", "auto"])
