@@ -350,8 +350,9 @@ def main():
         # timing only: the big dense operands are drawn on the device (seeded)
         tg = torch.Generator(device=dev)
         tg.manual_seed(args.seed)
-        # odd slice widths are held with their row stride padded to 4 elements (vector path)
-        lds = [-(-s // 4) * 4 for s in slices]
+        # slice rows start on 128-byte lines when they are at least one line wide (the aggregation
+        # then walks the columns line by line), else on 16-byte vectors
+        lds = [-(-s // 32) * 32 if s >= 32 else -(-s // 4) * 4 for s in slices]
         xs = [torch.randn(n, ld, generator=tg, **f32) for ld in lds]
         ys = [torch.empty_like(x) for x in xs]
         A = [torch.randn(n_share, dims[l], generator=tg, **f32) for l in range(L)]

@@ -110,8 +110,14 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
     a.fp = (int32_t)((f + 7) / 8 * 8);
 
     int L, nacc, passes;
-    if (scatter) L = scatter_lanes(f);
-    else agg_shape(f, agg_pick_vec(X, Y, f, ldx, ldy, dtype), &L, &nacc, &passes);
+    if (scatter) {
+        L = scatter_lanes(f);
+    } else {
+        const int vec = agg_pick_vec(X, Y, f, ldx, ldy, dtype);
+        const int64_t rows = c.partial_row ? 1 : c.row_end - c.row_begin;
+        a.pass_lanes = agg_pick_pass_lanes(X, ldx, dtype, vec, (double)(c.e_end - c.e_begin) / (double)std::max<int64_t>(1, rows));
+        agg_shape(f, vec, a.pass_lanes, &L, &nacc, &passes);
+    }
     const int R = 64 / L;
 
     int ng = 0;
@@ -181,7 +187,7 @@ int check_agg_args(const ntp_graph* g, const void* X, const void* Y, int64_t f, 
     if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
     if (g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
     if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
-    if (f < 1 || f > INT_MAX / 4) { set_error("slice width %lld out of range", (long long)f); return NTP_EINVAL; }
+    if (f < 1 || f > (1 << 20)) { set_error("slice width %lld out of range (1..2^20)", (long long)f); return NTP_EINVAL; }
     if (ldx < f || ldy < f) { set_error("row stride smaller than the slice width"); return NTP_EINVAL; }
     if (g->g.n > 0 && (!X || !Y)) { set_error("X or Y is NULL"); return NTP_EINVAL; }
     if (X == Y && g->g.n > 0) { set_error("input and output must not overlap"); return NTP_EINVAL; }

@@ -134,6 +134,7 @@ struct AggArgs {
     int64_t ldx, ldy;
     int32_t f;                 // slice width
     int32_t fp;                // row stride of `partial` in floats: f rounded up to 8
+    int32_t pass_lanes;        // vectors per feature row and column pass (0: widest shape)
     int32_t n_groups;          // entries used in the tables below
     int32_t wave_start[NGROUPS + 1];   // first wavefront of each group; last = total
     int32_t item_off[NGROUPS];         // offset into rows[] (bins) or segs[] (segment group)
@@ -161,7 +162,8 @@ int scatter_lanes(int64_t f);      // lanes per feature row the scatter kernel u
 // Y[0:n, 0:f] = 0 (row stride ld); a fill kernel, not a memset node
 int launch_zero_rows(void* Y, int64_t n, int64_t f, int64_t ld, int dtype, void* stream);
 // lanes per row chosen for (f, vec): exposed for tests of the host logic
-void agg_shape(int64_t f, int vec, int* lanes_per_row, int* n_acc, int* n_passes);
+void agg_shape(int64_t f, int vec, int pass_lanes, int* lanes_per_row, int* n_acc, int* n_passes);
+int agg_pick_pass_lanes(const void* X, int64_t ldx, int dtype, int vec, double entries_per_row);
 int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype);
 
 int launch_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,

@@ -48,7 +48,9 @@ def test_widths_bf16(hub_graph, f, direction):
 
 
 @pytest.mark.parametrize("f,ld_in,ld_out", [(32, 40, 32), (32, 32, 48), (76, 602, 80), (13, 100, 13), (16, 17, 19), (64, 65, 66),
-                                            (13, 16, 16), (77, 80, 80), (30, 32, 32), (1, 8, 8), (257, 264, 260), (1433, 1440, 1440)])
+                                            (13, 16, 16), (77, 80, 80), (30, 32, 32), (1, 8, 8), (257, 264, 260), (1433, 1440, 1440),
+                                            # rows that start on 128-byte lines: columns walked line by line, ragged last pass
+                                            (76, 96, 96), (100, 128, 128), (602, 608, 608), (200, 256, 224), (33, 64, 64), (65, 128, 96)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_strided_layouts(hub_graph, f, ld_in, ld_out, dtype):
     from gpu_util import check_agg
