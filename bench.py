@@ -36,6 +36,13 @@ def agg_bytes(n, nnz, f, elem=4):
     return 8 * nnz + 8 * (n + 1) + 2 * n * f * elem
 
 
+def line_padded_ld(f, elem=4):
+    """row stride (elements) for a slice of width f: rows at least one 128-byte line wide start
+    on line boundaries, narrower ones on 16-byte vectors"""
+    per_line, per_vec = 128 // elem, 16 // elem
+    return -(-f // per_line) * per_line if f >= per_line else -(-f // per_vec) * per_vec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -284,27 +291,31 @@ def main():
         widths = [int(w) for w in args.widths.split(",")] if args.widths else list(spec.agg_slices)
         res = []
         for f in widths:
-            x = torch.from_numpy(gen.normal_features(n, f, args.seed)).to(dev)
+            x0 = torch.from_numpy(gen.normal_features(n, f, args.seed)).to(dev)
             code, elem = ntp.NTP_F32, 4
             if args.agg_dtype == "bf16":
-                x = torch.from_numpy(gen.to_bf16_bits(x.cpu().numpy()).view(np.int16)).to(dev)
+                x0 = torch.from_numpy(gen.to_bf16_bits(x0.cpu().numpy()).view(np.int16)).to(dev)
                 code, elem = ntp.NTP_BF16, 2
+            ld = line_padded_ld(f, elem)          # rows start on 128-byte lines
+            x = torch.zeros(n, ld, dtype=x0.dtype, device=dev)
+            x[:, :f] = x0
+            del x0
             y = torch.empty_like(x)
             st = torch.cuda.current_stream()
             for direction, fn in (("fwd", ntp.ntp_aggregate_fwd), ("bwd", ntp.ntp_aggregate_bwd)):
                 for _ in range(args.warmup):
-                    fn(g, x, y, f, f, f, code, st)
+                    fn(g, x, y, f, ld, ld, code, st)
                 evs = []
                 for _ in range(args.steps):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
-                    fn(g, x, y, f, f, f, code, st)
+                    fn(g, x, y, f, ld, ld, code, st)
                     e1.record()
                     evs.append((e0, e1))
                 torch.cuda.synchronize()
                 ms = np.array([a.elapsed_time(b) for a, b in evs])
                 balg = agg_bytes(n, nnz, f, elem)
-                r = dict(width=f, direction=direction, dtype=args.agg_dtype, avg_ms=float(ms.mean()), min_ms=float(ms.min()),
+                r = dict(width=f, row_stride=ld, direction=direction, dtype=args.agg_dtype, avg_ms=float(ms.mean()), min_ms=float(ms.min()),
                          geps=nnz * f / (ms.mean() * 1e-3) / 1e9, alg_gbs=balg / (ms.mean() * 1e-3) / 1e9,
                          frac_hbm=balg / (ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS)
                 log("agg %s f=%d %s: %.3f ms  %.0f GEPS  %.0f GB/s algorithmic (%.1f%% of 8 TB/s)"
@@ -352,7 +363,7 @@ def main():
         tg.manual_seed(args.seed)
         # slice rows start on 128-byte lines when they are at least one line wide (the aggregation
         # then walks the columns line by line), else on 16-byte vectors
-        lds = [-(-s // 32) * 32 if s >= 32 else -(-s // 4) * 4 for s in slices]
+        lds = [line_padded_ld(s, 4) for s in slices]
         xs = [torch.randn(n, ld, generator=tg, **f32) for ld in lds]
         ys = [torch.empty_like(x) for x in xs]
         A = [torch.randn(n_share, dims[l], generator=tg, **f32) for l in range(L)]
