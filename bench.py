@@ -24,6 +24,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+# The transform forms every fp32 product from six bf16 piece products on the bf16 matrix
+# instructions (narrow or short products stay on the fp32 instructions): its useful flops are
+# priced against a sixth of the bf16 rate.
+SPLIT_PEAK_TFLOPS = BF16_MFMA_PEAK_TFLOPS / 6.0
 
 
 def log(*a):
@@ -463,9 +468,15 @@ def main():
                     algorithmic_bytes_per_launch=balg, avg_launch_ms=dur_ms,
                     geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
     nn_tflops = flops_nn / (nn_ms * 1e-3) / 1e12 if nn_ms > 0 else None
-    roofline_nn = dict(bound="mfma", kernel="gemm_kernel (fp32 MFMA, all transform calls of a step)",
-                       achieved=nn_tflops, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
-                       frac=(nn_tflops / FP32_MFMA_PEAK_TFLOPS) if nn_tflops else None, traffic=None)
+    split_core = not os.environ.get("NTP_NN_CORE", "").startswith("f")
+    nn_peak = SPLIT_PEAK_TFLOPS if split_core else FP32_MFMA_PEAK_TFLOPS
+    roofline_nn = dict(bound="mfma",
+                       kernel=("gemm_split_kernel (fp32 products from bf16 pieces, 6 bf16 MFMA per product; "
+                               "peak = 2500/6) + gemm_kernel (fp32 MFMA) for narrow products, all transform calls of a step"
+                               if split_core else "gemm_kernel (fp32 MFMA, all transform calls of a step)"),
+                       achieved=nn_tflops, peak=nn_peak, unit="TFLOP/s (useful fp32 flops)",
+                       frac=(nn_tflops / nn_peak) if nn_tflops else None,
+                       frac_of_fp32_mfma_peak=(nn_tflops / FP32_MFMA_PEAK_TFLOPS) if nn_tflops else None, traffic=None)
 
     # context, outside the timed region: the same model in the paper's decoupled order
     # (all transforms first, then L aggregations at the output width, Section 4.1)

@@ -12,9 +12,20 @@
 // dW contracts over the vertices: the rows are split over blocks, each block writes an
 // fp32 partial [K x M] to the caller's workspace and a second kernel adds them in order
 // (deterministic, no atomics).
+//
+// Two multiply cores share that skeleton:
+//   * fp32 MFMA (v_mfma_f32_32x32x2_f32), the plain form;
+//   * split bf16 MFMA (v_mfma_f32_32x32x16_bf16), the default: every fp32 operand element
+//     is cut into three bf16 pieces hi + mid + lo = x (exact: 3 x 8 significant bits, by
+//     truncation) on its way into LDS, and a product a*b is formed as the six piece
+//     products of weight >= 2^-16 (hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi), each exact
+//     in the fp32 accumulator's input; the dropped pieces are below 2^-23 |a b|.  Six bf16
+//     instructions cost 6 x 32 cycles per 32x32x16 block against 8 x 64 for fp32, and
+//     operands that are bf16 in memory need one piece only.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "ntp_internal.h"
 
@@ -23,6 +34,31 @@ namespace ntp {
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// pieces an element of type T is cut into for the bf16 core
+template <class T> struct Pieces { static constexpr int n = 3; };
+template <> struct Pieces<unsigned short> { static constexpr int n = 1; };
+
+// x = sum of NP bf16 values, each returned as an fp32 bit pattern whose low half is zero
+// (NP = 1: x is a bf16 value already)
+template <int NP>
+__device__ __forceinline__ void split_bf16(float x, unsigned (&piece)[NP]) {
+    if constexpr (NP == 1) {
+        piece[0] = __float_as_uint(x);
+    } else {
+        const unsigned hi = __float_as_uint(x) & 0xffff0000u;
+        const float r1 = x - __uint_as_float(hi);                 // exact: at most 16 significant bits left
+        const unsigned mid = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(mid);               // exact: at most 8 significant bits left
+        piece[0] = hi; piece[1] = mid; piece[2] = __float_as_uint(r2);
+    }
+}
+// bf16 pair in one dword: low half = piece of the even contraction index, high half = odd
+__device__ __forceinline__ unsigned pack_pair(unsigned even, unsigned odd) {
+    return __builtin_amdgcn_perm(odd, even, 0x07060302u);
+}
 
 constexpr int BK = 32;
 constexpr int NTHREADS = 256;
@@ -69,11 +105,41 @@ __device__ __forceinline__ void load4(const unsigned short* p, float (&v)[4]) {
     v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
 }
 
+// Four consecutive elements of row `row` starting at column `col` of a row-major source,
+// as floats; elements outside [0,row_lim) x [0,col_lim) read as zero.  With a mask, an
+// element is kept only where the mask element is > 0.
+template <class T, bool MASK>
+__device__ __forceinline__ void load_vec4(const T* __restrict__ src, const T* __restrict__ mask, int64_t ld,
+                                          int64_t row, int64_t col, int64_t row_lim, int64_t col_lim, bool vec_ok,
+                                          float (&out)[4]) {
+    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    if (row < row_lim && col < col_lim) {
+        const T* p = src + row * ld + col;
+        if (vec_ok && col + 3 < col_lim) {
+            load4(p, x);
+            if constexpr (MASK) {
+                float m[4];
+                load4(mask + row * ld + col, m);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = m[e] > 0.f ? x[e] : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < col_lim) {
+                    float t = elem_to_f32(p[e]);
+                    if constexpr (MASK) t = elem_to_f32(mask[row * ld + col + e]) > 0.f ? t : 0.f;
+                    x[e] = t;
+                }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[e] = x[e];
+}
+
 // Fetch this thread's share of a tile into registers.
 //   KCONTIG: tile element (mn, kk) at src[(mn0+mn)*ld + k0+kk]  (rows = mn, 4 consecutive kk per vector)
 //   else   : tile element (mn, kk) at src[(k0+kk)*ld + mn0+mn]  (rows = kk, 4 consecutive mn per vector)
-// Elements outside [0,mn_lim) x [0,k_lim) read as zero.  With a mask, an element is kept
-// only where the mask element is > 0.
 template <class T, bool KCONTIG, bool MASK, int TILE_MN>
 __device__ __forceinline__ void fetch_tile(const T* __restrict__ src, const T* __restrict__ mask, int64_t ld,
                                            int64_t mn0, int64_t k0, int64_t mn_lim, int64_t k_lim, bool vec_ok,
@@ -84,33 +150,8 @@ __device__ __forceinline__ void fetch_tile(const T* __restrict__ src, const T* _
     for (int v = 0; v < NV; ++v) {
         const int idx = threadIdx.x + NTHREADS * v;
         const int r = idx / VPR, c4 = (idx % VPR) * 4;
-        const int64_t row = (KCONTIG ? mn0 : k0) + r;
-        const int64_t col = (KCONTIG ? k0 : mn0) + c4;
-        const int64_t row_lim = KCONTIG ? mn_lim : k_lim;
-        const int64_t col_lim = KCONTIG ? k_lim : mn_lim;
-        float x[4] = {0.f, 0.f, 0.f, 0.f};
-        if (row < row_lim && col < col_lim) {
-            const T* p = src + row * ld + col;
-            if (vec_ok && col + 3 < col_lim) {
-                load4(p, x);
-                if constexpr (MASK) {
-                    float m[4];
-                    load4(mask + row * ld + col, m);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] = m[e] > 0.f ? x[e] : 0.f;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (col + e < col_lim) {
-                        float t = elem_to_f32(p[e]);
-                        if constexpr (MASK) t = elem_to_f32(mask[row * ld + col + e]) > 0.f ? t : 0.f;
-                        x[e] = t;
-                    }
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) regs[v][e] = x[e];
+        load_vec4<T, MASK>(src, mask, ld, (KCONTIG ? mn0 : k0) + r, (KCONTIG ? k0 : mn0) + c4,
+                           KCONTIG ? mn_lim : k_lim, KCONTIG ? k_lim : mn_lim, vec_ok, regs[v]);
     }
 }
 
@@ -138,6 +179,41 @@ template <bool KCONTIG, int TILE_MN> struct LdsStride {
     static constexpr int value = KCONTIG ? TILE_MN + 1 : TILE_MN + 4;
 };
 
+// block id -> (row tile, column tile, split); false for the padding blocks of the last group
+__device__ __forceinline__ bool block_to_tile(const GemmArgs& g, int& bx, int& by, int& bz) {
+    const int n_major = g.share_splits ? g.n_splits : g.tiles_m;
+    const int n_minor = g.share_splits ? g.tiles_m * g.tiles_n : g.tiles_n;
+    const int id = (int)blockIdx.x;
+    const int grp = id / (8 * n_minor), r = id % (8 * n_minor);
+    const int minor = r / 8, major = grp * 8 + r % 8;
+    if (major >= n_major) return false;
+    if (g.share_splits) { bz = major; bx = minor % g.tiles_m; by = minor / g.tiles_m; }
+    else { bz = 0; bx = major; by = minor; }
+    return true;
+}
+
+// epilogue: element e of a 32x32 accumulator sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+template <class TC, int TM, int TN>
+__device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc)[TM][TN], int bz,
+                                           int64_t row0, int64_t col0, int lane) {
+    TC* C = static_cast<TC*>(g.C) + (int64_t)bz * g.c_split_stride;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = col0 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int64_t row = row0 + i * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4);
+                if (row < g.Mdim && col < g.Ndim) {
+                    float v = acc[i][j][e];
+                    if (g.relu) v = v > 0.f ? v : 0.f;
+                    store_elem(C + row * g.ldc + col, v);
+                }
+            }
+        }
+}
+
 // C[Mdim x Ndim] (+split) = Aop * Bop, tiles BM x BN, WM x WN wavefronts.
 template <class TA, class TB, class TC, bool A_KCONTIG, bool B_KCONTIG, bool MASK_A, bool MASK_B,
           int BM, int BN, int WM, int WN>
@@ -153,16 +229,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(const GemmArgs g) {
     const int wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave % WN;
     int bx, by, bz;
-    {
-        const int n_major = g.share_splits ? g.n_splits : g.tiles_m;
-        const int n_minor = g.share_splits ? g.tiles_m * g.tiles_n : g.tiles_n;
-        const int id = (int)blockIdx.x;
-        const int grp = id / (8 * n_minor), r = id % (8 * n_minor);
-        const int minor = r / 8, major = grp * 8 + r % 8;
-        if (major >= n_major) return;              // padding of the last group of eight
-        if (g.share_splits) { bz = major; bx = minor % g.tiles_m; by = minor / g.tiles_m; }
-        else { bz = 0; bx = major; by = minor; }
-    }
+    if (!block_to_tile(g, bx, by, bz)) return;     // padding of the last group of eight
     const int64_t m0 = (int64_t)bx * BM;
     const int64_t n0 = (int64_t)by * BN;
     const int64_t kbeg = (int64_t)bz * g.k_per_split;
@@ -215,23 +282,328 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(const GemmArgs g) {
         }
     }
 
-    // epilogue: element e of a 32x32 accumulator sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
-    TC* C = static_cast<TC*>(g.C) + (int64_t)bz * g.c_split_stride;
+    store_tile<TC, TM, TN>(g, acc, bz, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane);
+}
+
+// ---- the split-bf16 core -----------------------------------------------------------------
+// LDS holds, per operand and piece, P[g][mn] = four dwords = the eight bf16 of contraction
+// indices 8g .. 8g+7 of tile row/column mn (g = 0..BK/8-1).  A lane of the 32x32x16
+// instruction (mn = lane % 32, h = lane / 32) needs exactly such a 16-byte group
+// (g = 2c + h in chunk c), so a fragment is one ds_read_b128 and consecutive lanes read
+// consecutive 16 bytes.
+//
+// Operand loaders.  Each thread owns whole items of the tile:
+//   contraction-contiguous source (memory rows run along k): an item = 4 consecutive k of
+//     one row mn = half a group, written with one 8-byte LDS store per piece;
+//   otherwise (memory rows run along mn): an item = 8 contraction rows x 2 adjacent mn =
+//     two whole groups, loaded with eight 8-byte reads that are contiguous across the lanes.
+// fetch<true> is the interior form: no bounds checks and no branches (rows/columns beyond
+// the matrix are clamped to the last valid ones: what they produce lands only in output
+// rows/columns that are never stored), so the loads of two tiles can be in flight with
+// exact wait counts.  fetch<false> checks every element and reads zero outside.
+template <class T, bool KCONTIG, bool MASK, int TILE_MN> struct Loader;
+
+template <class T, bool MASK, int TILE_MN>
+struct Loader<T, true, MASK, TILE_MN> {
+    static constexpr int NI = TILE_MN * BK / 4 / NTHREADS;     // items per thread (all threads busy)
+    static constexpr int REGS = 4;
+    using Regs = float[NI][REGS];
+    static __device__ __forceinline__ bool can_be_fast(const void* src, const void* mask, int64_t ld, int64_t mn_lim) {
+        return mn_lim > 0 && ld % 4 == 0 && (uintptr_t)src % (4 * sizeof(T)) == 0 && (!MASK || (uintptr_t)mask % (4 * sizeof(T)) == 0);
+    }
+    template <bool FAST>
+    static __device__ __forceinline__ void fetch(const T* __restrict__ src, const T* __restrict__ mask, int64_t ld,
+                                                 int64_t mn0, int64_t k0, int64_t mn_lim, int64_t k_lim, Regs& regs) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int v = 0; v < NI; ++v) {
+            const int idx = threadIdx.x + NTHREADS * v;
+            const int r = idx / (BK / 4), c4 = (idx % (BK / 4)) * 4;
+            if constexpr (FAST) {
+                int64_t row = mn0 + r;
+                row = row < mn_lim ? row : mn_lim - 1;
+                const int64_t off = row * ld + k0 + c4;
+                load4(src + off, regs[v]);
+                if constexpr (MASK) {
+                    float m[4];
+                    load4(mask + off, m);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = n0 + wn * (TN * 32) + j * 32 + (lane & 31);
+                    for (int e = 0; e < 4; ++e) regs[v][e] = m[e] > 0.f ? regs[v][e] : 0.f;
+                }
+            } else {
+                const bool vec_ok = ld % 4 == 0 && (uintptr_t)src % (4 * sizeof(T)) == 0 && (!MASK || (uintptr_t)mask % (4 * sizeof(T)) == 0);
+                load_vec4<T, MASK>(src, mask, ld, mn0 + r, k0 + c4, mn_lim, k_lim, vec_ok, regs[v]);
+            }
+        }
+    }
+    template <int NP, int LD>
+    static __device__ __forceinline__ void stash(uint4 (*dst)[BK / 8][LD], const Regs& regs) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t row = m0 + wm * (TM * 32) + i * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4);
-                if (row < g.Mdim && col < g.Ndim) {
-                    float v = acc[i][j][e];
-                    if (g.relu) v = v > 0.f ? v : 0.f;
-                    store_elem(C + row * g.ldc + col, v);
+        for (int v = 0; v < NI; ++v) {
+            const int idx = threadIdx.x + NTHREADS * v;
+            const int r = idx / (BK / 4), q = idx % (BK / 4);       // q-th group of four k: half of group q/2
+            unsigned x[4][NP];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) split_bf16<NP>(regs[v][e], x[e]);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                unsigned* g4 = reinterpret_cast<unsigned*>(&dst[p][q / 2][r]);
+                *reinterpret_cast<uint2*>(g4 + 2 * (q % 2)) = make_uint2(pack_pair(x[0][p], x[1][p]), pack_pair(x[2][p], x[3][p]));
+            }
+        }
+    }
+};
+
+template <class T, bool MASK, int TILE_MN>
+struct Loader<T, false, MASK, TILE_MN> {
+    static constexpr int ITEMS = (BK / 8) * (TILE_MN / 2);
+    static constexpr int NI = (ITEMS + NTHREADS - 1) / NTHREADS;
+    static constexpr bool ALL = ITEMS % NTHREADS == 0;
+    static constexpr int REGS = 16;                               // [8 contraction rows][2 mn]
+    using Regs = float[NI][REGS];
+    static __device__ __forceinline__ bool can_be_fast(const void* src, const void* mask, int64_t ld, int64_t mn_lim) {
+        return mn_lim >= 2 && mn_lim % 2 == 0 && ld % 2 == 0 && (uintptr_t)src % (2 * sizeof(T)) == 0 &&
+               (!MASK || (uintptr_t)mask % (2 * sizeof(T)) == 0);
+    }
+    static __device__ __forceinline__ void load2(const float* p, float& a, float& b) {
+        const float2 t = *reinterpret_cast<const float2*>(p);
+        a = t.x; b = t.y;
+    }
+    static __device__ __forceinline__ void load2(const unsigned short* p, float& a, float& b) {
+        const unsigned t = *reinterpret_cast<const unsigned*>(p);
+        a = __uint_as_float(t << 16); b = __uint_as_float(t & 0xffff0000u);
+    }
+    template <bool FAST>
+    static __device__ __forceinline__ void fetch(const T* __restrict__ src, const T* __restrict__ mask, int64_t ld,
+                                                 int64_t mn0, int64_t k0, int64_t mn_lim, int64_t k_lim, Regs& regs) {
+#pragma unroll
+        for (int u = 0; u < NI; ++u) {
+            const int idx = threadIdx.x + NTHREADS * u;
+            const int g = idx / (TILE_MN / 2), m2 = (idx % (TILE_MN / 2)) * 2;
+            if (ALL || idx < ITEMS) {
+                if constexpr (FAST) {
+                    int64_t col = mn0 + m2;
+                    col = col < mn_lim ? col : mn_lim - 2;
+                    const T* p = src + (k0 + 8 * g) * ld + col;
+                    const T* pm = MASK ? mask + (k0 + 8 * g) * ld + col : nullptr;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        load2(p + j * ld, regs[u][2 * j], regs[u][2 * j + 1]);
+                        if constexpr (MASK) {
+                            float ma, mb;
+                            load2(pm + j * ld, ma, mb);
+                            regs[u][2 * j] = ma > 0.f ? regs[u][2 * j] : 0.f;
+                            regs[u][2 * j + 1] = mb > 0.f ? regs[u][2 * j + 1] : 0.f;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            const int64_t row = k0 + 8 * g + j, col = mn0 + m2 + e;
+                            float t = 0.f;
+                            if (row < k_lim && col < mn_lim) {
+                                t = elem_to_f32(src[row * ld + col]);
+                                if constexpr (MASK) t = elem_to_f32(mask[row * ld + col]) > 0.f ? t : 0.f;
+                            }
+                            regs[u][2 * j + e] = t;
+                        }
                 }
             }
         }
+    }
+    template <int NP, int LD>
+    static __device__ __forceinline__ void stash(uint4 (*dst)[BK / 8][LD], const Regs& regs) {
+#pragma unroll
+        for (int u = 0; u < NI; ++u) {
+            const int idx = threadIdx.x + NTHREADS * u;
+            const int g = idx / (TILE_MN / 2), m2 = (idx % (TILE_MN / 2)) * 2;
+            if (ALL || idx < ITEMS) {
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    unsigned x[8][NP];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) split_bf16<NP>(regs[u][2 * j + e], x[j]);
+#pragma unroll
+                    for (int p = 0; p < NP; ++p)
+                        dst[p][g][m2 + e] = make_uint4(pack_pair(x[0][p], x[1][p]), pack_pair(x[2][p], x[3][p]),
+                                                       pack_pair(x[4][p], x[5][p]), pack_pair(x[6][p], x[7][p]));
+                }
+            }
+        }
+    }
+};
+
+// Scheduling hint for one pipelined step: after the first fragment reads, every matrix
+// instruction is followed by a few vector instructions of the stash (and now and then an LDS
+// write or a fragment read of the next chunk), so that the matrix pipe runs while the vector
+// pipe cuts the next tile into pieces.
+template <int N, int VALU_PER_MFMA, int DS_READS_FIRST>
+__device__ __forceinline__ void interleave_hint() {
+    if constexpr (N > 0) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);   // vector ALU
+        if constexpr (N % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // an LDS write
+        if constexpr (N % 2 == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // an LDS read
+        interleave_hint<N - 1, VALU_PER_MFMA, DS_READS_FIRST>();
+    }
+}
+
+// LDS bytes of the split kernel: two buffers of (pieces x BK/8 groups x padded tile) 16-byte groups
+template <class TA, class TB, int BM, int BN>
+constexpr int split_lds_bytes() {
+    return 2 * (BK / 8) * 16 * (Pieces<TA>::n * (BM + 4) + Pieces<TB>::n * (BN + 4));
+}
+
+// One block per compute unit (the two LDS buffers take 100-126 KB for fp32 operands).  In
+// step s a wavefront multiplies the tile in buffer s%2 while it cuts tile s+1 (already in
+// registers) into pieces and writes it to the other buffer, and tile s+2 is on its way from
+// memory: matrix instructions, vector arithmetic, LDS and memory traffic of three tiles
+// overlap inside every wavefront, with one barrier per step.
+template <class TA, class TB, class TC, bool A_KCONTIG, bool B_KCONTIG, bool MASK_A, bool MASK_B,
+          int BM, int BN, int WM, int WN>
+__global__ void __launch_bounds__(NTHREADS) gemm_split_kernel(const GemmArgs g) {
+    static_assert(WM * WN == 4, "four wavefronts per block");
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int NPA = Pieces<TA>::n, NPB = Pieces<TB>::n;
+    // row stride in 16-byte groups: 4 mod 16 spreads the 8-byte stores of a contraction-
+    // contiguous source (4 rows x 4 groups x 2 halves per 32 lanes) over all banks
+    constexpr int LDA_S = BM + 4, LDB_S = BN + 4;
+    extern __shared__ uint4 smem[];
+    typedef uint4 (*TileA)[BK / 8][LDA_S];
+    typedef uint4 (*TileB)[BK / 8][LDB_S];
+    const TileA As0 = reinterpret_cast<TileA>(smem), As1 = As0 + NPA;
+    const TileB Bs0 = reinterpret_cast<TileB>(As1 + NPA), Bs1 = Bs0 + NPB;
+    using LA = Loader<TA, A_KCONTIG, MASK_A, BM>;
+    using LB = Loader<TB, B_KCONTIG, MASK_B, BN>;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    int bx, by, bz;
+    if (!block_to_tile(g, bx, by, bz)) return;     // padding of the last group of eight
+    const int64_t m0 = (int64_t)bx * BM;
+    const int64_t n0 = (int64_t)by * BN;
+    const int64_t kbeg = (int64_t)bz * g.k_per_split;
+    const int64_t kend = kbeg + g.k_per_split < g.Kdim ? kbeg + g.k_per_split : g.Kdim;
+
+    const TA* A = static_cast<const TA*>(g.A);
+    const TB* B = static_cast<const TB*>(g.B);
+    const TA* mA = static_cast<const TA*>(g.maskA);
+    const TB* mB = static_cast<const TB*>(g.maskB);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int mn_a = wm * (TM * 32) + (lane & 31);
+    const int mn_b = wn * (TN * 32) + (lane & 31);
+    const int h = lane >> 5;
+    // multiply the tile held in (as, bs) into the accumulators
+    auto multiply = [&](TileA as, TileB bs) {
+#pragma unroll
+        for (int c = 0; c < BK / 16; ++c) {
+            uint4 a[TM][NPA], b[TN][NPB];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int p = 0; p < NPA; ++p) a[i][p] = as[p][2 * c + h][mn_a + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int p = 0; p < NPB; ++p) b[j][p] = bs[p][2 * c + h][mn_b + j * 32];
+            // piece products of weight 2^-8w, small ones first; consecutive instructions go to
+            // different accumulators so that none waits for its predecessor
+#pragma unroll
+            for (int w = 2; w >= 0; --w)
+#pragma unroll
+                for (int pa = 0; pa <= w; ++pa)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const int pb = w - pa;
+                            if (pa < NPA && pb < NPB)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                    __builtin_bit_cast(bf16x8, a[i][pa < NPA ? pa : 0]), __builtin_bit_cast(bf16x8, b[j][pb < NPB ? pb : 0]), acc[i][j], 0, 0, 0);
+                        }
+        }
+    };
+    auto stash = [&](TileA as, TileB bs, const typename LA::Regs& ra, const typename LB::Regs& rb) {
+        LA::template stash<NPA, LDA_S>(as, ra);
+        LB::template stash<NPB, LDB_S>(bs, rb);
+    };
+
+    int64_t k0 = kbeg;
+    const bool fast = LA::can_be_fast(A, mA, g.lda, g.Mdim) && LB::can_be_fast(B, mB, g.ldb, g.Ndim);
+    if (fast && kend - kbeg >= 2 * BK) {
+        // An even number of whole steps.  Every fetch is issued unconditionally (past the end
+        // it re-reads a tile already taken, and what is stashed from it is never multiplied)
+        // so that the number of loads in flight is known at compile time and a stash waits
+        // only for its own tile; the scheduling fences keep the loads in program order, which
+        // the wait counts rely on.
+        const int64_t npipe = (kend - kbeg) / BK / 2 * 2;
+        constexpr int N_PROD = NPA == 3 && NPB == 3 ? 6 : (NPA == 1 && NPB == 1 ? 1 : 3);
+        constexpr int N_MFMA = (BK / 16) * TM * TN * N_PROD;           // matrix instructions per step
+        constexpr int FIRST_READS = TM * NPA + TN * NPB;               // fragment reads of the first chunk
+        constexpr int VALU_PER_MFMA = (LA::NI * LA::REGS * (4 * NPA - 2) + LB::NI * LB::REGS * (4 * NPB - 2)) / N_MFMA + 1;
+        typename LA::Regs ra0, ra1;
+        typename LB::Regs rb0, rb1;
+        auto fetch = [&](int64_t s, typename LA::Regs& ra, typename LB::Regs& rb) {
+            LA::template fetch<true>(A, mA, g.lda, m0, kbeg + s * BK, g.Mdim, kend, ra);
+            LB::template fetch<true>(B, mB, g.ldb, n0, kbeg + s * BK, g.Ndim, kend, rb);
+        };
+        fetch(0, ra0, rb0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(1, ra1, rb1);
+        __builtin_amdgcn_sched_barrier(0);
+        stash(As0, Bs0, ra0, rb0);
+        __syncthreads();
+        for (int64_t s = 0; s < npipe; s += 2) {
+            fetch(s + 2 < npipe ? s + 2 : s, ra0, rb0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(As0, Bs0);                 // tile s
+            stash(As1, Bs1, ra1, rb1);          // tile s+1
+            __builtin_amdgcn_sched_group_barrier(0x100, FIRST_READS, 0);
+            interleave_hint<N_MFMA, VALU_PER_MFMA, FIRST_READS>();
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            fetch(s + 3 < npipe ? s + 3 : s + 1, ra1, rb1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(As1, Bs1);                 // tile s+1
+            stash(As0, Bs0, ra0, rb0);          // tile s+2 (not used after the last step)
+            __builtin_amdgcn_sched_group_barrier(0x100, FIRST_READS, 0);
+            interleave_hint<N_MFMA, VALU_PER_MFMA, FIRST_READS>();
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        }
+        k0 = kbeg + npipe * BK;
+    }
+    // what is left (an odd whole step, a partial last step, or everything when the operands
+    // are not aligned for the interior form): checked loads, one buffer, next tile fetched
+    // while this one is multiplied
+    if (k0 < kend) {
+        typename LA::Regs ra;
+        typename LB::Regs rb;
+        LA::template fetch<false>(A, mA, g.lda, m0, k0, g.Mdim, kend, ra);
+        LB::template fetch<false>(B, mB, g.ldb, n0, k0, g.Ndim, kend, rb);
+        for (; k0 < kend; k0 += BK) {
+            __syncthreads();
+            stash(As0, Bs0, ra, rb);
+            __syncthreads();
+            if (k0 + BK < kend) {
+                LA::template fetch<false>(A, mA, g.lda, m0, k0 + BK, g.Mdim, kend, ra);
+                LB::template fetch<false>(B, mB, g.ldb, n0, k0 + BK, g.Ndim, kend, rb);
+            }
+            multiply(As0, Bs0);
+        }
+    }
+
+    store_tile<TC, TM, TN>(g, acc, bz, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane);
 }
 
 // out[i] = sum over the splits of part[s * stride + i].  A block owns 64 consecutive
@@ -277,6 +649,15 @@ __global__ void __launch_bounds__(256) relu_kernel(const T* __restrict__ dh, T* 
     }
 }
 
+// NTP_NN_CORE=fp32 selects the plain fp32 MFMA core (for comparison); default is the split-bf16 core
+bool use_split_core() {
+    static const bool v = [] {
+        const char* e = getenv("NTP_NN_CORE");
+        return !(e && e[0] == 'f');
+    }();
+    return v;
+}
+
 template <class TA, class TB, class TC, bool AK, bool BKC, bool MA, bool MB, int BM, int BN, int WM, int WN>
 void launch_tiles(GemmArgs g, int n_splits, hipStream_t st) {
     g.tiles_m = (int)((g.Mdim + BM - 1) / BM);
@@ -286,7 +667,21 @@ void launch_tiles(GemmArgs g, int n_splits, hipStream_t st) {
     const int64_t n_major = g.share_splits ? n_splits : g.tiles_m;
     const int64_t n_minor = g.share_splits ? (int64_t)g.tiles_m * g.tiles_n : g.tiles_n;
     const int64_t blocks = (n_major + 7) / 8 * 8 * n_minor;
-    hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>), dim3((unsigned)blocks), dim3(NTHREADS), 0, st, g);
+    // The split core pays off when a block runs several whole contraction steps through its
+    // two-buffer pipeline and the output tile is wide enough to be compute bound; short
+    // contractions and narrow outputs (memory bound) stay on the plain core.  bf16 operands
+    // need one piece product only and always take the bf16 instructions.
+    const int64_t k_len = std::min<int64_t>(g.k_per_split, g.Kdim);
+    const bool split_pays = sizeof(TA) == 2 || (k_len >= 4 * BK && BN >= 128);
+    if (use_split_core() && split_pays) {
+        constexpr int lds = split_lds_bytes<TA, TB, BM, BN>();
+        auto kernel = gemm_split_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)attr;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(NTHREADS), lds, st, g);
+    } else
+        hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>), dim3((unsigned)blocks), dim3(NTHREADS), 0, st, g);
 }
 
 template <class TA, class TB, class TC, bool AK, bool BKC, bool MA, bool MB>

@@ -140,3 +140,33 @@ def test_relu_alone(n, f, ld, dtype):
     want_dz = np.zeros_like(dhv)
     want_dz[:, :f] = np.where(hv[:, :f] > 0, dhv[:, :f], 0)
     assert np.array_equal(back(dZ), want_dz)
+
+
+@pytest.mark.parametrize("n,k,m", [(2048, 1024, 256), (1111, 160, 130), (3000, 130, 256), (5000, 512, 192)])
+def test_wide_dynamic_range_keeps_fp32_accuracy(n, k, m):
+    """Operands whose magnitudes span six decades: the transform (whose default core forms
+    fp32 products from bf16 pieces) must stay at fp32-class accuracy, far inside the
+    tolerance: every piece product that matters at 2^-23 has to be there."""
+    import torch
+    from gpu_util import dev_f32
+    from helpers import rel_errors
+    say("nn dynamic range", n, k, m)
+    rng = gen.stream_rng(n + k + m, 77)
+    A = (gen.normal_features(n, k, seed=k) * 10.0 ** rng.uniform(-3, 3, size=(n, k))).astype(np.float32)
+    W = (gen.glorot_weight(k, m, seed=m) * 10.0 ** rng.uniform(-3, 3, size=(k, m))).astype(np.float32)
+    dH = (gen.normal_features(n, m, seed=9, stream=6) * 10.0 ** rng.uniform(-3, 3, size=(n, m))).astype(np.float32)
+    H = torch.full((n, m), float("nan"), device="cuda:0")
+    ntp.ntp_nn_fwd(dev_f32(A), dev_f32(W), H, n, k, m, ntp.NTP_ACT_NONE)
+    dA = torch.full((n, k), float("nan"), device="cuda:0")
+    dW = torch.full((k, m), float("nan"), device="cuda:0")
+    wsb = ntp.ntp_nn_bwd_workspace_bytes(n, k, m)
+    ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device="cuda:0")
+    ntp.ntp_nn_bwd(dev_f32(A), dev_f32(W), H, dev_f32(dH), dA, dW, n, k, m, ntp.NTP_ACT_NONE, ntp.NTP_F32, ws, wsb)
+    torch.cuda.synchronize()
+    A64, W64, dH64 = A.astype(np.float64), W.astype(np.float64), dH.astype(np.float64)
+    for name, got, ref, scale in (("H", H, A64 @ W64, _abs_scale(A, W)),
+                                  ("dA", dA, dH64 @ W64.T, _abs_scale(dH, W.T)),
+                                  ("dW", dW, A64.T @ dH64, _abs_scale(A.T, dH))):
+        norm, comp, _ = rel_errors(got.cpu().numpy(), ref, scale)
+        say("   %s: normwise %.2e componentwise %.2e" % (name, norm, comp))
+        assert comp <= 2e-6 and norm <= 2e-6, name
