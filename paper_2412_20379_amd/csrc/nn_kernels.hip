@@ -676,9 +676,13 @@ void launch_tiles(GemmArgs g, int n_splits, hipStream_t st) {
     if (use_split_core() && split_pays) {
         constexpr int lds = split_lds_bytes<TA, TB, BM, BN>();
         auto kernel = gemm_split_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>;
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        (void)attr;
+        static bool allowed[64] = {};          // per device: the kernel may use more than 64 KB of LDS
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        if (dev >= 0 && dev < 64 && !allowed[dev]) {
+            allowed[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
+        }
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(NTHREADS), lds, st, g);
     } else
         hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>), dim3((unsigned)blocks), dim3(NTHREADS), 0, st, g);
@@ -706,8 +710,10 @@ int dw_splits(int64_t n, int64_t k, int64_t m) {
     const int64_t bm = m > 64 ? 128 : 256;
     const int64_t bn = m > 64 ? 128 : (m > 32 ? 64 : 32);
     const int64_t tiles = ((k + bm - 1) / bm) * ((m + bn - 1) / bn);
-    // one round of blocks at three blocks per compute unit (256 CUs): no partial last round
-    int64_t s = std::max<int64_t>(1, 768 / tiles);
+    // one round of blocks: one block per compute unit (256 CUs) for the 128-wide tiles of the
+    // split core (its two LDS buffers fill a CU), two per CU for the narrow tiles of the fp32 core
+    const int64_t target = (m > 64 && use_split_core()) ? 256 : 512;
+    int64_t s = std::max<int64_t>(1, target / tiles);
     const int64_t max_s = std::max<int64_t>(1, n / (BK * 8));
     s = std::max<int64_t>(1, std::min(s, max_s));
     return (int)std::min<int64_t>(s, 1024);
