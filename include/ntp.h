@@ -187,9 +187,11 @@ int ntp_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int6
 /*
  * Gradients of the dense transform (UPDATE in the reverse loop of Alg. 1):
  *   dZ = dH * 1[H > 0] for NTP_ACT_RELU (else dH);  dW = A^T dZ [k x m] (overwritten, always
- *   fp32);  dA = dZ W^T [n x k] (skipped when dA is NULL).
+ *   fp32; skipped when dW is NULL);  dA = dZ W^T [n x k] (skipped when dA is NULL).  At least
+ *   one of the two must be given: a caller may ask for them in two calls on two streams, e.g.
+ *   dA on the stream that continues with the backward aggregation and dW beside it.
  * workspace: device scratch of at least ntp_nn_bwd_workspace_bytes(n,k,m) bytes, caller
- * owned (holds the partial sums of the reduction over n).
+ * owned (holds the partial sums of the reduction over n; not needed when dW is NULL).
  */
 int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH,
                void* dA, float* dW, int64_t n, int64_t k, int64_t m,

@@ -746,6 +746,7 @@ int nn_bwd_t(const void* A, const void* W, const void* H, const void* dH, void* 
                   : launch_gemm<T, T, T, true, true, false, false>(g, 1, st);
         if (rc != NTP_OK) return rc;
     }
+    if (!dW) return NTP_OK;
     // dW[k x m] = A^T[k x n] * dZ[n x m] : contraction over the vertices, split over blocks
     const int S = dw_splits(n, k, m);
     GemmArgs g{};
@@ -808,6 +809,7 @@ int launch_nn_bwd(const void* A, const void* W, const void* H, const void* dH, v
                   void* workspace, int64_t, void* stream) {
     hipStream_t st = (hipStream_t)stream;
     if (n == 0) {   // nothing to contract over: dW = 0 (a fill kernel, not a memset node)
+        if (!dW) return NTP_OK;
         const int64_t count = k * m;
         hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st,
                            (const float*)nullptr, dW, count, count, 0);

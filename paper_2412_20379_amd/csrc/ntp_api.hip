@@ -511,11 +511,11 @@ int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH, void
                int64_t n, int64_t k, int64_t m, int act, int dtype,
                void* workspace, int64_t workspace_bytes, void* stream) {
     if (n < 0 || k < 1 || m < 1 || k > 65536 || m > 65536) { set_error("bad transform shape n=%lld k=%lld m=%lld", (long long)n, (long long)k, (long long)m); return NTP_EINVAL; }
-    if (!dW) { set_error("dW is NULL"); return NTP_EINVAL; }
+    if (!dW && !dA) { set_error("dW and dA are both NULL: nothing to compute"); return NTP_EINVAL; }
     if (n > 0 && (!A || !dH || (dA && !W) || (act == NTP_ACT_RELU && !H))) { set_error("NULL buffer"); return NTP_EINVAL; }
     if (act != NTP_ACT_NONE && act != NTP_ACT_RELU) { set_error("unknown activation %d", act); return NTP_EINVAL; }
     if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
-    if (workspace_bytes < nn_bwd_workspace_bytes(n, k, m) || (!workspace && nn_bwd_workspace_bytes(n, k, m) > 0)) {
+    if (dW && (workspace_bytes < nn_bwd_workspace_bytes(n, k, m) || (!workspace && nn_bwd_workspace_bytes(n, k, m) > 0))) {
         set_error("workspace too small: need %lld bytes", (long long)nn_bwd_workspace_bytes(n, k, m));
         return NTP_EINVAL;
     }

@@ -26,8 +26,12 @@ class GcnEpoch:
                                activation); the others stay aggregate-first.
     """
 
-    def __init__(self, graph: ntp.Graph, n: int, dims, device="cuda:0", order="layerwise", chunked=False):
+    def __init__(self, graph: ntp.Graph, n: int, dims, device="cuda:0", order="layerwise", chunked=False,
+                 overlap_dw=False):
         self.g, self.n, self.dims, self.order, self.chunked = graph, n, tuple(dims), order, chunked
+        # overlap_dw: in the layer-wise backward, dW of a layer runs on a second stream beside
+        # dA and the backward aggregation that follows it (matrix cores beside the memory system)
+        self.overlap_dw = overlap_dw
         L = len(dims) - 1
         f32 = dict(dtype=torch.float32, device=device)
         # per layer: evaluate as sigma(A_hat (H W)) instead of sigma((A_hat H) W)?
@@ -44,12 +48,14 @@ class GcnEpoch:
         self.hid = [torch.empty(n, dims[l + 1], **f32) for l in range(L)]
         self.dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
         wmax = max(dims)
-        self.tmp = [torch.empty(n, wmax, **f32) for _ in range(2)]
+        self.tmp = [torch.empty(n, wmax, **f32) for _ in range(3 if overlap_dw else 2)]
         self.logits_buf = torch.empty(n, dims[-1], **f32) if order == "decoupled" else None
         ws = max(ntp.ntp_nn_bwd_workspace_bytes(n, dims[l], dims[l + 1]) for l in range(L))
         self.ws_bytes = ws
         self.ws = torch.empty(max(ws, 4), dtype=torch.uint8, device=device)
         self.copy_stream = torch.cuda.Stream(device=device) if chunked else None
+        self.dw_stream = torch.cuda.Stream(device=device) if overlap_dw else None
+        self.ws2 = torch.empty(max(ws, 4), dtype=torch.uint8, device=device) if overlap_dw else None
         self.loss = None
         self.logits = None
         self.events = None      # set to a list to collect (tag, start, end) HIP events per library call
@@ -68,7 +74,8 @@ class GcnEpoch:
         self._timed("nn_fwd %dx%d" % (a[4], a[5]), ntp.ntp_nn_fwd, *a)
 
     def _nn_bwd(self, *a):
-        self._timed("nn_bwd %dx%d%s" % (a[7], a[8], "" if a[4] is None else " +dA"), ntp.ntp_nn_bwd, *a)
+        tag = "nn_bwd %dx%d%s" % (a[7], a[8], "" if a[4] is None else (" +dA" if a[5] is not None else " dA only"))
+        self._timed(tag, ntp.ntp_nn_bwd, *a)
 
     def _agg(self, direction, src, dst, f):
         self._timed("agg_%s f=%d" % ("fwd" if direction == ntp.NTP_FWD else "bwd", f), self._agg_call, direction, src, dst, f)
@@ -126,9 +133,13 @@ class GcnEpoch:
             H = self.hid[l]
         self.logits = H
         dH = self._loss_grad(H, labels)
+        pending = None      # event of the last dW issued on the side stream
         for l in range(L - 1, -1, -1):
             last = l == L - 1
             if tf[l]:
+                if pending is not None:
+                    st.wait_event(pending)
+                    pending = None
                 if not last:       # dZ = dH * 1[H > 0], in place
                     self._timed("relu_bwd %d" % d[l + 1], ntp.ntp_relu_bwd, dH, self.hid[l], dH, n, d[l + 1], d[l + 1], ntp.NTP_F32, st)
                 dT = self.tbuf[l]  # dT = A_hat^T dZ at the output width; then dW = H_in^T dT, dH_in = dT W^T
@@ -137,14 +148,43 @@ class GcnEpoch:
                 self._nn_bwd(ins[l], Ws[l], self.hid[l], dT, dHin, self.dW[l], n, d[l], d[l + 1],
                              ntp.NTP_ACT_NONE, ntp.NTP_F32, self.ws, self.ws_bytes, st)
                 dH = dHin
+            elif self.overlap_dw and l > 0:
+                act = ntp.NTP_ACT_NONE if last else ntp.NTP_ACT_RELU
+                # dW beside dA + aggregation: the side stream reads dH, which therefore must not
+                # be overwritten before its event; three scratch buffers rotate
+                ready = torch.cuda.Event()
+                ready.record(st)
+                self.dw_stream.wait_event(ready)
+                ntp.ntp_nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, None, self.dW[l], n, d[l], d[l + 1], act,
+                               ntp.NTP_F32, self.ws2, self.ws_bytes, self.dw_stream)
+                done = torch.cuda.Event()
+                done.record(self.dw_stream)
+                used = {dH.data_ptr()} if any(dH.data_ptr() == t.data_ptr() for t in self.tmp) else set()
+                ia = next(i for i in range(3) if self.tmp[i].data_ptr() not in used)
+                dA = self._view(ia, d[l])
+                if pending is not None:        # the buffer of the previous layer's dH may be written now
+                    st.wait_event(pending)
+                self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, None, n, d[l], d[l + 1], act,
+                             ntp.NTP_F32, None, 0, st)
+                used.add(dA.data_ptr())
+                io = next(i for i in range(3) if self.tmp[i].data_ptr() not in used)
+                out = self._view(io, d[l])
+                self._agg(ntp.NTP_BWD, dA, out, d[l])
+                dH = out
+                pending = done
             else:
                 act = ntp.NTP_ACT_NONE if last else ntp.NTP_ACT_RELU
                 dA = self._other_view(dH, d[l]) if l > 0 else None
+                if pending is not None:
+                    st.wait_event(pending)
+                    pending = None
                 self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
                              ntp.NTP_F32, self.ws, self.ws_bytes, st)
                 if l > 0:
                     dH = self._other_view(dA, d[l])
                     self._agg(ntp.NTP_BWD, dA, dH, d[l])
+        if pending is not None:
+            st.wait_event(pending)
         return self.loss
 
     def _decoupled(self, X, Ws, labels):

@@ -16,7 +16,7 @@ def say(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False):
+def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, overlap_dw=False):
     import torch
     from paper_2412_20379_amd.gcn import GcnEpoch
     from gpu_util import dev_f32
@@ -32,7 +32,7 @@ def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False):
     X = gen.make_features(cfg, dims[0], seed=0, scale_down=scale)
     Ws = [gen.glorot_weight(dims[i], dims[i + 1], 0, i) for i in range(len(dims) - 1)]
     labels = gen.uniform_labels(n, dims[-1], 0)
-    ep = GcnEpoch(g, n, dims, order=order, chunked=chunked)
+    ep = GcnEpoch(g, n, dims, order=order, chunked=chunked, overlap_dw=overlap_dw)
     loss = ep.run(dev_f32(X), [dev_f32(w) for w in Ws], torch.from_numpy(labels.astype(np.int64)).to("cuda:0"))
     torch.cuda.synchronize()
     fn = ogcn.epoch_decoupled if order == "decoupled" else ogcn.epoch_layerwise
@@ -97,6 +97,13 @@ def test_epoch_config1_directed_scatter_backward():
 @pytest.mark.parametrize("order", ["layerwise", "decoupled", "reordered", "auto"])
 def test_epoch_config2(order):
     _run(2, order)
+
+
+@pytest.mark.parametrize("order", ["layerwise", "auto"])
+def test_epoch_config2_dw_on_a_second_stream(order):
+    """dW of a layer issued beside dA and the backward aggregation: same gradients"""
+    _run(2, order, overlap_dw=True)
+    _run(1, order, overlap_dw=True, directed=True)
 
 
 def test_epoch_auto_order_mixed_widths():
