@@ -9,8 +9,11 @@ import it; the product never does, and it imports nothing from the product.
 Pins (tests/test_oracle_pins.py): dense brute force on tiny graphs, the
 constant-vector closed form, the sqrt-degree fixed point, textbook graphs
 (empty, complete, star, ring), the adjoint identity on directed graphs,
-chunk/slice invariance, finite-difference gradients of the epoch loss, and a
-hand-derived fixture under tests/golden/.  No function here is unpinned.
+chunk/slice invariance, finite-difference gradients of the epoch loss, a
+hand-derived fixture under tests/golden/, and for the attention weights: rows
+summing to one, the slope-1 closed form, equal scores giving 1/degree, a dense
+brute force, and the transposed order against scipy's transpose.  No function
+here is unpinned.
 """
 from .graph import (  # noqa: F401
     Graph, Sparse, build_graph, plan_chunks,
@@ -21,6 +24,7 @@ from .aggregate import (  # noqa: F401
     chunked_aggregate, round_bf16, num_threads, build_native,
 )
 from .sampled import rows_from_undirected_edges  # noqa: F401
+from .attention import edge_softmax, leaky_relu, weighted  # noqa: F401
 from .gcn import (  # noqa: F401
     nn_fwd, nn_bwd, softmax_cross_entropy, epoch_layerwise, epoch_decoupled,
 )

@@ -1,0 +1,72 @@
+"""Oracle for GAT-style edge attention weights (TEST INFRASTRUCTURE).
+
+Follows the AGG step of GAT in Section 2.1 of the paper: for every in-edge u -> v of a
+vertex v (self loop included, as in eq. 1),
+
+    e(u -> v)     = LeakyReLU( a^T [W h_u || W h_v] ) = LeakyReLU( p[u] + q[v] )
+    alpha(u -> v) = exp(e(u -> v)) / sum_{u' in N_in(v)} exp(e(u' -> v))        (softmax over
+                                                                                 the in-edges of v)
+
+where p[u] = a_src . (W h_u) and q[v] = a_dst . (W h_v) are the two halves of the mapping
+a^T [. || .]; they are per-vertex scalars and are inputs here (they come out of a dense
+transform).  Section 4.1 computes these coefficients for all edges before the aggregation
+starts and then aggregates with them as edge weights, which is what `weighted` does.
+
+Plain numpy in fp64, one row at a time; no max-subtraction tricks beyond the textbook
+shift by the row maximum (which does not change the value of a softmax).
+"""
+from __future__ import annotations
+
+from dataclasses import replace
+
+import numpy as np
+
+from .graph import Graph, Sparse
+
+
+def leaky_relu(x, negative_slope: float):
+    x = np.asarray(x, dtype=np.float64)
+    return np.where(x > 0, x, negative_slope * x)
+
+
+def edge_softmax(g: Graph, p, q, negative_slope: float = 0.2):
+    """Attention weights of every stored entry of g.
+
+    Returns (alpha_in, alpha_out): float64 arrays in the entry order of g.csr (row v lists
+    its in-neighbours u: alpha_in[k] = alpha(u_k -> v)) and of g.csc (row u lists its
+    out-neighbours v: alpha_out[k] = alpha(u -> v_k), the same numbers transposed).
+    """
+    p = np.asarray(p, dtype=np.float64)
+    q = np.asarray(q, dtype=np.float64)
+    n = g.n
+    csr, csc = g.csr, g.csc
+    alpha_in = np.empty(csr.nnz, dtype=np.float64)
+    row_max = np.zeros(n, dtype=np.float64)
+    row_sum = np.ones(n, dtype=np.float64)
+    for v in range(n):
+        b, e = int(csr.rowptr[v]), int(csr.rowptr[v + 1])
+        if e == b:
+            continue
+        s = leaky_relu(p[csr.colidx[b:e]] + q[v], negative_slope)
+        m = s.max()
+        w = np.exp(s - m)
+        t = w.sum()
+        alpha_in[b:e] = w / t
+        row_max[v], row_sum[v] = m, t
+    # the same coefficients in by-source order, from the definition (not by permuting alpha_in)
+    alpha_out = np.empty(csc.nnz, dtype=np.float64)
+    for u in range(n):
+        b, e = int(csc.rowptr[u]), int(csc.rowptr[u + 1])
+        if e == b:
+            continue
+        vs = csc.colidx[b:e]
+        s = leaky_relu(p[u] + q[vs], negative_slope)
+        alpha_out[b:e] = np.exp(s - row_max[vs]) / row_sum[vs]
+    return alpha_in, alpha_out
+
+
+def weighted(g: Graph, alpha_in, alpha_out) -> Graph:
+    """g with its stored weights replaced by attention weights (float32, as the device holds them)."""
+    return replace(g,
+                   csr=Sparse(g.csr.rowptr, g.csr.colidx, np.asarray(alpha_in, dtype=np.float32)),
+                   csc=Sparse(g.csc.rowptr, g.csc.colidx, np.asarray(alpha_out, dtype=np.float32)))

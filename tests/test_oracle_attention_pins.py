@@ -1,0 +1,153 @@
+"""Pins for the attention-weight oracle (GAT AGG of Section 2.1), each against something
+other than the oracle itself:
+
+A1 every destination's weights sum to one and are positive;
+A2 with negative slope 1 the LeakyReLU is the identity and the destination's score cancels:
+   alpha(u -> v) = exp(p_u) / sum_u' exp(p_u'), written out with pure Python loops;
+A3 equal scores give 1 / in-degree (self loop counted);
+A4 a dense brute force (dictionary of edges, math.exp) on tiny directed graphs with the
+   slope the GAT paper uses;
+A5 the by-source order equals the transpose of the by-destination order (scipy.sparse);
+A6 a worked example by hand: a star with scores chosen so that the exponentials are powers of two;
+A7 a planted mistake (score of the wrong endpoint, softmax over the out-edges) fails A4.
+"""
+import math
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import oracle
+import ntp_inputs as gen
+
+
+def _directed(n, m, seed):
+    src, dst = gen.directed_random_edges(n, m, seed, hub=1, hub_in=min(n - 1, 12), hub_out=min(n - 1, 5))
+    return oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+
+
+def _scores(n, seed):
+    rng = gen.stream_rng(seed, 31)
+    return rng.normal(size=n) * 1.5, rng.normal(size=n) * 1.5
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_a1_rows_sum_to_one(seed):
+    g = _directed(300, 2500, seed)
+    p, q = _scores(g.n, seed)
+    a_in, a_out = oracle.edge_softmax(g, p, q, 0.2)
+    assert np.all(a_in > 0) and np.all(a_out > 0)
+    sums = np.add.reduceat(a_in, g.csr.rowptr[:-1])
+    assert np.allclose(sums, 1.0, rtol=0, atol=1e-14)
+    # the same weights, summed per destination from the by-source order
+    by_dst = np.bincount(g.csc.colidx, weights=a_out, minlength=g.n)
+    assert np.allclose(by_dst, 1.0, rtol=0, atol=1e-13)
+
+
+def test_a2_slope_one_closed_form():
+    g = _directed(60, 300, 5)
+    p, q = _scores(g.n, 5)
+    a_in, _ = oracle.edge_softmax(g, p, q, 1.0)
+    for v in range(g.n):
+        b, e = int(g.csr.rowptr[v]), int(g.csr.rowptr[v + 1])
+        us = [int(u) for u in g.csr.colidx[b:e]]
+        den = sum(math.exp(p[u]) for u in us)
+        for k, u in enumerate(us):
+            assert abs(a_in[b + k] - math.exp(p[u]) / den) <= 1e-14
+
+
+def test_a3_equal_scores_give_one_over_degree():
+    g = _directed(200, 1500, 7)
+    a_in, a_out = oracle.edge_softmax(g, np.full(g.n, 0.3), np.full(g.n, -1.1), 0.2)
+    deg = np.diff(g.csr.rowptr)
+    assert np.allclose(a_in, np.repeat(1.0 / deg, deg), rtol=1e-15, atol=0)
+    assert np.allclose(a_out, 1.0 / deg[g.csc.colidx], rtol=1e-15, atol=0)
+
+
+def _brute_force(n, src, dst, p, q, slope, score=None, over_out_edges=False):
+    """alpha[(u, v)] from the definition, with Python dictionaries and math.exp"""
+    edges = set()
+    for s, d in zip(src, dst):
+        if int(s) != int(d):
+            edges.add((int(s), int(d)))
+    for v in range(n):
+        edges.add((v, v))
+    if score is None:
+        score = lambda u, v: p[u] + q[v]
+    e = {}
+    for (u, v) in edges:
+        x = score(u, v)
+        e[(u, v)] = x if x > 0 else slope * x
+    alpha = {}
+    for (u, v) in edges:
+        if over_out_edges:
+            den = sum(math.exp(e[(uu, vv)]) for (uu, vv) in edges if uu == u)
+        else:
+            den = sum(math.exp(e[(uu, vv)]) for (uu, vv) in edges if vv == v)
+        alpha[(u, v)] = math.exp(e[(u, v)]) / den
+    return alpha
+
+
+@pytest.mark.parametrize("seed", [0, 3])
+def test_a4_dense_brute_force(seed):
+    n = 40
+    src, dst = gen.directed_random_edges(n, 200, seed, hub=2, hub_in=15, hub_out=6)
+    g = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    p, q = _scores(n, seed)
+    a_in, a_out = oracle.edge_softmax(g, p, q, 0.2)
+    want = _brute_force(n, src, dst, p, q, 0.2)
+    assert len(want) == g.csr.nnz
+    for v in range(n):
+        for k in range(int(g.csr.rowptr[v]), int(g.csr.rowptr[v + 1])):
+            assert abs(a_in[k] - want[(int(g.csr.colidx[k]), v)]) <= 1e-14
+    for u in range(n):
+        for k in range(int(g.csc.rowptr[u]), int(g.csc.rowptr[u + 1])):
+            assert abs(a_out[k] - want[(u, int(g.csc.colidx[k]))]) <= 1e-14
+
+
+def test_a5_by_source_order_is_the_transpose():
+    g = _directed(500, 6000, 11)
+    p, q = _scores(g.n, 11)
+    a_in, a_out = oracle.edge_softmax(g, p, q, 0.2)
+    M = sp.csr_matrix((a_in, g.csr.colidx, g.csr.rowptr), shape=(g.n, g.n))       # M[v, u]
+    T = M.transpose().tocsr()                                                     # T[u, v]
+    T.sort_indices()
+    assert np.array_equal(T.indptr, g.csc.rowptr) and np.array_equal(T.indices, g.csc.colidx)
+    assert np.allclose(T.data, a_out, rtol=1e-15, atol=0)
+
+
+def test_a6_worked_star():
+    """centre 0 with in-edges from 1, 2, 3 (one-way) and its self loop.  Scores chosen so that
+    exp(e) are 1, 2, 4, 8: p = ln(1, 2, 4, 8), q = 0, all scores >= 0 (LeakyReLU inactive):
+    alpha into the centre = (1, 2, 4, 8) / 15; the leaves have only their self loop: 1."""
+    n = 4
+    src = np.array([1, 2, 3], dtype=np.int32)
+    dst = np.array([0, 0, 0], dtype=np.int32)
+    g = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    p = np.log(np.array([1.0, 2.0, 4.0, 8.0]))
+    a_in, a_out = oracle.edge_softmax(g, p, np.zeros(n), 0.2)
+    assert g.csr.colidx[:4].tolist() == [0, 1, 2, 3]
+    assert np.allclose(a_in[:4], np.array([1, 2, 4, 8]) / 15.0, rtol=1e-15)
+    assert np.allclose(a_in[4:], 1.0)
+    # by source: vertex 0 -> {0}; vertex k -> {0, k}
+    assert np.allclose(a_out, [1 / 15, 2 / 15, 1.0, 4 / 15, 1.0, 8 / 15, 1.0], rtol=1e-15)
+    # negative scores take the slope: p = -ln(1,2,4,8)/0.5 with slope 0.5 gives exp(e) = 1, 1/2, 1/4, 1/8
+    a_in, _ = oracle.edge_softmax(g, -p / 0.5, np.zeros(n), 0.5)
+    assert np.allclose(a_in[:4], np.array([8, 4, 2, 1]) / 15.0, rtol=1e-14)
+
+
+def test_a7_planted_mistakes_are_caught():
+    n = 30
+    src, dst = gen.directed_random_edges(n, 150, 4, hub=2, hub_in=10, hub_out=4)
+    g = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    p, q = _scores(n, 4)
+    a_in, _ = oracle.edge_softmax(g, p, q, 0.2)
+
+    def max_diff(want):
+        return max(abs(a_in[k] - want[(int(g.csr.colidx[k]), v)])
+                   for v in range(n) for k in range(int(g.csr.rowptr[v]), int(g.csr.rowptr[v + 1])))
+
+    assert max_diff(_brute_force(n, src, dst, p, q, 0.2)) <= 1e-14
+    assert max_diff(_brute_force(n, src, dst, p, q, 0.2, score=lambda u, v: p[v] + q[u])) > 1e-3     # endpoints swapped
+    assert max_diff(_brute_force(n, src, dst, p, q, 0.2, over_out_edges=True)) > 1e-3               # wrong normalisation set
+    assert max_diff(_brute_force(n, src, dst, p, q, 0.0)) > 1e-3                                    # slope dropped
