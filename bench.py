@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--order", default="layerwise", choices=["layerwise", "decoupled", "reordered", "auto"])
     ap.add_argument("--full-width", action="store_true",
                     help="configs 3, 4: the whole model at full width on this GPU instead of one worker's share")
-    ap.add_argument("--mode", default="step", choices=["step", "agg", "chunk", "budget"],
+    ap.add_argument("--mode", default="step", choices=["step", "agg", "chunk", "budget", "gat"],
                     help="agg: time only aggregation calls at --widths (kernel tuning / profiling); "
                          "chunk: chunk-streamed vs in-memory aggregation; "
                          "budget: the config's own device budget and chunk size (config 5), with a sampled parity check")
@@ -288,6 +288,54 @@ def main():
         out["all_resident_over_inmem"] = out["t_chunked_all_resident_ms"] / t_inmem
         g_cold.close()
         log(json.dumps(out, indent=1))
+        print(json.dumps(out), flush=True)
+        g.close()
+        return
+
+    if args.mode == "gat":
+        # GAT-style edge attention (Section 2.1): weights of all edges by ntp_edge_softmax, then the
+        # aggregation with them as edge weights
+        f = int(args.widths.split(",")[0]) if args.widths else spec.agg_slices[0]
+        tg = torch.Generator(device=dev)
+        tg.manual_seed(args.seed)
+        p = torch.randn(n, generator=tg, device=dev)
+        q = torch.randn(n, generator=tg, device=dev)
+        a_in = torch.empty(nnz, device=dev)
+        a_out = torch.empty(nnz, device=dev)
+        ld = line_padded_ld(f, 4)
+        x = torch.randn(n, ld, generator=tg, device=dev)
+        y = torch.empty_like(x)
+        st = torch.cuda.current_stream()
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+
+        t_att = timed(lambda: ntp.ntp_edge_softmax(g, p, q, 0.2, a_in, a_out, st))
+        t_att_in = timed(lambda: ntp.ntp_edge_softmax(g, p, q, 0.2, a_in, None, st))
+        t_w = timed(lambda: ntp.ntp_aggregate_weighted(g, ntp.NTP_FWD, a_in, x, y, f, ld, ld, ntp.NTP_F32, st))
+        t_s = timed(lambda: ntp.ntp_aggregate_fwd(g, x, y, f, ld, ld, ntp.NTP_F32, st))
+        # algorithmic bytes: by-destination pass reads indices, writes weights (8 B per entry) plus
+        # per-vertex arrays (row pointers, p, q, the two statistics); the by-source pass the same
+        # per entry plus reads of the statistics
+        b_in = 8 * nnz + 8 * (n + 1) + 16 * n
+        b_out = 8 * nnz + 8 * (n + 1) + 16 * n
+        out = {"mode": "gat", "config": args.config, "n_vertices": n, "nnz": nnz, "width": f,
+               "edge_softmax_both_orders_ms": t_att, "edge_softmax_by_destination_ms": t_att_in,
+               "edge_softmax_gbs": (b_in + b_out) / (t_att * 1e-3) / 1e9,
+               "edge_softmax_frac_hbm": (b_in + b_out) / (t_att * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               "edges_per_s_both_orders": nnz / (t_att * 1e-3),
+               "aggregate_weighted_fwd_ms": t_w, "aggregate_stored_weights_fwd_ms": t_s}
+        log("edge softmax: %.3f ms both orders (%.0f GB/s algorithmic, %.1f%% of 8 TB/s), %.3f ms by destination only; "
+            "weighted aggregation f=%d %.3f ms (stored weights %.3f ms)"
+            % (t_att, out["edge_softmax_gbs"], 100 * out["edge_softmax_frac_hbm"], t_att_in, f, t_w, t_s))
         print(json.dumps(out), flush=True)
         g.close()
         return

@@ -177,6 +177,38 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
                                 void* compute_stream, void* copy_stream);
 
 /*
+ * Edge attention weights of GAT-style aggregation (AGG of GAT, Section 2.1; Section 4.1 computes
+ * the coefficients of all edges before the aggregation starts and then aggregates with them as
+ * edge weights).  For every stored entry u -> v of g (self loops included; g's own weights are
+ * not used):
+ *     e(u -> v)     = LeakyReLU(p[u] + q[v])              (negative_slope for e < 0)
+ *     alpha(u -> v) = exp(e(u -> v)) / sum over the in-edges u' -> v of exp(e(u' -> v))
+ * p[u] = a_src . (W h_u) and q[v] = a_dst . (W h_v) are the two halves of a^T [W h_u || W h_v]:
+ * device fp32 arrays of n_vertices, e.g. two columns of an ntp_nn_fwd output.
+ * alpha_in  [nnz] device fp32: the weights in the entry order of the by-destination form
+ *           (ntp_graph_export(NTP_CSR)): what ntp_aggregate_weighted(NTP_FWD) takes.
+ * alpha_out [nnz] device fp32, nullable: the same numbers (bit for bit) in the entry order of
+ *           the by-source form: what ntp_aggregate_weighted(NTP_BWD) takes.
+ * Needs the topology as one device-resident chunk (NTP_EUNSUPPORTED otherwise; alpha_out also
+ * for graphs built with NTP_SCATTER_BWD).  Deterministic.  The handle keeps 16 bytes per vertex
+ * of scratch from the first call on; calls on one handle must not overlap.
+ */
+int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negative_slope,
+                     float* alpha_in, float* alpha_out, void* stream);
+
+/*
+ * ntp_aggregate_fwd / ntp_aggregate_bwd with caller-supplied edge weights in place of the
+ * stored ones (gamma of Section 4.1: attention weights, or any per-edge weight):
+ *   NTP_FWD: Y[v,:] = sum over entries k of row v of the by-destination form  weights[k] X[colidx[k],:]
+ *   NTP_BWD: the product with the by-source form; weights in that form's entry order.  On a
+ *            graph built with NTP_SCATTER_BWD the backward scatters along the by-destination
+ *            rows and takes the weights in by-destination order.
+ * weights: device fp32 [nnz].  Everything else as for ntp_aggregate_fwd.
+ */
+int ntp_aggregate_weighted(ntp_graph_t* g, int direction, const float* weights, const void* X, void* Y,
+                           int64_t f_slice, int64_t ldx, int64_t ldy, int dtype, void* stream);
+
+/*
  * Dense transform, UPDATE of eq. (4):  H = act(A W),  A [n x k] (ld k), W [k x m] (ld m),
  * H [n x m] (ld m), all device, row-major, dtype NTP_F32 (fp32 MFMA) or NTP_BF16 (bf16
  * MFMA, fp32 accumulate, bf16 output).  act = NTP_ACT_NONE or NTP_ACT_RELU.

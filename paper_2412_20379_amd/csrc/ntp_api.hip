@@ -44,6 +44,7 @@ struct ntp_graph {
     // partial sums of split rows
     float* partial = nullptr;
     size_t partial_bytes = 0;
+    float* att_stats = nullptr;    // [4 n]: per-destination (q, maximum, 1 / sum, 0) of the last ntp_edge_softmax
     int64_t device_bytes = 0;
 
     // the by-source product runs as a scatter over the by-destination form
@@ -90,15 +91,17 @@ inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX
 
 // Enqueue the kernels of one chunk whose image lives at `img` on the device.
 // scatter: Y[colidx[k], :] += val[k] * X[row, :] instead of Y[row, :] = sum val[k] * X[colidx[k], :]
+// weights: caller's edge weights in the entry order of the form (nullptr: the stored ones)
 int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* partial,
-              int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st, bool scatter = false) {
+              int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st, bool scatter = false,
+              const float* weights = nullptr) {
     AggArgs a;
     memset(&a, 0, sizeof a);
     a.rowptr = reinterpret_cast<const int64_t*>(img + c.off_rowptr);
     a.rows = reinterpret_cast<const int32_t*>(img + c.off_rows);
     a.segs = reinterpret_cast<const Segment*>(img + c.off_segs);
     a.colidx = reinterpret_cast<const int32_t*>(img + c.img_off_colidx);
-    a.val = reinterpret_cast<const float*>(img + c.img_off_val);
+    a.val = weights ? weights + c.e_begin : reinterpret_cast<const float*>(img + c.img_off_val);
     a.X = X;
     a.Y = Y;
     a.partial = partial;
@@ -211,6 +214,7 @@ void destroy(ntp_graph* G) {
         if (G->ev_free[k]) (void)hipEventDestroy(G->ev_free[k]);
     }
     if (G->partial) (void)hipFree(G->partial);
+    if (G->att_stats) (void)hipFree(G->att_stats);
     if (G->pinned_meta) (void)hipHostFree(G->pinned_meta);
     free_entries(G->g.csr, G->pinned_entries);
     free_entries(G->g.csc, G->pinned_entries);
@@ -406,7 +410,7 @@ int ntp_graph_device_bytes(const ntp_graph_t* g, int64_t* bytes) {
 }
 
 static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y, int64_t f,
-                              int64_t ldx, int64_t ldy, int dtype, void* stream) {
+                              int64_t ldx, int64_t ldy, int dtype, void* stream, const float* weights = nullptr) {
     int rc = check_agg_args(g, X, Y, f, ldx, ldy, dtype);
     if (rc != NTP_OK) return rc;
     Form& F = g->f(which);
@@ -418,7 +422,7 @@ static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y,
     else rc = ensure_partial(g, F, f);
     if (rc != NTP_OK) return rc;
     for (auto& c : F.plan.chunks) {
-        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter);
+        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights);
         if (rc != NTP_OK) return rc;
     }
     return NTP_OK;
@@ -495,6 +499,59 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
 int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y, int64_t f,
                           int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream) {
     return ntp_chunked_aggregate_multi(g, direction, 1, &X, &Y, f, ldx, ldy, dtype, compute_stream, copy_stream);
+}
+
+int ntp_aggregate_weighted(ntp_graph_t* g, int direction, const float* weights, const void* X, void* Y,
+                           int64_t f, int64_t ldx, int64_t ldy, int dtype, void* stream) {
+    if (direction != NTP_FWD && direction != NTP_BWD) { set_error("direction must be NTP_FWD or NTP_BWD"); return NTP_EINVAL; }
+    if (g && g->g.csr.nnz > 0 && !weights) { set_error("weights is NULL"); return NTP_EINVAL; }
+    return aggregate_resident(g, direction == NTP_FWD ? NTP_CSR : NTP_CSC, X, Y, f, ldx, ldy, dtype, stream, weights);
+}
+
+int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negative_slope,
+                     float* alpha_in, float* alpha_out, void* stream) {
+    if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
+    if (g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
+    if (!(negative_slope >= 0.f) || !(negative_slope <= 1.f)) { set_error("negative_slope must be in [0, 1]"); return NTP_EINVAL; }
+    const int64_t n = g->g.n;
+    if (n == 0) return NTP_OK;
+    if (!p || !q || !alpha_in) { set_error("p, q or alpha_in is NULL"); return NTP_EINVAL; }
+    if (alpha_out && g->scatter_bwd()) { set_error("graph was built with NTP_SCATTER_BWD: no by-source form is stored"); return NTP_EUNSUPPORTED; }
+    Form& Fin = g->f(NTP_CSR);
+    Form& Fout = g->f(NTP_CSC);
+    auto one_resident_chunk = [](const Form& F) { return F.plan.chunks.size() == 1 && F.plan.chunks[0].d_image; };
+    if (!one_resident_chunk(Fin) || (alpha_out && !one_resident_chunk(Fout))) {
+        set_error("attention weights need the topology as one device-resident chunk (build without chunk_edges and budget)");
+        return NTP_EUNSUPPORTED;
+    }
+    // scratch kept by the handle: 16 bytes per vertex + 8 bytes per segment of a split row
+    const int64_t seg_floats = 2 * Fin.plan.n_slots;
+    if (!g->att_stats) {
+        void* ptr = nullptr;
+        const size_t bytes = (size_t)n * 16 + (size_t)seg_floats * 4 + 16;
+        if (hipMalloc(&ptr, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes failed", bytes); return NTP_ENOMEM; }
+        g->att_stats = (float*)ptr;
+        g->device_bytes += (int64_t)bytes;
+    }
+    float* seg_stats = g->att_stats + 4 * n;
+    auto run = [&](const Form& F, float* out, bool transposed) -> int {
+        const Chunk& c = F.plan.chunks[0];
+        AttArgs a;
+        a.rowptr = reinterpret_cast<const int64_t*>(c.d_image + c.off_rowptr);
+        a.colidx = reinterpret_cast<const int32_t*>(c.d_image + c.img_off_colidx);
+        a.rows = reinterpret_cast<const int32_t*>(c.d_image + c.off_rows);
+        a.p = p; a.q = q;
+        a.st = g->att_stats;
+        a.alpha = out;
+        a.slope = negative_slope;
+        return launch_attention(a, c.bin_row_off, c.bin_count,
+                                reinterpret_cast<const Segment*>(c.d_image + c.off_segs), c.n_segs,
+                                reinterpret_cast<const ReduceItem*>(c.d_image + c.off_reduce), c.n_reduce,
+                                seg_stats, transposed, stream);
+    };
+    int rc = run(Fin, alpha_in, false);
+    if (rc == NTP_OK && alpha_out) rc = run(Fout, alpha_out, true);
+    return rc;
 }
 
 int ntp_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,

@@ -166,6 +166,22 @@ void agg_shape(int64_t f, int vec, int pass_lanes, int* lanes_per_row, int* n_ac
 int agg_pick_pass_lanes(const void* X, int64_t ldx, int dtype, int vec, double entries_per_row);
 int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype);
 
+// edge attention weights (attention_kernels.hip)
+struct AttArgs {
+    const int64_t* rowptr;     // whole form: rowptr[row]
+    const int32_t* colidx;
+    const int32_t* rows;       // bin row lists
+    const float* p;            // per-vertex source score
+    const float* q;            // per-vertex destination score
+    float* st;                 // per destination, four floats (16-byte aligned): q, maximum score over its
+                               // in-edges, 1 / sum of exp(score - maximum), 0
+    float* alpha;              // output, entry order of the form
+    float slope;               // LeakyReLU slope for negative scores
+};
+int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t* bin_count,
+                     const Segment* segs, int n_segs, const ReduceItem* split_rows, int n_split_rows,
+                     float* seg_stats, bool transposed, void* stream);
+
 int launch_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,
                   int act, int dtype, void* stream);
 int launch_nn_bwd(const void* A, const void* W, const void* H, const void* dH, void* dA, float* dW,

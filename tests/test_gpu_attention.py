@@ -1,0 +1,199 @@
+"""GPU parity of ntp_edge_softmax (GAT-style attention weights, Section 2.1) and of
+ntp_aggregate_weighted (aggregation with caller-supplied edge weights) against the oracle."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import ntp_inputs as gen
+import paper_2412_20379_amd as ntp
+from helpers import assert_close, TOL_F32
+
+pytestmark = pytest.mark.gpu
+TOL_ALPHA = 1e-5          # relative, per weight
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def _scores(n, seed, scale=1.5):
+    rng = gen.stream_rng(seed, 31)
+    return (rng.normal(size=n) * scale).astype(np.float32), (rng.normal(size=n) * scale).astype(np.float32)
+
+
+def _device_alpha(g, nnz, p, q, slope, want_out=True):
+    import torch
+    from gpu_util import dev_f32
+    a_in = torch.full((nnz,), float("nan"), device="cuda:0")
+    a_out = torch.full((nnz,), float("nan"), device="cuda:0") if want_out else None
+    ntp.ntp_edge_softmax(g, dev_f32(p), dev_f32(q), slope, a_in, a_out)
+    torch.cuda.synchronize()
+    return a_in, a_out
+
+
+def _check_alpha(og, a_in, a_out, p, q, slope, what):
+    r_in, r_out = oracle.edge_softmax(og, p, q, slope)
+    got_in = a_in.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got_in)), what
+    err = np.abs(got_in - r_in) / r_in
+    say("   %s: alpha_in max rel err %.2e" % (what, err.max()))
+    assert err.max() <= TOL_ALPHA, what
+    sums = np.add.reduceat(got_in, og.csr.rowptr[:-1])
+    assert np.abs(sums - 1.0).max() <= 1e-5
+    if a_out is not None:
+        got_out = a_out.cpu().numpy()
+        assert (np.abs(got_out.astype(np.float64) - r_out) / r_out).max() <= TOL_ALPHA, what
+        # the same edge carries the same bits in both orders
+        import scipy.sparse as sp
+        n = og.n
+        # entry ids of the by-destination order, transposed to the by-source order
+        ids = sp.csr_matrix((np.arange(1, og.csr.nnz + 1, dtype=np.float64), og.csr.colidx, og.csr.rowptr), shape=(n, n))
+        t = ids.transpose().tocsr()
+        t.sort_indices()
+        perm = t.data.astype(np.int64) - 1
+        assert np.array_equal(a_in.cpu().numpy()[perm].view(np.uint32), got_out.view(np.uint32)), what + ": orders differ in bits"
+
+
+@pytest.fixture(scope="module")
+def hub():
+    """directed, every degree bin populated, the hub's row beyond the split threshold"""
+    n = 3000
+    src, dst = gen.directed_random_edges(n, 40000, 21, hub=5, hub_in=2600, hub_out=900)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    yield n, src, dst, g, og
+    g.close()
+
+
+@pytest.mark.parametrize("slope", [0.2, 0.0, 1.0])
+def test_attention_weights_directed(hub, slope):
+    n, src, dst, g, og = hub
+    p, q = _scores(n, 3)
+    a_in, a_out = _device_alpha(g, og.csr.nnz, p, q, slope)
+    _check_alpha(og, a_in, a_out, p, q, slope, "hub graph slope %g" % slope)
+
+
+def test_attention_weights_extreme_scores(hub):
+    """scores far apart: the shift by the row maximum keeps everything finite"""
+    n, src, dst, g, og = hub
+    p, q = _scores(n, 4, scale=25.0)
+    a_in, a_out = _device_alpha(g, og.csr.nnz, p, q, 0.2)
+    got = a_in.cpu().numpy().astype(np.float64)
+    ref, _ = oracle.edge_softmax(og, p, q, 0.2)
+    assert np.all(np.isfinite(got))
+    big = ref > 1e-30                     # weights that are not denormal in fp32
+    assert (np.abs(got[big] - ref[big]) / ref[big]).max() <= 5e-5      # exp(x) carries the rounding of x ~ 50
+    assert np.abs(np.add.reduceat(got, og.csr.rowptr[:-1]) - 1.0).max() <= 1e-5
+
+
+def test_attention_weights_symmetric_and_configs():
+    for cfg, scale in ((1, 1), (2, 1), (4, 64)):
+        n, src, dst = gen.make_graph(cfg, seed=0, scale_down=scale)
+        og = oracle.build_graph(n, src, dst, oracle.GCN_FLAGS)
+        g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS)
+        assert ntp.ntp_graph_info(g)["is_symmetric"]
+        p, q = _scores(n, cfg)
+        a_in, a_out = _device_alpha(g, og.csr.nnz, p, q, 0.2)
+        _check_alpha(og, a_in, a_out, p, q, 0.2, "config %d" % cfg)
+        g.close()
+
+
+def test_attention_degree_edge_cases():
+    degs = [1, 2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257,
+            511, 512, 513, 1023, 1024, 1025, 2047, 2048, 2049, 5000]
+    n = 6000
+    rng = gen.stream_rng(5, 1)
+    src, dst = [], []
+    for v, d in enumerate(degs):
+        others = rng.choice(np.setdiff1d(np.arange(n), [v]), size=d - 1, replace=False)
+        src.append(others)
+        dst.append(np.full(d - 1, v))
+    src = np.concatenate(src).astype(np.int32)
+    dst = np.concatenate(dst).astype(np.int32)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    p, q = _scores(n, 9)
+    a_in, a_out = _device_alpha(g, og.csr.nnz, p, q, 0.2)
+    _check_alpha(og, a_in, a_out, p, q, 0.2, "degree edge cases")
+    g.close()
+
+
+@pytest.mark.parametrize("f,dtype", [(16, "f32"), (76, "f32"), (256, "f32"), (64, "bf16")])
+def test_weighted_aggregation(hub, f, dtype):
+    """forward and backward aggregation with the attention weights as edge weights"""
+    import torch
+    from gpu_util import dev_f32, dev_bf16_bits, host_bf16
+    from helpers import TOL_BF16
+    n, src, dst, g, og = hub
+    p, q = _scores(n, 6)
+    a_in, a_out = _device_alpha(g, og.csr.nnz, p, q, 0.2)
+    # the oracle aggregates with the very weights the device holds (isolates the aggregation) ...
+    wg = oracle.weighted(og, a_in.cpu().numpy(), a_out.cpu().numpy())
+    x = gen.normal_features(n, f, seed=f)
+    for direction, m, w in ((ntp.NTP_FWD, wg.csr, a_in), (ntp.NTP_BWD, wg.csc, a_out)):
+        if dtype == "f32":
+            y = torch.full((n, f), float("nan"), device="cuda:0")
+            ntp.ntp_aggregate_weighted(g, direction, w, dev_f32(x), y, f, f, f)
+            torch.cuda.synchronize()
+            ref, ref_abs = oracle.aggregate(m, x, with_abs=True)
+            assert_close(y.cpu().numpy(), ref, ref_abs, TOL_F32, "weighted %d f=%d" % (direction, f))
+        else:
+            bits, xv = dev_bf16_bits(x)
+            y = torch.zeros((n, f), dtype=torch.int16, device="cuda:0")
+            ntp.ntp_aggregate_weighted(g, direction, w, bits, y, f, f, f, ntp.NTP_BF16)
+            torch.cuda.synchronize()
+            ref, ref_abs = oracle.aggregate(m, xv, with_abs=True)
+            assert_close(host_bf16(y), oracle.round_bf16(ref).astype(np.float64), ref_abs, TOL_BF16, "weighted bf16")
+    # ... and end to end: oracle weights, oracle aggregation
+    if dtype == "f32":
+        r_in, r_out = oracle.edge_softmax(og, p, q, 0.2)
+        ref, ref_abs = oracle.aggregate(oracle.weighted(og, r_in, r_out).csr, x, with_abs=True)
+        y = torch.full((n, f), float("nan"), device="cuda:0")
+        ntp.ntp_aggregate_weighted(g, ntp.NTP_FWD, a_in, dev_f32(x), y, f, f, f)
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy(), ref, ref_abs, TOL_F32, "attention + aggregation f=%d" % f)
+    # the stored (GCN) weights are untouched
+    from gpu_util import check_agg
+    check_agg(g, og, x, "fwd", dtype, "stored weights after a weighted call")
+
+
+def test_weighted_backward_on_a_one_form_graph(hub):
+    """a graph without the by-source form scatters along its rows with by-destination weights"""
+    import torch
+    from gpu_util import dev_f32
+    n, src, dst, _, og = hub
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | ntp.NTP_SCATTER_BWD)
+    p, q = _scores(n, 8)
+    a_in, _ = _device_alpha(g, og.csr.nnz, p, q, 0.2, want_out=False)
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_edge_softmax(g, dev_f32(p), dev_f32(q), 0.2, a_in, torch.empty_like(a_in))
+    r_in, r_out = oracle.edge_softmax(og, p, q, 0.2)
+    f = 48
+    x = gen.normal_features(n, f, seed=2)
+    y = torch.full((n, f), float("nan"), device="cuda:0")
+    ntp.ntp_aggregate_weighted(g, ntp.NTP_BWD, a_in, dev_f32(x), y, f, f, f)
+    torch.cuda.synchronize()
+    ref, ref_abs = oracle.aggregate(oracle.weighted(og, r_in, r_out).csc, x, with_abs=True)
+    assert_close(y.cpu().numpy(), ref, ref_abs, TOL_F32, "scatter with attention weights")
+    g.close()
+
+
+def test_attention_argument_errors(hub):
+    import torch
+    from gpu_util import dev_f32
+    n, src, dst, g, og = hub
+    p, q = _scores(n, 1)
+    a = torch.empty(og.csr.nnz, device="cuda:0")
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_edge_softmax(g, dev_f32(p), dev_f32(q), -0.5, a)
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_edge_softmax(g, None, dev_f32(q), 0.2, a)
+    chunked = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=5000)
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_edge_softmax(chunked, dev_f32(p), dev_f32(q), 0.2, a)
+    assert e.value.code == ntp.NTP_EUNSUPPORTED
+    chunked.close()
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_aggregate_weighted(g, 7, a, a, a, 4, 4, 4)
