@@ -159,3 +159,44 @@ def test_column_slices_equal_full_width():
     # different lane mapping per width: equal to rounding, not bit-equal
     assert np.abs(a - b).max() <= 1e-5 * np.abs(a).max()
     g.close()
+
+
+def test_epoch_captured_in_a_hip_graph_replays_identically():
+    """The library calls of an epoch are capturable (no allocation after the first call, no
+    memset nodes): several replays, with eager work and synchronisations between them, give
+    the bits of the eager run."""
+    import torch
+    from paper_2412_20379_amd.gcn import GcnEpoch
+    from gpu_util import dev_f32
+    cfg = 1
+    n, src, dst = gen.make_graph(cfg, seed=0)
+    dims = gen.CONFIGS[cfg].layers
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS)
+    X = dev_f32(gen.make_features(cfg, dims[0], seed=0))
+    Ws = [dev_f32(gen.glorot_weight(dims[i], dims[i + 1], 0, i)) for i in range(len(dims) - 1)]
+    labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], 0).astype(np.int64)).to("cuda:0")
+    for order in ("layerwise", "decoupled", "auto"):
+        ep = GcnEpoch(g, n, dims, order=order)
+        ep.run(X, Ws, labels)                      # first call: scratch is allocated here
+        torch.cuda.synchronize()
+        want_loss = float(ep.loss)
+        want_dW = [w.clone() for w in ep.dW]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ep.run(X, Ws, labels)
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ep.run(X, Ws, labels)
+        for r in range(4):
+            for w in ep.dW:
+                w.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert float(ep.loss) == want_loss, "%s replay %d" % (order, r)
+            for a, b in zip(ep.dW, want_dW):
+                assert torch.equal(a, b), "%s replay %d" % (order, r)
+            _ = float((X * 2).sum())               # eager work between the replays
+    g.close()
