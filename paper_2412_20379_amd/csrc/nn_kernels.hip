@@ -192,24 +192,33 @@ __device__ __forceinline__ bool block_to_tile(const GemmArgs& g, int& bx, int& b
     return true;
 }
 
-// epilogue: element e of a 32x32 accumulator sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+// epilogue: element e of a 32x32 accumulator sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+// One pointer per 32x32 block walks down the rows; the row test is a 32-bit compare against the
+// rows left below the block's first row, and a wavefront whose whole tile lies inside the matrix
+// stores without tests.
 template <class TC, int TM, int TN>
 __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc)[TM][TN], int bz,
                                            int64_t row0, int64_t col0, int lane) {
     TC* C = static_cast<TC*>(g.C) + (int64_t)bz * g.c_split_stride;
+    const bool inside = row0 + TM * 32 <= g.Mdim && col0 + TN * 32 <= g.Ndim;      // uniform over the wavefront
+    const int64_t ldc = g.ldc;
+    const bool relu = g.relu != 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int64_t col = col0 + j * 32 + (lane & 31);
+            const int64_t rbase = row0 + i * 32 + 4 * (lane >> 5);
+            const int64_t left64 = g.Mdim - rbase;
+            const int rows_left = inside ? 32 : (col < g.Ndim ? (left64 > 32 ? 32 : (left64 < 0 ? 0 : (int)left64)) : 0);
+            TC* p = C + rbase * ldc + col;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int64_t row = row0 + i * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4);
-                if (row < g.Mdim && col < g.Ndim) {
-                    float v = acc[i][j][e];
-                    if (g.relu) v = v > 0.f ? v : 0.f;
-                    store_elem(C + row * g.ldc + col, v);
-                }
+                const int r = 8 * (e / 4) + (e % 4);          // row offset inside the block, compile time
+                float v = acc[i][j][e];
+                if (relu) v = v > 0.f ? v : 0.f;
+                if (r < rows_left) store_elem(p, v);
+                p += (e % 4 == 3) ? 5 * ldc : ldc;             // next row: +1, or +5 to the next group of four
             }
         }
 }
