@@ -405,3 +405,28 @@ def test_golden_worked_examples():
         x = np.array(c["x"])[:, None]
         np.testing.assert_allclose(oracle.aggregate_fwd(g, x)[:, 0], c["fwd"], rtol=2e-7, err_msg=name)
         np.testing.assert_allclose(oracle.aggregate_bwd(g, x)[:, 0], c["bwd"], rtol=2e-7, err_msg=name)
+
+
+def test_p7_softmax_cross_entropy_direct():
+    """the loss of the downstream task on its own: equal logits give log(classes) and the
+    gradient (1/c - onehot)/n; gradient rows sum to zero; finite differences on single logits"""
+    n, c = 9, 5
+    labels = np.array([0, 1, 2, 3, 4, 0, 2, 4, 1])
+    loss, dZ = gcn.softmax_cross_entropy(np.full((n, c), 3.7), labels)
+    assert abs(loss - np.log(c)) < 1e-14
+    want = np.full((n, c), 1.0 / c)
+    want[np.arange(n), labels] -= 1.0
+    np.testing.assert_allclose(dZ, want / n, rtol=1e-14)
+    Z = gen.normal_features(n, c, 21).astype(np.float64) * 4.0
+    loss, dZ = gcn.softmax_cross_entropy(Z, labels)
+    np.testing.assert_allclose(dZ.sum(axis=1), 0.0, atol=1e-16)
+    eps = 1e-6
+    for (i, j) in ((0, 0), (3, 1), (8, 4), (5, 2)):
+        Zp, Zm = Z.copy(), Z.copy()
+        Zp[i, j] += eps
+        Zm[i, j] -= eps
+        fd = (gcn.softmax_cross_entropy(Zp, labels)[0] - gcn.softmax_cross_entropy(Zm, labels)[0]) / (2 * eps)
+        assert abs(fd - dZ[i, j]) <= 1e-8
+    # shift invariance and no overflow on large logits
+    big, dB = gcn.softmax_cross_entropy(Z + 800.0, labels)
+    assert abs(big - loss) < 1e-10 and np.allclose(dB, dZ, atol=1e-12)
