@@ -232,6 +232,19 @@ int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH,
 int64_t ntp_nn_bwd_workspace_bytes(int64_t n, int64_t k, int64_t m);
 
 /*
+ * Loss of the vertex classification task that closes the forward loop of Alg. 1 and starts the
+ * reverse loop:  loss[0] = mean over the n vertices of -log softmax(Z[v, 0:c])[labels[v]]  and
+ * dZ[v, :] = (softmax(Z[v, :]) - onehot(labels[v])) / n.  Z, dZ: device fp32, row strides ldz,
+ * lddz >= c, not overlapping; labels: device int64, a label
+ * outside [0, c) contributes no loss and no -1; loss: one device float.  scratch: device memory
+ * of ntp_softmax_xent_scratch_bytes(n) bytes, caller owned.  Deterministic (fixed-order sums).
+ */
+int ntp_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss,
+                     void* scratch, int64_t scratch_bytes, int64_t n, int64_t c,
+                     int64_t ldz, int64_t lddz, void* stream);
+int64_t ntp_softmax_xent_scratch_bytes(int64_t n);
+
+/*
  * The activation sigma of eq. (4) on its own, for a layer evaluated as sigma(A_hat (H W))
  * (transform first, aggregate at the narrower output width, then activate), where it cannot
  * be fused into the transform.  ntp_relu_fwd: H = max(H, 0) in place.  ntp_relu_bwd:

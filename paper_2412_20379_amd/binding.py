@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_chunks",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
     "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_aggregate_weighted",
-    "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_relu_fwd", "ntp_relu_bwd",
+    "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent", "ntp_softmax_xent_scratch_bytes", "ntp_relu_fwd", "ntp_relu_bwd",
     "ntp_graph_free", "ntp_last_error",
 ]
 
@@ -68,12 +68,15 @@ def lib():
     L.ntp_relu_bwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_nn_bwd_workspace_bytes.argtypes = [i64, i64, i64]
     L.ntp_nn_bwd_workspace_bytes.restype = i64
+    L.ntp_softmax_xent.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
+    L.ntp_softmax_xent_scratch_bytes.argtypes = [i64]
+    L.ntp_softmax_xent_scratch_bytes.restype = i64
     L.ntp_graph_free.argtypes = [vp]
     L.ntp_graph_free.restype = None
     L.ntp_last_error.restype = ctypes.c_char_p
     for name in EXPORTED_SYMBOLS:
         fn = getattr(L, name)
-        if name not in ("ntp_graph_free", "ntp_last_error", "ntp_nn_bwd_workspace_bytes"):
+        if name not in ("ntp_graph_free", "ntp_last_error", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent_scratch_bytes"):
             fn.restype = ctypes.c_int
     _lib = L
     return L
@@ -228,6 +231,15 @@ def ntp_nn_bwd(A, W, H, dH, dA, dW, n, k, m, act=NTP_ACT_NONE, dtype=NTP_F32,
                workspace=None, workspace_bytes=0, stream=None):
     _check(lib().ntp_nn_bwd(_ptr(A), _ptr(W), _ptr(H), _ptr(dH), _ptr(dA), _ptr(dW), int(n), int(k), int(m),
                             int(act), int(dtype), _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def ntp_softmax_xent_scratch_bytes(n) -> int:
+    return int(lib().ntp_softmax_xent_scratch_bytes(int(n)))
+
+
+def ntp_softmax_xent(Z, labels, dZ, loss, scratch, scratch_bytes, n, c, ldz, lddz, stream=None):
+    _check(lib().ntp_softmax_xent(_ptr(Z), _ptr(labels), _ptr(dZ), _ptr(loss), _ptr(scratch), int(scratch_bytes),
+                                  int(n), int(c), int(ldz), int(lddz), _stream(stream)))
 
 
 def ntp_relu_fwd(H, n, f, ld, dtype=NTP_F32, stream=None):

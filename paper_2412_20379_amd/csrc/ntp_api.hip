@@ -579,6 +579,16 @@ int ntp_nn_bwd(const void* A, const void* W, const void* H, const void* dH, void
     return launch_nn_bwd(A, W, H, dH, dA, dW, n, k, m, act, dtype, workspace, workspace_bytes, stream);
 }
 
+int64_t ntp_softmax_xent_scratch_bytes(int64_t n) { return n < 0 ? 0 : (n + 1024) * 4; }
+
+int ntp_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss, void* scratch, int64_t scratch_bytes,
+                     int64_t n, int64_t c, int64_t ldz, int64_t lddz, void* stream) {
+    if (n < 1 || c < 1 || c > 65536 || ldz < c || lddz < c) { set_error("bad loss shape n=%lld c=%lld ldz=%lld lddz=%lld", (long long)n, (long long)c, (long long)ldz, (long long)lddz); return NTP_EINVAL; }
+    if (!Z || !labels || !dZ || !loss) { set_error("NULL buffer"); return NTP_EINVAL; }
+    if (!scratch || scratch_bytes < ntp_softmax_xent_scratch_bytes(n)) { set_error("scratch too small: need %lld bytes", (long long)ntp_softmax_xent_scratch_bytes(n)); return NTP_EINVAL; }
+    return launch_softmax_xent(Z, labels, dZ, loss, static_cast<float*>(scratch), n, c, ldz, lddz, stream);
+}
+
 int ntp_relu_fwd(void* H, int64_t n, int64_t f, int64_t ld, int dtype, void* stream) {
     if (n < 0 || f < 1 || ld < f) { set_error("bad activation shape n=%lld f=%lld ld=%lld", (long long)n, (long long)f, (long long)ld); return NTP_EINVAL; }
     if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }

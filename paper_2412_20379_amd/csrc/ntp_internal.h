@@ -182,6 +182,9 @@ int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t
                      const Segment* segs, int n_segs, const ReduceItem* split_rows, int n_split_rows,
                      float* seg_stats, bool transposed, void* stream);
 
+int launch_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss, float* scratch,
+                        int64_t n, int64_t c, int64_t ldz, int64_t lddz, void* stream);
+
 int launch_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,
                   int act, int dtype, void* stream);
 int launch_nn_bwd(const void* A, const void* W, const void* H, const void* dH, void* dA, float* dW,

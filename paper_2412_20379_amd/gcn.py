@@ -1,9 +1,8 @@
 """Layer-wise and decoupled GCN epochs composed from the library calls.
 
 Harness code: it owns the device buffers (torch tensors) and the order of the calls;
-all aggregation and transform arithmetic runs inside libntp.  The softmax
-cross-entropy at the end of the forward pass is the downstream task of Alg. 1 and is
-not part of the library; it is a few torch ops on the logits.
+all arithmetic of an epoch runs inside libntp: aggregation, transform, activation and
+the softmax cross-entropy of the downstream task that closes the forward pass of Alg. 1.
 """
 from __future__ import annotations
 
@@ -53,6 +52,9 @@ class GcnEpoch:
         ws = max(ntp.ntp_nn_bwd_workspace_bytes(n, dims[l], dims[l + 1]) for l in range(L))
         self.ws_bytes = ws
         self.ws = torch.empty(max(ws, 4), dtype=torch.uint8, device=device)
+        self.dlogits = torch.empty(n, dims[-1], **f32)
+        self.loss_buf = torch.zeros(1, **f32)
+        self.loss_scratch = torch.empty(ntp.ntp_softmax_xent_scratch_bytes(n) // 4, **f32)
         self.copy_stream = torch.cuda.Stream(device=device) if chunked else None
         self.dw_stream = torch.cuda.Stream(device=device) if overlap_dw else None
         self.ws2 = torch.empty(max(ws, 4), dtype=torch.uint8, device=device) if overlap_dw else None
@@ -93,12 +95,11 @@ class GcnEpoch:
         return self.tmp[i].view(-1)[: self.n * f].view(self.n, f)
 
     def _loss_grad(self, Z, labels):
-        logp = torch.log_softmax(Z, dim=1)
-        self.loss = -logp.gather(1, labels.view(-1, 1)).mean()
-        dZ = torch.exp(logp)
-        dZ.scatter_add_(1, labels.view(-1, 1), torch.full((self.n, 1), -1.0, device=Z.device))
-        dZ.div_(self.n)
-        return dZ
+        c = self.dims[-1]
+        self._timed("softmax_xent %d" % c, ntp.ntp_softmax_xent, Z, labels, self.dlogits, self.loss_buf, self.loss_scratch,
+                    self.loss_scratch.numel() * 4, self.n, c, c, c, torch.cuda.current_stream())
+        self.loss = self.loss_buf[0]
+        return self.dlogits
 
     def run(self, X, weights, labels):
         if self.order in ("layerwise", "reordered", "auto"):

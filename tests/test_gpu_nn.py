@@ -170,3 +170,36 @@ def test_wide_dynamic_range_keeps_fp32_accuracy(n, k, m):
         norm, comp, _ = rel_errors(got.cpu().numpy(), ref, scale)
         say("   %s: normwise %.2e componentwise %.2e" % (name, norm, comp))
         assert comp <= 2e-6 and norm <= 2e-6, name
+
+
+@pytest.mark.parametrize("n,c", [(1, 1), (7, 3), (1000, 7), (2708, 16), (5000, 40), (3001, 47), (999, 172), (70000, 41), (4099, 300)])
+def test_softmax_cross_entropy(n, c):
+    """loss of the downstream task and its gradient against the oracle; strided logits,
+    large logits (no overflow), determinism"""
+    import torch
+    from gpu_util import dev_f32
+    say("softmax_xent", n, c)
+    Z = (gen.normal_features(n, c, seed=n + c) * 6.0).astype(np.float32)
+    Z[::7] += 300.0                                  # rows of large logits
+    labels = gen.uniform_labels(n, c, n)
+    ld = c + 3
+    Zd = torch.full((n, ld), 1e30, device="cuda:0")
+    Zd[:, :c] = dev_f32(Z)
+    dZ = torch.full((n, c), float("nan"), device="cuda:0")
+    loss = torch.full((1,), float("nan"), device="cuda:0")
+    lab = torch.from_numpy(labels.astype(np.int64)).to("cuda:0")
+    nb = ntp.ntp_softmax_xent_scratch_bytes(n)
+    scratch = torch.empty(nb // 4, device="cuda:0")
+    ntp.ntp_softmax_xent(Zd, lab, dZ, loss, scratch, nb, n, c, ld, c)
+    torch.cuda.synchronize()
+    want_loss, want_dZ = ogcn.softmax_cross_entropy(Z, labels)
+    got = dZ.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert abs(float(loss) - want_loss) <= 1e-5 * max(abs(want_loss), 1e-3), (float(loss), want_loss)
+    assert np.abs(got - want_dZ).max() <= 1e-5 / n                 # every entry of dZ is a probability / n
+    first = (float(loss), dZ.clone())
+    ntp.ntp_softmax_xent(Zd, lab, dZ, loss, scratch, nb, n, c, ld, c)
+    torch.cuda.synchronize()
+    assert float(loss) == first[0] and torch.equal(dZ, first[1])
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_softmax_xent(Zd, lab, dZ, loss, scratch, nb - 4, n, c, ld, c)
