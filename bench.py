@@ -416,14 +416,19 @@ def main():
         tg.manual_seed(args.seed)
         # slice rows start on 128-byte lines when they are at least one line wide (the aggregation
         # then walks the columns line by line), else on 16-byte vectors
-        lds = [line_padded_ld(s, 4) for s in slices]
-        xs = [torch.randn(n, ld, generator=tg, **f32) for ld in lds]
+        # --agg-dtype bf16: the bf16 feature variant (features, activations and their gradients in
+        # bf16; weights' gradients and all accumulation in fp32)
+        share_bf16 = args.agg_dtype == "bf16"
+        code_s = ntp.NTP_BF16 if share_bf16 else ntp.NTP_F32
+        tdt = torch.bfloat16 if share_bf16 else torch.float32
+        lds = [line_padded_ld(s, 2 if share_bf16 else 4) for s in slices]
+        xs = [torch.randn(n, ld, generator=tg, **f32).to(tdt) for ld in lds]
         ys = [torch.empty_like(x) for x in xs]
-        A = [torch.randn(n_share, dims[l], generator=tg, **f32) for l in range(L)]
-        Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev) for l in range(L)]
-        H = [torch.empty(n_share, dims[l + 1], **f32) for l in range(L)]
-        dH = [torch.randn(n_share, dims[l + 1], generator=tg, **f32) for l in range(L)]
-        dA = [torch.empty(n_share, dims[l], **f32) for l in range(L)]
+        A = [torch.randn(n_share, dims[l], generator=tg, **f32).to(tdt) for l in range(L)]
+        Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev).to(tdt) for l in range(L)]
+        H = [torch.empty(n_share, dims[l + 1], dtype=tdt, device=dev) for l in range(L)]
+        dH = [torch.randn(n_share, dims[l + 1], generator=tg, **f32).to(tdt) for l in range(L)]
+        dA = [torch.empty(n_share, dims[l], dtype=tdt, device=dev) for l in range(L)]
         dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
         wsb = max(ntp.ntp_nn_bwd_workspace_bytes(n_share, dims[l], dims[l + 1]) for l in range(L))
         ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device=dev)
@@ -455,16 +460,16 @@ def main():
             st = torch.cuda.current_stream()
             for l in range(L):
                 s = slices[l]
-                timed("agg_fwd f=%d" % s, agg_fwd, g, xs[l], ys[l], s, lds[l], lds[l], ntp.NTP_F32, st)
+                timed("agg_fwd f=%d" % s, agg_fwd, g, xs[l], ys[l], s, lds[l], lds[l], code_s, st)
                 act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
-                timed("nn_fwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_fwd, A[l], Ws[l], H[l], n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, st)
+                timed("nn_fwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_fwd, A[l], Ws[l], H[l], n_share, dims[l], dims[l + 1], act, code_s, st)
             for l in range(L - 1, -1, -1):
                 act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
                 timed("nn_bwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_bwd, A[l], Ws[l], H[l], dH[l], dA[l] if l > 0 else None, dW[l],
-                      n_share, dims[l], dims[l + 1], act, ntp.NTP_F32, ws, wsb, st)
+                      n_share, dims[l], dims[l + 1], act, code_s, ws, wsb, st)
                 if l > 0:
                     s = slices[l]
-                    timed("agg_bwd f=%d" % s, agg_bwd, g, ys[l], xs[l], s, lds[l], lds[l], ntp.NTP_F32, st)
+                    timed("agg_bwd f=%d" % s, agg_bwd, g, ys[l], xs[l], s, lds[l], lds[l], code_s, st)
 
         def set_events(lst):
             holder["ev"] = lst
@@ -502,22 +507,26 @@ def main():
         by_width.setdefault(f, []).extend(per[k])
     fdom = max(by_width, key=lambda f: np.sum(by_width[f]))
     dur_ms = float(np.mean(by_width[fdom]))
-    balg = agg_bytes(n, nnz, fdom)
+    step_bf16 = args.agg_dtype == "bf16" and not (args.config in (1, 2) or args.full_width)
+    dtype_label = "bf16" if step_bf16 else "f32"
+    balg = agg_bytes(n, nnz, fdom, 2 if step_bf16 else 4)
     achieved = balg / (dur_ms * 1e-3) / 1e9
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tfile):
         try:
-            traffic = json.load(open(tfile)).get("cfg%d_f%d" % (args.config, fdom)) if args.scale_down == 1 else None
+            traffic = json.load(open(tfile)).get("cfg%d_f%d%s" % (args.config, fdom, "_bf16" if step_bf16 else "")) if args.scale_down == 1 else None
         except Exception:
             traffic = None
-    roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, fp32)" % fdom, achieved=achieved, peak=HBM_PEAK_GBS,
+    roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, %s)" % (fdom, "bf16" if step_bf16 else "fp32"), achieved=achieved, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=traffic,
                     algorithmic_bytes_per_launch=balg, avg_launch_ms=dur_ms,
                     geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
     nn_tflops = flops_nn / (nn_ms * 1e-3) / 1e12 if nn_ms > 0 else None
     split_core = not os.environ.get("NTP_NN_CORE", "").startswith("f")
     nn_peak = SPLIT_PEAK_TFLOPS if split_core else FP32_MFMA_PEAK_TFLOPS
+    if step_bf16:
+        nn_peak = BF16_MFMA_PEAK_TFLOPS       # bf16 operands: one bf16 matrix instruction per product
     roofline_nn = dict(bound="mfma",
                        kernel=("gemm_split_kernel (fp32 products from bf16 pieces, 6 bf16 MFMA per product; "
                                "peak = 2500/6) + gemm_kernel (fp32 MFMA) for narrow products, all transform calls of a step"
@@ -598,7 +607,7 @@ def main():
         "metric": "aggregation GEPS (stored entries x F_slice / s) over the step; epoch ms in ms_per_step",
         "value": geps, "unit": "GEPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": dtype_label, "data": "synthetic",
         "config": {"workload": workload, "n_vertices": n, "nnz": nnz, "max_degree": info["max_degree"],
                    "seed": args.seed, "scale_down": args.scale_down},
         "roofline": roofline, "roofline_nn": roofline_nn, "cpu_baseline": cpu_baseline,
