@@ -521,6 +521,10 @@ def main():
     roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, %s)" % (fdom, "bf16" if step_bf16 else "fp32"), achieved=achieved, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=traffic,
                     algorithmic_bytes_per_launch=balg, avg_launch_ms=dur_ms,
+                    # measured HBM-side bytes over the same duration, and how far they exceed the algorithmic ones
+                    traffic_gbs=(traffic / (dur_ms * 1e-3) / 1e9) if traffic else None,
+                    traffic_frac_of_peak=(traffic / (dur_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic else None,
+                    overfetch=(traffic / balg) if traffic else None,
                     geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
     nn_tflops = flops_nn / (nn_ms * 1e-3) / 1e12 if nn_ms > 0 else None
     split_core = not os.environ.get("NTP_NN_CORE", "").startswith("f")
