@@ -160,8 +160,8 @@ def main():
             ntp.binding._check(ntp.lib().ntp_graph_export(gw.handle, ntp.NTP_CSR, ntp.binding._ptr(rp), None, None))
             rowptr = rp
         deg = np.diff(rowptr)
-        top = np.argsort(deg)[-100:]
-        uni = gen.stream_rng(args.seed, 98).choice(n, size=min(n, 20000), replace=False)
+        top = np.argsort(deg)[-1000:]                  # the 1,000 highest-degree rows ...
+        uni = gen.stream_rng(args.seed, 98).choice(n, size=min(n, 100000), replace=False)     # ... and 100,000 uniform ones
         rows = np.unique(np.concatenate([top, uni])).astype(np.int64)
         t0 = time.time()
         m = oracle.rows_from_undirected_edges(n, src, dst, rows)
