@@ -189,8 +189,8 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
  *           (ntp_graph_export(NTP_CSR)): what ntp_aggregate_weighted(NTP_FWD) takes.
  * alpha_out [nnz] device fp32, nullable: the same numbers (bit for bit) in the entry order of
  *           the by-source form: what ntp_aggregate_weighted(NTP_BWD) takes.
- * Needs the topology as one device-resident chunk (NTP_EUNSUPPORTED otherwise; alpha_out also
- * for graphs built with NTP_SCATTER_BWD).  Deterministic.  The handle keeps 16 bytes per vertex
+ * Needs every chunk of the topology device-resident (NTP_EBUDGET otherwise); alpha_out is not
+ * available for graphs built with NTP_SCATTER_BWD (NTP_EUNSUPPORTED).  Deterministic.  The handle keeps 16 bytes per vertex
  * of scratch from the first call on; calls on one handle must not overlap.
  */
 int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negative_slope,

@@ -194,43 +194,50 @@ int launch_rows(const AttArgs& a, int first, int n_rows, hipStream_t st) {
 
 }  // namespace
 
+// One chunk of a form, one phase at a time (a row beyond the split threshold may have its
+// segments in several chunks, so the caller runs a phase over all chunks before the next):
+//   phase 0: per-segment statistics of split rows (by-destination pass only)
+//   phase 1: per-row combination of the segment statistics (by-destination pass only)
+//   phase 2: weights of the split rows' segments and of all other rows
 // bins: bin_row_off / bin_count describe rows[] (see Plan); bins 0..3 hold rows of up to 8
 // entries, 4..5 up to 32, the rest up to the split threshold; split rows come as segments
 // (segs, n_segs), their rows as reduce items; seg_stats: two floats per partial-sum slot.
 int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t* bin_count,
                      const Segment* segs, int n_segs, const ReduceItem* split_rows, int n_split_rows,
-                     float* seg_stats, bool transposed, void* stream) {
+                     float* seg_stats, bool transposed, int phase, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    auto span = [&](int b0, int b1, int& first, int& count) {
-        first = bin_row_off[b0];
-        count = 0;
-        for (int b = b0; b <= b1; ++b) count += bin_count[b];
-    };
-    int first, count, rc = NTP_OK;
-    // long rows first: they are the longest-running pieces
-    if (n_segs > 0) {
-        if (transposed) {
-            hipLaunchKernelGGL(attention_segment_write_kernel<true>, dim3((unsigned)n_segs), dim3(256), 0, st, a, segs);
-        } else {
-            float2* ss = reinterpret_cast<float2*>(seg_stats);
+    float2* ss = reinterpret_cast<float2*>(seg_stats);
+    int rc = NTP_OK;
+    if (phase == 0) {
+        if (!transposed && n_segs > 0)
             hipLaunchKernelGGL(attention_segment_stats_kernel, dim3((unsigned)n_segs), dim3(256), 0, st, a, segs, ss);
+    } else if (phase == 1) {
+        if (!transposed && n_split_rows > 0)
             hipLaunchKernelGGL(attention_combine_kernel, dim3((unsigned)n_split_rows), dim3(64), 0, st, a, split_rows, ss);
-            hipLaunchKernelGGL(attention_segment_write_kernel<false>, dim3((unsigned)n_segs), dim3(256), 0, st, a, segs);
+    } else {
+        auto span = [&](int b0, int b1, int& first, int& count) {
+            first = bin_row_off[b0];
+            count = 0;
+            for (int b = b0; b <= b1; ++b) count += bin_count[b];
+        };
+        int first, count;
+        // long rows first: they are the longest-running pieces
+        if (n_segs > 0) {
+            if (transposed) hipLaunchKernelGGL(attention_segment_write_kernel<true>, dim3((unsigned)n_segs), dim3(256), 0, st, a, segs);
+            else hipLaunchKernelGGL(attention_segment_write_kernel<false>, dim3((unsigned)n_segs), dim3(256), 0, st, a, segs);
         }
-        rc = hipGetLastError() == hipSuccess ? NTP_OK : NTP_EHIP;
-    }
-    if (rc == NTP_OK) {
         span(6, NBINS - 1, first, count);
         rc = transposed ? launch_rows<64, true>(a, first, count, st) : launch_rows<64, false>(a, first, count, st);
+        if (rc == NTP_OK) {
+            span(4, 5, first, count);
+            rc = transposed ? launch_rows<32, true>(a, first, count, st) : launch_rows<32, false>(a, first, count, st);
+        }
+        if (rc == NTP_OK) {
+            span(0, 3, first, count);
+            rc = transposed ? launch_rows<8, true>(a, first, count, st) : launch_rows<8, false>(a, first, count, st);
+        }
     }
-    if (rc == NTP_OK) {
-        span(4, 5, first, count);
-        rc = transposed ? launch_rows<32, true>(a, first, count, st) : launch_rows<32, false>(a, first, count, st);
-    }
-    if (rc == NTP_OK) {
-        span(0, 3, first, count);
-        rc = transposed ? launch_rows<8, true>(a, first, count, st) : launch_rows<8, false>(a, first, count, st);
-    }
+    if (rc == NTP_OK && hipGetLastError() != hipSuccess) rc = NTP_EHIP;
     if (rc != NTP_OK) set_error("attention kernel launch failed");
     return rc;
 }

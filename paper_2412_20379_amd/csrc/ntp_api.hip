@@ -519,10 +519,9 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
     if (alpha_out && g->scatter_bwd()) { set_error("graph was built with NTP_SCATTER_BWD: no by-source form is stored"); return NTP_EUNSUPPORTED; }
     Form& Fin = g->f(NTP_CSR);
     Form& Fout = g->f(NTP_CSC);
-    auto one_resident_chunk = [](const Form& F) { return F.plan.chunks.size() == 1 && F.plan.chunks[0].d_image; };
-    if (!one_resident_chunk(Fin) || (alpha_out && !one_resident_chunk(Fout))) {
-        set_error("attention weights need the topology as one device-resident chunk (build without chunk_edges and budget)");
-        return NTP_EUNSUPPORTED;
+    if (!Fin.all_resident || (alpha_out && !Fout.all_resident)) {
+        set_error("attention weights need every chunk of the topology device-resident");
+        return NTP_EBUDGET;
     }
     // scratch kept by the handle: 16 bytes per vertex + 8 bytes per segment of a split row
     const int64_t seg_floats = 2 * Fin.plan.n_slots;
@@ -534,20 +533,25 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
         g->device_bytes += (int64_t)bytes;
     }
     float* seg_stats = g->att_stats + 4 * n;
+    // chunk by chunk, phase by phase (a split row's segments may lie in several chunks)
     auto run = [&](const Form& F, float* out, bool transposed) -> int {
-        const Chunk& c = F.plan.chunks[0];
-        AttArgs a;
-        a.rowptr = reinterpret_cast<const int64_t*>(c.d_image + c.off_rowptr);
-        a.colidx = reinterpret_cast<const int32_t*>(c.d_image + c.img_off_colidx);
-        a.rows = reinterpret_cast<const int32_t*>(c.d_image + c.off_rows);
-        a.p = p; a.q = q;
-        a.st = g->att_stats;
-        a.alpha = out;
-        a.slope = negative_slope;
-        return launch_attention(a, c.bin_row_off, c.bin_count,
-                                reinterpret_cast<const Segment*>(c.d_image + c.off_segs), c.n_segs,
-                                reinterpret_cast<const ReduceItem*>(c.d_image + c.off_reduce), c.n_reduce,
-                                seg_stats, transposed, stream);
+        for (int phase = transposed ? 2 : 0; phase < 3; ++phase)
+            for (const Chunk& c : F.plan.chunks) {
+                AttArgs a;
+                a.rowptr = reinterpret_cast<const int64_t*>(c.d_image + c.off_rowptr) - c.row_begin;
+                a.colidx = reinterpret_cast<const int32_t*>(c.d_image + c.img_off_colidx) - c.e_begin;
+                a.rows = reinterpret_cast<const int32_t*>(c.d_image + c.off_rows);
+                a.p = p; a.q = q;
+                a.st = g->att_stats;
+                a.alpha = out;
+                a.slope = negative_slope;
+                const int rc = launch_attention(a, c.bin_row_off, c.bin_count,
+                                                reinterpret_cast<const Segment*>(c.d_image + c.off_segs), c.n_segs,
+                                                reinterpret_cast<const ReduceItem*>(c.d_image + c.off_reduce), c.n_reduce,
+                                                seg_stats, transposed, phase, stream);
+                if (rc != NTP_OK) return rc;
+            }
+        return NTP_OK;
     };
     int rc = run(Fin, alpha_in, false);
     if (rc == NTP_OK && alpha_out) rc = run(Fout, alpha_out, true);

@@ -168,8 +168,8 @@ int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t l
 
 // edge attention weights (attention_kernels.hip)
 struct AttArgs {
-    const int64_t* rowptr;     // whole form: rowptr[row]
-    const int32_t* colidx;
+    const int64_t* rowptr;     // indexed by the global row id (a chunk's slice, shifted)
+    const int32_t* colidx;     // indexed by the global entry offset (a chunk's slice, shifted)
     const int32_t* rows;       // bin row lists
     const float* p;            // per-vertex source score
     const float* q;            // per-vertex destination score
@@ -180,7 +180,7 @@ struct AttArgs {
 };
 int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t* bin_count,
                      const Segment* segs, int n_segs, const ReduceItem* split_rows, int n_split_rows,
-                     float* seg_stats, bool transposed, void* stream);
+                     float* seg_stats, bool transposed, int phase, void* stream);
 
 int launch_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss, float* scratch,
                         int64_t n, int64_t c, int64_t ldz, int64_t lddz, void* stream);

@@ -190,10 +190,26 @@ def test_attention_argument_errors(hub):
         ntp.ntp_edge_softmax(g, dev_f32(p), dev_f32(q), -0.5, a)
     with pytest.raises(ntp.NtpError):
         ntp.ntp_edge_softmax(g, None, dev_f32(q), 0.2, a)
-    chunked = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=5000)
+    streamed = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | ntp.NTP_FORCE_STREAM, chunk_edges=5000)
     with pytest.raises(ntp.NtpError) as e:
-        ntp.ntp_edge_softmax(chunked, dev_f32(p), dev_f32(q), 0.2, a)
-    assert e.value.code == ntp.NTP_EUNSUPPORTED
-    chunked.close()
+        ntp.ntp_edge_softmax(streamed, dev_f32(p), dev_f32(q), 0.2, a)
+    assert e.value.code == ntp.NTP_EBUDGET
+    streamed.close()
     with pytest.raises(ntp.NtpError):
         ntp.ntp_aggregate_weighted(g, 7, a, a, a, 4, 4, 4)
+
+
+@pytest.mark.parametrize("chunk_edges", [101, 700, 5003])
+def test_attention_weights_on_a_chunked_resident_graph(hub, chunk_edges):
+    """several resident chunks, among them pieces of the hub's row: the bits of the one-chunk graph"""
+    import torch
+    n, src, dst, g, og = hub
+    p, q = _scores(n, 12)
+    a_in, a_out = _device_alpha(g, og.csr.nnz, p, q, 0.2)
+    gc = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=chunk_edges)
+    assert ntp.ntp_graph_info(gc)["n_chunks"] > 1
+    c_in, c_out = _device_alpha(gc, og.csr.nnz, p, q, 0.2)
+    _check_alpha(og, c_in, c_out, p, q, 0.2, "chunked %d" % chunk_edges)
+    if chunk_edges >= 5003:          # same segments as the one-chunk plan: identical reduction trees
+        assert torch.equal(a_in, c_in) and torch.equal(a_out, c_out)
+    gc.close()
