@@ -70,3 +70,46 @@ def weighted(g: Graph, alpha_in, alpha_out) -> Graph:
     return replace(g,
                    csr=Sparse(g.csr.rowptr, g.csr.colidx, np.asarray(alpha_in, dtype=np.float32)),
                    csc=Sparse(g.csc.rowptr, g.csc.colidx, np.asarray(alpha_out, dtype=np.float32)))
+
+
+def edge_softmax_bwd(g: Graph, p, q, Z, dY, negative_slope: float = 0.2):
+    """Gradient of a scalar loss with respect to the scores p and q through the attention
+    weights, when the loss depends on them only through Y = sum_u alpha(u -> v) Z[u]
+    (AGG of GAT, Section 2.1) and dY = dLoss/dY is given.  Chain rule, step by step:
+
+        dalpha(u -> v) = dY[v] . Z[u]
+        t[v]           = sum_u alpha(u -> v) dalpha(u -> v)
+        de(u -> v)     = alpha(u -> v) (dalpha(u -> v) - t[v])                (softmax over the in-edges of v)
+        ds(u -> v)     = de(u -> v) * (1 if p[u] + q[v] > 0 else negative_slope)   (LeakyReLU)
+        dq[v]          = sum over the in-edges of v of ds,   dp[u] = sum over the out-edges of u of ds
+
+    Returns (dp, dq, scale_p, scale_q) in float64; the scales are the sums of |alpha| (|dalpha| + |t|)
+    over the same edges (what bounds the rounding error of any evaluation order).
+    """
+    p = np.asarray(p, dtype=np.float64)
+    q = np.asarray(q, dtype=np.float64)
+    Z = np.asarray(Z, dtype=np.float64)
+    dY = np.asarray(dY, dtype=np.float64)
+    alpha_in, _ = edge_softmax(g, p, q, negative_slope)
+    n = g.n
+    csr = g.csr
+    dp = np.zeros(n)
+    dq = np.zeros(n)
+    sp = np.zeros(n)
+    sq = np.zeros(n)
+    for v in range(n):
+        b, e = int(csr.rowptr[v]), int(csr.rowptr[v + 1])
+        if e == b:
+            continue
+        us = csr.colidx[b:e]
+        a = alpha_in[b:e]
+        dalpha = Z[us] @ dY[v]
+        t = float(np.dot(a, dalpha))
+        de = a * (dalpha - t)
+        ds = de * np.where(p[us] + q[v] > 0, 1.0, negative_slope)
+        mag = a * (np.abs(dalpha) + abs(t))
+        dq[v] = ds.sum()
+        sq[v] = mag.sum()
+        np.add.at(dp, us, ds)
+        np.add.at(sp, us, mag)
+    return dp, dq, sp, sq

@@ -151,3 +151,52 @@ def test_a7_planted_mistakes_are_caught():
     assert max_diff(_brute_force(n, src, dst, p, q, 0.2, score=lambda u, v: p[v] + q[u])) > 1e-3     # endpoints swapped
     assert max_diff(_brute_force(n, src, dst, p, q, 0.2, over_out_edges=True)) > 1e-3               # wrong normalisation set
     assert max_diff(_brute_force(n, src, dst, p, q, 0.0)) > 1e-3                                    # slope dropped
+
+
+# ---- gradient of the attention weights with respect to the scores -------------------------------
+def _gat_loss(g, p, q, Z, dY, slope):
+    """L = sum_v dY[v] . (sum_u alpha(u -> v) Z[u]), from the forward oracle and a dense matrix"""
+    a_in, _ = oracle.edge_softmax(g, p, q, slope)
+    M = sp.csr_matrix((a_in, g.csr.colidx, g.csr.rowptr), shape=(g.n, g.n))
+    return float(np.sum(dY * (M @ Z)))
+
+
+@pytest.mark.parametrize("slope", [0.2, 0.0, 1.0])
+def test_a8_score_gradients_by_finite_differences(slope):
+    n, m = 25, 6
+    src, dst = gen.directed_random_edges(n, 120, 8, hub=3, hub_in=12, hub_out=5)
+    g = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    p, q = _scores(n, 8)
+    Z = gen.normal_features(n, m, 41).astype(np.float64)
+    dY = gen.normal_features(n, m, 42).astype(np.float64)
+    dp, dq, _, _ = oracle.edge_softmax_bwd(g, p, q, Z, dY, slope)
+    eps = 1e-6
+    for i in range(n):
+        for arr, grad in ((p, dp), (q, dq)):
+            save = arr[i]
+            arr[i] = save + eps
+            lp = _gat_loss(g, p, q, Z, dY, slope)
+            arr[i] = save - eps
+            lm = _gat_loss(g, p, q, Z, dY, slope)
+            arr[i] = save
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - grad[i]) <= 1e-7 * max(1.0, abs(fd)), (i, fd, grad[i])
+
+
+def test_a9_score_gradient_invariants():
+    """with slope 1 the weights do not depend on q at all, and a common shift of p changes
+    nothing: dq = 0 and sum(dp) = 0; in general the in-edge sums and the out-edge sums add up
+    the same edge terms: sum(dp) = sum(dq)"""
+    n, m = 200, 9
+    g = _directed(n, 1500, 13)
+    p, q = _scores(n, 13)
+    Z = gen.normal_features(n, m, 43).astype(np.float64)
+    dY = gen.normal_features(n, m, 44).astype(np.float64)
+    dp, dq, sp_, sq_ = oracle.edge_softmax_bwd(g, p, q, Z, dY, 1.0)
+    assert np.abs(dq).max() <= 1e-13 * sq_.max()
+    assert abs(dp.sum()) <= 1e-12 * sp_.sum()
+    dp, dq, sp_, sq_ = oracle.edge_softmax_bwd(g, p, q, Z, dY, 0.2)
+    assert abs(dp.sum() - dq.sum()) <= 1e-12 * sp_.sum()
+    # constant features: every dalpha of a row is the same number, so the softmax gradient vanishes
+    dp, dq, _, _ = oracle.edge_softmax_bwd(g, p, q, np.ones((n, m)), dY, 0.2)
+    assert np.abs(dp).max() <= 1e-12 and np.abs(dq).max() <= 1e-12
