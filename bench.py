@@ -322,6 +322,12 @@ def main():
         t_att_in = timed(lambda: ntp.ntp_edge_softmax(g, p, q, 0.2, a_in, None, st))
         t_w = timed(lambda: ntp.ntp_aggregate_weighted(g, ntp.NTP_FWD, a_in, x, y, f, ld, ld, ntp.NTP_F32, st))
         t_s = timed(lambda: ntp.ntp_aggregate_fwd(g, x, y, f, ld, ld, ntp.NTP_F32, st))
+        # gradient of the scores through the weights: two passes that each gather one feature row
+        # per edge (as an aggregation of that width does) and form a dot product with it
+        dp = torch.empty(n, device=dev)
+        dq = torch.empty(n, device=dev)
+        dy = torch.randn(n, ld, generator=tg, device=dev)
+        t_sg = timed(lambda: ntp.ntp_edge_softmax_bwd(g, p, q, 0.2, a_in, a_out, x, dy, f, ld, ld, dp, dq, st))
         # algorithmic bytes: by-destination pass reads indices, writes weights (8 B per entry) plus
         # per-vertex arrays (row pointers, p, q, the two statistics); the by-source pass the same
         # per entry plus reads of the statistics
@@ -332,10 +338,13 @@ def main():
                "edge_softmax_gbs": (b_in + b_out) / (t_att * 1e-3) / 1e9,
                "edge_softmax_frac_hbm": (b_in + b_out) / (t_att * 1e-3) / 1e9 / HBM_PEAK_GBS,
                "edges_per_s_both_orders": nnz / (t_att * 1e-3),
-               "aggregate_weighted_fwd_ms": t_w, "aggregate_stored_weights_fwd_ms": t_s}
+               "aggregate_weighted_fwd_ms": t_w, "aggregate_stored_weights_fwd_ms": t_s,
+               "edge_softmax_bwd_ms": t_sg, "edge_softmax_bwd_vs_two_aggregations": t_sg / (2 * t_w),
+               "edge_softmax_bwd_gathered_gbs": 2 * nnz * f * 4 / (t_sg * 1e-3) / 1e9}
         log("edge softmax: %.3f ms both orders (%.0f GB/s algorithmic, %.1f%% of 8 TB/s), %.3f ms by destination only; "
-            "weighted aggregation f=%d %.3f ms (stored weights %.3f ms)"
-            % (t_att, out["edge_softmax_gbs"], 100 * out["edge_softmax_frac_hbm"], t_att_in, f, t_w, t_s))
+            "weighted aggregation f=%d %.3f ms (stored weights %.3f ms); score gradient %.3f ms (%.2f x two aggregations)"
+            % (t_att, out["edge_softmax_gbs"], 100 * out["edge_softmax_frac_hbm"], t_att_in, f, t_w, t_s, t_sg,
+               out["edge_softmax_bwd_vs_two_aggregations"]))
         print(json.dumps(out), flush=True)
         g.close()
         return

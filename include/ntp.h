@@ -197,6 +197,30 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
                      float* alpha_in, float* alpha_out, void* stream);
 
 /*
+ * Gradient of the scores p, q through the attention weights of ntp_edge_softmax, for the weighted
+ * aggregation Y[v,:] = sum over in-edges u -> v of alpha(u -> v) Z[u,:] (the backward counterpart
+ * of the edge-associated computation of Section 4.1, chained through the softmax and LeakyReLU of
+ * the GAT aggregation of Section 2.1).  With dY = dLoss/dY:
+ *     dalpha(u -> v) = dY[v,:] . Z[u,:]
+ *     t[v]           = sum over in-edges of alpha dalpha
+ *     de(u -> v)     = alpha (dalpha - t[v])
+ *     ds(u -> v)     = de * (1 if p[u] + q[v] > 0 else negative_slope)
+ *     dq[v] = sum over the in-edges of v of ds,   dp[u] = sum over the out-edges of u of ds.
+ * (The gradient with respect to Z itself is ntp_aggregate_weighted(NTP_BWD, alpha_out, dY).)
+ * p, q [n] device fp32: the scores the weights were computed from; alpha_in, alpha_out [nnz]: both
+ * outputs of ntp_edge_softmax; Z, dY [n x m] device fp32, row strides ldz, lddy >= m,
+ * 1 <= m <= 1024 when both are 16-byte aligned with m and the strides multiples of 4, m <= 256
+ * otherwise (NTP_EUNSUPPORTED); dp, dq [n] device fp32 outputs (every element written).
+ * Needs every chunk device-resident (NTP_EBUDGET) and a by-source form (NTP_EUNSUPPORTED for
+ * NTP_SCATTER_BWD graphs); a vertex whose edges span several chunks is not taken
+ * (NTP_EUNSUPPORTED).  Deterministic.  The handle keeps 4 bytes per edge + 4 per vertex of scratch
+ * from the first call on; calls on one handle must not overlap.
+ */
+int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float negative_slope,
+                         const float* alpha_in, const float* alpha_out, const float* Z, const float* dY,
+                         int64_t m, int64_t ldz, int64_t lddy, float* dp, float* dq, void* stream);
+
+/*
  * ntp_aggregate_fwd / ntp_aggregate_bwd with caller-supplied edge weights in place of the
  * stored ones (gamma of Section 4.1: attention weights, or any per-edge weight):
  *   NTP_FWD: Y[v,:] = sum over entries k of row v of the by-destination form  weights[k] X[colidx[k],:]

@@ -21,7 +21,7 @@ NTP_ACT_NONE, NTP_ACT_RELU = 0, 1
 EXPORTED_SYMBOLS = [
     "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_chunks",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
-    "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_aggregate_weighted",
+    "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_edge_softmax_bwd", "ntp_aggregate_weighted",
     "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent", "ntp_softmax_xent_scratch_bytes", "ntp_relu_fwd", "ntp_relu_bwd",
     "ntp_graph_free", "ntp_last_error",
 ]
@@ -61,6 +61,7 @@ def lib():
     L.ntp_chunked_aggregate.argtypes = [vp, ctypes.c_int, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_chunked_aggregate_multi.argtypes = [vp, ctypes.c_int, i32, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_edge_softmax.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp]
+    L.ntp_edge_softmax_bwd.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
     L.ntp_aggregate_weighted.argtypes = [vp, ctypes.c_int, vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_nn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp]
     L.ntp_nn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, i64, vp]
@@ -195,6 +196,11 @@ def ntp_aggregate_bwd(g: Graph, Gout, Gin, f_slice, ldg_out, ldg_in, dtype=NTP_F
 def ntp_edge_softmax(g: Graph, p, q, negative_slope, alpha_in, alpha_out=None, stream=None):
     _check(lib().ntp_edge_softmax(g.handle, _ptr(p), _ptr(q), float(negative_slope), _ptr(alpha_in), _ptr(alpha_out),
                                   _stream(stream)))
+
+
+def ntp_edge_softmax_bwd(g: Graph, p, q, negative_slope, alpha_in, alpha_out, Z, dY, m, ldz, lddy, dp, dq, stream=None):
+    _check(lib().ntp_edge_softmax_bwd(g.handle, _ptr(p), _ptr(q), float(negative_slope), _ptr(alpha_in), _ptr(alpha_out),
+                                      _ptr(Z), _ptr(dY), int(m), int(ldz), int(lddy), _ptr(dp), _ptr(dq), _stream(stream)))
 
 
 def ntp_aggregate_weighted(g: Graph, direction, weights, X, Y, f_slice, ldx, ldy, dtype=NTP_F32, stream=None):

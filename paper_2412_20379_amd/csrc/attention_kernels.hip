@@ -184,6 +184,185 @@ __global__ void __launch_bounds__(256) attention_segment_write_kernel(const AttA
     }
 }
 
+// ---- gradient of the scores through the attention weights --------------------------------------
+// Given dY = dLoss/dY of Y[v,:] = sum_u alpha(u -> v) Z[u,:]:
+//   dalpha(u -> v) = dY[v,:] . Z[u,:],  t[v] = sum_u alpha dalpha,  de = alpha (dalpha - t[v]),
+//   ds = de * (1 if p[u] + q[v] > 0 else slope),  dq[v] = sum over in-edges of ds,
+//   dp[u] = sum over out-edges of ds.
+// By-destination pass (rows v, own = dY[v,:], gathered = Z[u,:]): dalpha of every entry (parked in
+// scratch), t[v], dq[v].  By-source pass (rows u, own = Z[u,:], gathered = dY[v,:]): dalpha again
+// in that order, with t[v] and alpha in by-source order: dp[u].  A group of 16 lanes forms one dot
+// product at a time (16 x VEC x NJ columns, xor tree over the 16 lanes); rows beyond the split
+// threshold take one block (16 groups over the entries, partial sums combined through LDS in a
+// fixed order).  Every entry's parked dalpha is read back by the thread that wrote it.
+template <int VEC, int NJ>
+struct DotRow {
+    float own[NJ][VEC];
+    int col[NJ];
+    bool on[NJ];
+    __device__ __forceinline__ void load_own(const float* row, int l, int m) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            col[j] = (j * 16 + l) * VEC;
+            on[j] = col[j] < m;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) own[j][i] = 0.f;
+            if (on[j]) {
+                if constexpr (VEC == 4) { const float4 t = *reinterpret_cast<const float4*>(row + col[j]); own[j][0] = t.x; own[j][1] = t.y; own[j][2] = t.z; own[j][3] = t.w; }
+                else own[j][0] = row[col[j]];
+            }
+        }
+    }
+    // this lane's share of own . other (columns outside the row contribute zero)
+    __device__ __forceinline__ float partial(const float* other) const {
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            if (on[j]) {
+                if constexpr (VEC == 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(other + col[j]);
+                    acc = fmaf(own[j][0], t.x, acc); acc = fmaf(own[j][1], t.y, acc);
+                    acc = fmaf(own[j][2], t.z, acc); acc = fmaf(own[j][3], t.w, acc);
+                } else {
+                    acc = fmaf(own[j][0], other[col[j]], acc);
+                }
+            }
+        }
+        return acc;
+    }
+};
+
+// BLOCK = false: four rows per wavefront (one group each), rows[first .. first + n_rows).
+// BLOCK = true : one row per block of 16 groups: items[blockIdx.x].row, or rows[first + blockIdx.x]
+//                when items is null.
+template <int VEC, int NJ, bool TRANSPOSED, bool BLOCK>
+__global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, int first, int n_rows, const ReduceItem* items) {
+    __shared__ float red[16];
+    constexpr int U = 4;                                               // dot products in flight per group
+    const int lane = threadIdx.x & 63;
+    const int l = lane & 15;
+    const int gi = BLOCK ? (int)(threadIdx.x >> 4) : (lane >> 4);      // group inside the block / wavefront
+    constexpr int GSTRIDE = BLOCK ? 16 : 1;                            // groups sharing a row
+    int row = 0;
+    bool valid = true;
+    if constexpr (BLOCK) {
+        row = items ? items[blockIdx.x].row : a.rows[first + blockIdx.x];
+    } else {
+        const int64_t idx = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + gi;
+        valid = idx < n_rows;
+        if (valid) row = a.rows[first + idx];
+    }
+    int64_t beg = 0, d = 0;
+    if (valid) { beg = a.rowptr[row]; d = a.rowptr[row + 1] - beg; }
+    const int32_t* ci = a.colidx + beg;
+    const float* al = a.alpha + beg;
+    DotRow<VEC, NJ> dot;
+    dot.load_own(a.own + (int64_t)row * a.ld_own, l, valid ? a.m : 0);
+    const int k_first = BLOCK ? gi : 0;
+    // dalpha of entries k, k + GSTRIDE, ...: U gathers issued before the first xor tree
+    auto dots = [&](int64_t k, bool (&in)[U], int (&c)[U], float (&da)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) { in[u] = k + u * GSTRIDE < d; c[u] = in[u] ? ci[k + u * GSTRIDE] : row; }
+#pragma unroll
+        for (int u = 0; u < U; ++u) da[u] = dot.partial(a.other + (int64_t)c[u] * a.ld_other);
+#pragma unroll
+        for (int u = 0; u < U; ++u) da[u] = group_sum<16>(da[u], lane);
+    };
+    bool in[U];
+    int c[U];
+    float da[U];
+    if constexpr (TRANSPOSED) {
+        const float pu = valid ? a.p[row] : 0.f;
+        float acc = 0.f;
+        for (int64_t k = k_first; __ballot(k < d) != 0; k += U * GSTRIDE) {   // the wavefront stays together for the shuffles
+            dots(k, in, c, da);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (in[u]) acc += al[k + u * GSTRIDE] * (da[u] - a.t[c[u]]) * (pu + a.q[c[u]] > 0.f ? 1.f : a.slope);
+        }
+        if constexpr (BLOCK) {
+            if (l == 0) red[gi] = acc;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                float s = 0.f;
+                for (int i = 0; i < 16; ++i) s += red[i];
+                a.out[row] = s;
+            }
+        } else {
+            if (valid && l == 0) a.out[row] = acc;
+        }
+        return;
+    }
+    // by destination: sweep 1 = dalpha of every entry (parked by the lane that reads it back), t
+    float* park = a.park + beg;
+    float t = 0.f;
+    for (int64_t k = k_first; __ballot(k < d) != 0; k += U * GSTRIDE) {
+        dots(k, in, c, da);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (in[u]) {
+                const int64_t ku = k + u * GSTRIDE;
+                t += al[ku] * da[u];
+                const int owner = BLOCK ? (int)((ku / 16) & 15) : (int)(ku & 15);
+                if (l == owner) park[ku] = da[u];
+            }
+        }
+    }
+    if constexpr (BLOCK) {
+        if (l == 0) red[gi] = t;
+        __syncthreads();
+        t = 0.f;
+        for (int i = 0; i < 16; ++i) t += red[i];
+        __syncthreads();
+    }
+    // sweep 2: ds of the entries this lane parked, summed over the row
+    const float qv = valid ? a.q[row] : 0.f;
+    float dqp = 0.f;
+    for (int64_t k = BLOCK ? gi + 16 * l : l; k < d; k += BLOCK ? 256 : 16) {   // BLOCK: k % 16 == gi, (k / 16) % 16 == l
+        const int cc = ci[k];
+        dqp += al[k] * (park[k] - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
+    }
+    dqp = group_sum<16>(dqp, lane);
+    if constexpr (BLOCK) {
+        if (l == 0) red[gi] = dqp;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float s = 0.f;
+            for (int i = 0; i < 16; ++i) s += red[i];
+            a.out[row] = s;
+            a.t[row] = t;
+        }
+    } else {
+        if (valid && l == 0) { a.out[row] = dqp; a.t[row] = t; }
+    }
+}
+
+template <int VEC, int NJ, bool T>
+int launch_bwd_shape(const AttBwdArgs& a, const AttBwdRows& r, hipStream_t st) {
+    if (r.n_split_rows > 0)
+        hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, true>), dim3((unsigned)r.n_split_rows), dim3(256), 0, st, a, 0, 0, r.split_rows);
+    if (r.n_block_rows > 0)
+        hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, true>), dim3((unsigned)r.n_block_rows), dim3(256), 0, st, a, r.n_group_rows, 0,
+                           (const ReduceItem*)nullptr);
+    if (r.n_group_rows > 0)
+        hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, false>), dim3((unsigned)((r.n_group_rows + 15) / 16)), dim3(256), 0, st, a, 0,
+                           r.n_group_rows, (const ReduceItem*)nullptr);
+    return hipGetLastError() == hipSuccess ? NTP_OK : NTP_EHIP;
+}
+
+template <int VEC, bool T>
+int launch_bwd_vec(const AttBwdArgs& a, const AttBwdRows& r, hipStream_t st) {
+    const int per = 16 * VEC;
+    const int nj = (a.m + per - 1) / per;
+    if (nj <= 1) return launch_bwd_shape<VEC, 1, T>(a, r, st);
+    if (nj <= 2) return launch_bwd_shape<VEC, 2, T>(a, r, st);
+    if (nj <= 4) return launch_bwd_shape<VEC, 4, T>(a, r, st);
+    if (nj <= 8) return launch_bwd_shape<VEC, 8, T>(a, r, st);
+    if (nj <= 16) return launch_bwd_shape<VEC, 16, T>(a, r, st);
+    set_error("feature width %d too large for the attention gradient (at most %d)", a.m, 16 * per);
+    return NTP_EUNSUPPORTED;
+}
+
 template <int L, bool T>
 int launch_rows(const AttArgs& a, int first, int n_rows, hipStream_t st) {
     if (n_rows <= 0) return NTP_OK;
@@ -239,6 +418,20 @@ int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t
     }
     if (rc == NTP_OK && hipGetLastError() != hipSuccess) rc = NTP_EHIP;
     if (rc != NTP_OK) set_error("attention kernel launch failed");
+    return rc;
+}
+
+// widest feature row the gradient kernels take: 1024 columns with 16-byte vectors, 256 otherwise
+int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transposed, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    const bool vec4 = a.m % 4 == 0 && a.ld_own % 4 == 0 && a.ld_other % 4 == 0 &&
+                      (uintptr_t)a.own % 16 == 0 && (uintptr_t)a.other % 16 == 0;
+    int rc;
+    if (vec4) rc = transposed ? launch_bwd_vec<4, true>(a, r, st)
+                              : launch_bwd_vec<4, false>(a, r, st);
+    else rc = transposed ? launch_bwd_vec<1, true>(a, r, st)
+                         : launch_bwd_vec<1, false>(a, r, st);
+    if (rc == NTP_EHIP) set_error("attention gradient kernel launch failed");
     return rc;
 }
 

@@ -45,6 +45,7 @@ struct ntp_graph {
     float* partial = nullptr;
     size_t partial_bytes = 0;
     float* att_stats = nullptr;    // [4 n]: per-destination (q, maximum, 1 / sum, 0) of the last ntp_edge_softmax
+    float* att_bwd = nullptr;      // [nnz + n]: per-edge dalpha and per-destination t of ntp_edge_softmax_bwd
     int64_t device_bytes = 0;
 
     // the by-source product runs as a scatter over the by-destination form
@@ -215,6 +216,7 @@ void destroy(ntp_graph* G) {
     }
     if (G->partial) (void)hipFree(G->partial);
     if (G->att_stats) (void)hipFree(G->att_stats);
+    if (G->att_bwd) (void)hipFree(G->att_bwd);
     if (G->pinned_meta) (void)hipHostFree(G->pinned_meta);
     free_entries(G->g.csr, G->pinned_entries);
     free_entries(G->g.csc, G->pinned_entries);
@@ -555,6 +557,69 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
     };
     int rc = run(Fin, alpha_in, false);
     if (rc == NTP_OK && alpha_out) rc = run(Fout, alpha_out, true);
+    return rc;
+}
+
+int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float negative_slope,
+                         const float* alpha_in, const float* alpha_out, const float* Z, const float* dY,
+                         int64_t m, int64_t ldz, int64_t lddy, float* dp, float* dq, void* stream) {
+    if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
+    if (g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
+    if (!(negative_slope >= 0.f) || !(negative_slope <= 1.f)) { set_error("negative_slope must be in [0, 1]"); return NTP_EINVAL; }
+    if (m < 1 || m > 1024 || ldz < m || lddy < m) { set_error("bad feature shape m=%lld ldz=%lld lddy=%lld (1 <= m <= 1024)", (long long)m, (long long)ldz, (long long)lddy); return NTP_EINVAL; }
+    const int64_t n = g->g.n;
+    if (n == 0) return NTP_OK;
+    if (!p || !q || !alpha_in || !alpha_out || !Z || !dY || !dp || !dq) { set_error("NULL buffer"); return NTP_EINVAL; }
+    if (g->scatter_bwd()) { set_error("graph was built with NTP_SCATTER_BWD: no by-source form is stored"); return NTP_EUNSUPPORTED; }
+    Form& Fin = g->f(NTP_CSR);
+    Form& Fout = g->f(NTP_CSC);
+    if (!Fin.all_resident || !Fout.all_resident) {
+        set_error("the attention gradient needs every chunk of the topology device-resident");
+        return NTP_EBUDGET;
+    }
+    for (const Form* F : {&Fin, &Fout})
+        for (const Chunk& c : F->plan.chunks)
+            if (c.partial_row) { set_error("the attention gradient does not take a vertex whose edges span several chunks"); return NTP_EUNSUPPORTED; }
+    // scratch kept by the handle: dalpha of every edge + t of every destination
+    const int64_t nnz = g->g.csr.nnz;
+    if (!g->att_bwd) {
+        void* ptr = nullptr;
+        const size_t bytes = ((size_t)nnz + (size_t)n) * 4 + 16;
+        if (hipMalloc(&ptr, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes failed", bytes); return NTP_ENOMEM; }
+        g->att_bwd = (float*)ptr;
+        g->device_bytes += (int64_t)bytes;
+    }
+    float* park = g->att_bwd;
+    float* t = g->att_bwd + nnz;
+    auto run = [&](const Form& F, bool transposed) -> int {
+        for (const Chunk& c : F.plan.chunks) {
+            AttBwdArgs a;
+            a.rowptr = reinterpret_cast<const int64_t*>(c.d_image + c.off_rowptr) - c.row_begin;
+            a.colidx = reinterpret_cast<const int32_t*>(c.d_image + c.img_off_colidx) - c.e_begin;
+            a.rows = reinterpret_cast<const int32_t*>(c.d_image + c.off_rows);
+            a.p = p; a.q = q;
+            a.alpha = transposed ? alpha_out : alpha_in;
+            a.own = transposed ? Z : dY;
+            a.ld_own = transposed ? ldz : lddy;
+            a.other = transposed ? dY : Z;
+            a.ld_other = transposed ? lddy : ldz;
+            a.t = t;
+            a.park = park;
+            a.out = transposed ? dp : dq;
+            a.slope = negative_slope;
+            a.m = (int32_t)m;
+            AttBwdRows r;
+            r.n_group_rows = c.bin_row_off[NBINS - 1];
+            r.n_block_rows = c.bin_count[NBINS - 1];
+            r.split_rows = reinterpret_cast<const ReduceItem*>(c.d_image + c.off_reduce);
+            r.n_split_rows = c.n_reduce;
+            const int rc = launch_attention_bwd(a, r, transposed, stream);
+            if (rc != NTP_OK) return rc;
+        }
+        return NTP_OK;
+    };
+    int rc = run(Fin, false);           // dq and t first: the by-source pass reads t
+    if (rc == NTP_OK) rc = run(Fout, true);
     return rc;
 }
 

@@ -182,6 +182,32 @@ int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t
                      const Segment* segs, int n_segs, const ReduceItem* split_rows, int n_split_rows,
                      float* seg_stats, bool transposed, int phase, void* stream);
 
+struct AttBwdArgs {
+    const int64_t* rowptr;     // indexed by the global row id
+    const int32_t* colidx;     // indexed by the global entry offset
+    const int32_t* rows;       // all rows below the split threshold (the bin lists, one after the other)
+    const float* p;
+    const float* q;
+    const float* alpha;        // attention weights in this form's entry order
+    const float* own;          // row vectors of this form's rows: dY (by destination) or Z (by source)
+    const float* other;        // row vectors gathered by column id: Z (by destination) or dY (by source)
+    int64_t ld_own, ld_other;
+    float* t;                  // per destination: sum of alpha * dalpha
+    float* park;               // [nnz] dalpha per entry (by-destination pass)
+    float* out;                // dq (by destination) or dp (by source)
+    float slope;
+    int32_t m;                 // feature width
+};
+// rows[0 .. n_group_rows): a group of 16 lanes each; rows[n_group_rows .. + n_block_rows) and the
+// split rows: a block each (the bin lists are stored by increasing entry count)
+struct AttBwdRows {
+    int n_group_rows;
+    int n_block_rows;
+    const ReduceItem* split_rows;
+    int n_split_rows;
+};
+int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transposed, void* stream);
+
 int launch_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss, float* scratch,
                         int64_t n, int64_t c, int64_t ldz, int64_t lddz, void* stream);
 

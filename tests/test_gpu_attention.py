@@ -213,3 +213,156 @@ def test_attention_weights_on_a_chunked_resident_graph(hub, chunk_edges):
     if chunk_edges >= 5003:          # same segments as the one-chunk plan: identical reduction trees
         assert torch.equal(a_in, c_in) and torch.equal(a_out, c_out)
     gc.close()
+
+
+# ---- gradient of the scores through the attention weights (ntp_edge_softmax_bwd) ---------------
+TOL_SCORE_GRAD = 1e-5     # relative to the sum of the magnitudes that enter each gradient
+
+
+def _grad_scales(og, p, q, Z, dY, slope):
+    """per vertex: sum over its edges of alpha (A + sum alpha A), A = |dY[v]| . |Z[u]| -- the
+    magnitude of everything that is added up to form dq[v] (by destination) and dp[u] (by source)"""
+    a_in, _ = oracle.edge_softmax(og, p, q, slope)
+    n = og.n
+    rp, ci = og.csr.rowptr, og.csr.colidx
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    A = np.einsum("ej,ej->e", np.abs(dY.astype(np.float64))[rows], np.abs(Z.astype(np.float64))[ci])
+    tA = np.zeros(n)
+    np.add.at(tA, rows, a_in * A)
+    mag = a_in * (A + tA[rows])
+    sq = np.zeros(n)
+    sp = np.zeros(n)
+    np.add.at(sq, rows, mag)
+    np.add.at(sp, ci, mag)
+    return sp, sq
+
+
+def _score_grad_case(g, og, m, slope, seed, what, ldz=None, lddy=None, scale=1.0):
+    import torch
+    from gpu_util import dev_f32
+    n, nnz = og.n, og.csr.nnz
+    ldz = ldz or m
+    lddy = lddy or m
+    p, q = _scores(n, seed)
+    rng = gen.stream_rng(seed, 77)
+    Z = (rng.normal(size=(n, m)) * scale).astype(np.float32)
+    dY = (rng.normal(size=(n, m)) * scale).astype(np.float32)
+    say("   score gradient: %s n=%d nnz=%d m=%d ldz=%d lddy=%d slope=%g" % (what, n, nnz, m, ldz, lddy, slope))
+    a_in, a_out = _device_alpha(g, nnz, p, q, slope)
+    Zd = torch.full((n, ldz), float("nan"), device="cuda:0")
+    Zd[:, :m] = dev_f32(Z)
+    dYd = torch.full((n, lddy), float("nan"), device="cuda:0")
+    dYd[:, :m] = dev_f32(dY)
+    dp = torch.full((n,), float("nan"), device="cuda:0")
+    dq = torch.full((n,), float("nan"), device="cuda:0")
+    ntp.ntp_edge_softmax_bwd(g, dev_f32(p), dev_f32(q), slope, a_in, a_out, Zd, dYd, m, ldz, lddy, dp, dq)
+    torch.cuda.synchronize()
+    r_dp, r_dq, _, _ = oracle.edge_softmax_bwd(og, p, q, Z, dY, slope)
+    sp, sq = _grad_scales(og, p, q, Z, dY, slope)
+    got_p = dp.cpu().numpy().astype(np.float64)
+    got_q = dq.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got_p)) and np.all(np.isfinite(got_q)), what
+    tiny = np.finfo(np.float32).tiny
+    ep = np.abs(got_p - r_dp) / np.maximum(sp, tiny)
+    eq = np.abs(got_q - r_dq) / np.maximum(sq, tiny)
+    say("      max |err| / scale: dp %.2e dq %.2e" % (ep.max(), eq.max()))
+    assert ep.max() <= TOL_SCORE_GRAD and eq.max() <= TOL_SCORE_GRAD, what
+    # normwise as well: the gradients as vectors
+    assert np.abs(got_p - r_dp).max() <= TOL_SCORE_GRAD * sp.max()
+    assert np.abs(got_q - r_dq).max() <= TOL_SCORE_GRAD * sq.max()
+    return dp, dq
+
+
+@pytest.mark.parametrize("m", [1, 8, 40, 50, 64, 128, 256, 1024])
+def test_score_gradient_widths(hub, m):
+    n, src, dst, g, og = hub
+    _score_grad_case(g, og, m, 0.2, 40 + m, "hub graph")
+
+
+@pytest.mark.parametrize("slope", [0.0, 1.0])
+def test_score_gradient_slopes(hub, slope):
+    n, src, dst, g, og = hub
+    _score_grad_case(g, og, 64, slope, 5, "hub graph")
+
+
+def test_score_gradient_strided_and_unaligned(hub):
+    n, src, dst, g, og = hub
+    _score_grad_case(g, og, 64, 0.2, 8, "padded rows", ldz=80, lddy=96)
+    _score_grad_case(g, og, 64, 0.2, 9, "odd strides (scalar loads)", ldz=67, lddy=65)
+    _score_grad_case(g, og, 24, 0.2, 10, "large values", scale=50.0)
+
+
+def test_score_gradient_degree_edge_cases():
+    degs = [1, 2, 3, 4, 5, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257,
+            511, 512, 513, 1023, 1024, 1025, 2047, 2048, 2049, 5000]
+    n = 6000
+    rng = gen.stream_rng(6, 1)
+    src, dst = [], []
+    for v, d in enumerate(degs):
+        others = rng.choice(np.setdiff1d(np.arange(n), [v]), size=d - 1, replace=False)
+        src.append(others)
+        dst.append(np.full(d - 1, v))
+    # and sources with many out-edges: vertex 100 + i points at i * 37 vertices
+    for i in range(1, 40):
+        u = 100 + i
+        src.append(np.full(i * 37, u))
+        dst.append(rng.choice(np.setdiff1d(np.arange(n), [u]), size=i * 37, replace=False))
+    src = np.concatenate(src).astype(np.int32)
+    dst = np.concatenate(dst).astype(np.int32)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    _score_grad_case(g, og, 32, 0.2, 11, "degree edge cases")
+    _score_grad_case(g, og, 20, 0.2, 12, "degree edge cases")
+    g.close()
+
+
+def test_score_gradient_symmetric_and_configs():
+    for cfg, scale, m in ((1, 1, 16), (2, 1, 64), (4, 64, 76)):
+        n, src, dst = gen.make_graph(cfg, seed=0, scale_down=scale)
+        og = oracle.build_graph(n, src, dst, oracle.GCN_FLAGS)
+        g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS)
+        _score_grad_case(g, og, m, 0.2, 20 + cfg, "config %d" % cfg)
+        g.close()
+
+
+def test_score_gradient_on_a_chunked_resident_graph(hub):
+    """whole rows in several resident chunks: the bits of the one-chunk graph; a vertex whose
+    edges span several chunks is refused"""
+    import torch
+    n, src, dst, g, og = hub
+    d1 = _score_grad_case(g, og, 64, 0.2, 13, "one chunk")
+    gc = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=5003)
+    assert ntp.ntp_graph_info(gc)["n_chunks"] > 1
+    d2 = _score_grad_case(gc, og, 64, 0.2, 13, "chunks of 5003 edges")
+    assert torch.equal(d1[0], d2[0]) and torch.equal(d1[1], d2[1])
+    gc.close()
+    gs = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=700)
+    a = torch.zeros(og.csr.nnz, device="cuda:0")
+    v = torch.zeros(n, 8, device="cuda:0")
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_edge_softmax_bwd(gs, v[:, 0].contiguous(), v[:, 1].contiguous(), 0.2, a, a, v, v, 8, 8, 8, torch.empty(n, device="cuda:0"), torch.empty(n, device="cuda:0"))
+    assert e.value.code == ntp.NTP_EUNSUPPORTED
+    gs.close()
+
+
+def test_score_gradient_argument_errors(hub):
+    import torch
+    n, src, dst, g, og = hub
+    a = torch.zeros(og.csr.nnz, device="cuda:0")
+    s = torch.zeros(n, device="cuda:0")
+    v = torch.zeros(n, 1100, device="cuda:0")
+    out = torch.empty(n, device="cuda:0")
+    for m, ldz, lddy in ((0, 8, 8), (1025, 1100, 1100), (64, 32, 64), (64, 64, 32)):
+        with pytest.raises(ntp.NtpError) as e:
+            ntp.ntp_edge_softmax_bwd(g, s, s, 0.2, a, a, v, v, m, ldz, lddy, out, out.clone())
+        assert e.value.code == ntp.NTP_EINVAL
+    with pytest.raises(ntp.NtpError):
+        ntp.ntp_edge_softmax_bwd(g, s, s, 0.2, a, None, v, v, 8, 1100, 1100, out, out.clone())
+    with pytest.raises(ntp.NtpError) as e:      # wider than the scalar-load path takes
+        ntp.ntp_edge_softmax_bwd(g, s, s, 0.2, a, a, v, v, 301, 1100, 1100, out, out.clone())
+    assert e.value.code == ntp.NTP_EUNSUPPORTED
+    one_form = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | ntp.NTP_SCATTER_BWD)
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_edge_softmax_bwd(one_form, s, s, 0.2, a, a, v, v, 8, 1100, 1100, out, out.clone())
+    assert e.value.code == ntp.NTP_EUNSUPPORTED
+    one_form.close()
