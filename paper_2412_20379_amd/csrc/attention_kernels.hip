@@ -232,30 +232,66 @@ struct DotRow {
     }
 };
 
-// BLOCK = false: four rows per wavefront (one group each), rows[first .. first + n_rows).
-// BLOCK = true : one row per block of 16 groups: items[blockIdx.x].row, or rows[first + blockIdx.x]
-//                when items is null.
-template <int VEC, int NJ, bool TRANSPOSED, bool BLOCK>
-__global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, int first, int n_rows, const ReduceItem* items) {
+// WORK_GROUP  : four rows per wavefront (one group each), rows[first .. first + n_rows).
+// WORK_BLOCK  : one row per block of 16 groups, rows[first + blockIdx.x].
+// WORK_SEG    : one segment of a split row per block, segs[blockIdx.x]: the dot products of its
+//               entries; the partial t (by destination) or partial dp (by source) goes to the
+//               segment's slot.
+// WORK_SEG_DS : by destination only, after the slots of t were combined: ds of the segment's
+//               entries from the parked dalpha, partial dq to the slot.
+enum { WORK_GROUP = 0, WORK_BLOCK = 1, WORK_SEG = 2, WORK_SEG_DS = 3 };
+
+template <int VEC, int NJ, bool TRANSPOSED, int WORK>
+__global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, int first, int n_rows, const Segment* segs) {
     __shared__ float red[16];
+    constexpr bool BLOCK = WORK != WORK_GROUP;
+    constexpr bool SEG = WORK == WORK_SEG || WORK == WORK_SEG_DS;
     constexpr int U = 4;                                               // dot products in flight per group
     const int lane = threadIdx.x & 63;
     const int l = lane & 15;
     const int gi = BLOCK ? (int)(threadIdx.x >> 4) : (lane >> 4);      // group inside the block / wavefront
     constexpr int GSTRIDE = BLOCK ? 16 : 1;                            // groups sharing a row
     int row = 0;
+    int slot = 0;
     bool valid = true;
-    if constexpr (BLOCK) {
-        row = items ? items[blockIdx.x].row : a.rows[first + blockIdx.x];
-    } else {
-        const int64_t idx = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + gi;
-        valid = idx < n_rows;
-        if (valid) row = a.rows[first + idx];
-    }
     int64_t beg = 0, d = 0;
-    if (valid) { beg = a.rowptr[row]; d = a.rowptr[row + 1] - beg; }
+    if constexpr (SEG) {
+        const Segment sg = segs[blockIdx.x];
+        row = sg.row; slot = sg.slot; beg = sg.e_begin; d = sg.len;
+    } else {
+        if constexpr (BLOCK) {
+            row = a.rows[first + blockIdx.x];
+        } else {
+            const int64_t idx = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + gi;
+            valid = idx < n_rows;
+            if (valid) row = a.rows[first + idx];
+        }
+        if (valid) { beg = a.rowptr[row]; d = a.rowptr[row + 1] - beg; }
+    }
     const int32_t* ci = a.colidx + beg;
     const float* al = a.alpha + beg;
+    float* park = a.park + beg;
+    // sum of one value per group over the block, in group order (every thread gets it)
+    auto block_sum = [&](float v) {
+        if (l == 0) red[gi] = v;
+        __syncthreads();
+        float s = 0.f;
+        for (int i = 0; i < 16; ++i) s += red[i];
+        __syncthreads();
+        return s;
+    };
+    if constexpr (WORK == WORK_SEG_DS) {
+        const float t = a.t[row];
+        const float qv = a.q[row];
+        float dqp = 0.f;
+        for (int64_t k = threadIdx.x; k < d; k += 256) {
+            const int cc = ci[k];
+            dqp += al[k] * (park[k] - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
+        }
+        dqp = block_sum(group_sum<16>(dqp, lane));
+        if (threadIdx.x == 0) a.slots[slot] = dqp;
+        return;
+    }
     DotRow<VEC, NJ> dot;
     dot.load_own(a.own + (int64_t)row * a.ld_own, l, valid ? a.m : 0);
     const int k_first = BLOCK ? gi : 0;
@@ -281,20 +317,14 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
                 if (in[u]) acc += al[k + u * GSTRIDE] * (da[u] - a.t[c[u]]) * (pu + a.q[c[u]] > 0.f ? 1.f : a.slope);
         }
         if constexpr (BLOCK) {
-            if (l == 0) red[gi] = acc;
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                float s = 0.f;
-                for (int i = 0; i < 16; ++i) s += red[i];
-                a.out[row] = s;
-            }
+            acc = block_sum(acc);
+            if (threadIdx.x == 0) { if constexpr (SEG) a.slots[slot] = acc; else a.out[row] = acc; }
         } else {
             if (valid && l == 0) a.out[row] = acc;
         }
         return;
     }
     // by destination: sweep 1 = dalpha of every entry (parked by the lane that reads it back), t
-    float* park = a.park + beg;
     float t = 0.f;
     for (int64_t k = k_first; __ballot(k < d) != 0; k += U * GSTRIDE) {
         dots(k, in, c, da);
@@ -308,12 +338,10 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
             }
         }
     }
-    if constexpr (BLOCK) {
-        if (l == 0) red[gi] = t;
-        __syncthreads();
-        t = 0.f;
-        for (int i = 0; i < 16; ++i) t += red[i];
-        __syncthreads();
+    if constexpr (BLOCK) t = block_sum(t);
+    if constexpr (SEG) {
+        if (threadIdx.x == 0) a.slots[slot] = t;
+        return;
     }
     // sweep 2: ds of the entries this lane parked, summed over the row
     const float qv = valid ? a.q[row] : 0.f;
@@ -324,41 +352,52 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
     }
     dqp = group_sum<16>(dqp, lane);
     if constexpr (BLOCK) {
-        if (l == 0) red[gi] = dqp;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            float s = 0.f;
-            for (int i = 0; i < 16; ++i) s += red[i];
-            a.out[row] = s;
-            a.t[row] = t;
-        }
+        dqp = block_sum(dqp);
+        if (threadIdx.x == 0) { a.out[row] = dqp; a.t[row] = t; }
     } else {
         if (valid && l == 0) { a.out[row] = dqp; a.t[row] = t; }
     }
 }
 
+// out[row] = sum of the row's slots, in segment order
+__global__ void __launch_bounds__(256) attention_bwd_combine_kernel(const ReduceItem* items, int n_items, const float* slots, float* out) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_items) return;
+    const ReduceItem it = items[i];
+    float s = 0.f;
+    for (int j = 0; j < it.n_slots; ++j) s += slots[it.first_slot + j];
+    out[it.row] = s;
+}
+
 template <int VEC, int NJ, bool T>
-int launch_bwd_shape(const AttBwdArgs& a, const AttBwdRows& r, hipStream_t st) {
-    if (r.n_split_rows > 0)
-        hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, true>), dim3((unsigned)r.n_split_rows), dim3(256), 0, st, a, 0, 0, r.split_rows);
-    if (r.n_block_rows > 0)
-        hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, true>), dim3((unsigned)r.n_block_rows), dim3(256), 0, st, a, r.n_group_rows, 0,
-                           (const ReduceItem*)nullptr);
-    if (r.n_group_rows > 0)
-        hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, false>), dim3((unsigned)((r.n_group_rows + 15) / 16)), dim3(256), 0, st, a, 0,
-                           r.n_group_rows, (const ReduceItem*)nullptr);
+int launch_bwd_shape(const AttBwdArgs& a, const AttBwdRows& r, int phase, hipStream_t st) {
+    const Segment* none = nullptr;
+    if (phase == 0) {
+        if (r.n_segs > 0)
+            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, WORK_SEG>), dim3((unsigned)r.n_segs), dim3(256), 0, st, a, 0, 0, r.segs);
+        if (r.n_block_rows > 0)
+            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, WORK_BLOCK>), dim3((unsigned)r.n_block_rows), dim3(256), 0, st, a, r.n_group_rows, 0, none);
+        if (r.n_group_rows > 0)
+            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, WORK_GROUP>), dim3((unsigned)((r.n_group_rows + 15) / 16)), dim3(256), 0, st, a, 0,
+                               r.n_group_rows, none);
+    } else if (phase == 2) {
+        if constexpr (!T) {
+            if (r.n_segs > 0)
+                hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, false, WORK_SEG_DS>), dim3((unsigned)r.n_segs), dim3(256), 0, st, a, 0, 0, r.segs);
+        }
+    }
     return hipGetLastError() == hipSuccess ? NTP_OK : NTP_EHIP;
 }
 
 template <int VEC, bool T>
-int launch_bwd_vec(const AttBwdArgs& a, const AttBwdRows& r, hipStream_t st) {
+int launch_bwd_vec(const AttBwdArgs& a, const AttBwdRows& r, int phase, hipStream_t st) {
     const int per = 16 * VEC;
     const int nj = (a.m + per - 1) / per;
-    if (nj <= 1) return launch_bwd_shape<VEC, 1, T>(a, r, st);
-    if (nj <= 2) return launch_bwd_shape<VEC, 2, T>(a, r, st);
-    if (nj <= 4) return launch_bwd_shape<VEC, 4, T>(a, r, st);
-    if (nj <= 8) return launch_bwd_shape<VEC, 8, T>(a, r, st);
-    if (nj <= 16) return launch_bwd_shape<VEC, 16, T>(a, r, st);
+    if (nj <= 1) return launch_bwd_shape<VEC, 1, T>(a, r, phase, st);
+    if (nj <= 2) return launch_bwd_shape<VEC, 2, T>(a, r, phase, st);
+    if (nj <= 4) return launch_bwd_shape<VEC, 4, T>(a, r, phase, st);
+    if (nj <= 8) return launch_bwd_shape<VEC, 8, T>(a, r, phase, st);
+    if (nj <= 16) return launch_bwd_shape<VEC, 16, T>(a, r, phase, st);
     set_error("feature width %d too large for the attention gradient (at most %d)", a.m, 16 * per);
     return NTP_EUNSUPPORTED;
 }
@@ -422,15 +461,27 @@ int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t
 }
 
 // widest feature row the gradient kernels take: 1024 columns with 16-byte vectors, 256 otherwise
-int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transposed, void* stream) {
+// By destination: phase 0 = whole rows (dq, t) and the first sweep of the segments (partial t),
+// 1 = t of the split rows from their slots, 2 = second sweep of the segments (partial dq),
+// 3 = dq of the split rows.  By source: phase 0 = whole rows and segments (partial dp), 1 = dp of
+// the split rows.  The caller runs each phase over every chunk before the next one.
+int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transposed, int phase, void* stream) {
     hipStream_t st = (hipStream_t)stream;
+    if (phase == 1 || phase == 3) {
+        if (r.n_split_rows == 0) return NTP_OK;
+        float* dst = (phase == 1 && !transposed) ? a.t : a.out;
+        hipLaunchKernelGGL(attention_bwd_combine_kernel, dim3((unsigned)((r.n_split_rows + 255) / 256)), dim3(256), 0, st,
+                           r.split_rows, r.n_split_rows, a.slots, dst);
+        if (hipGetLastError() != hipSuccess) { set_error("attention gradient kernel launch failed"); return NTP_EHIP; }
+        return NTP_OK;
+    }
     const bool vec4 = a.m % 4 == 0 && a.ld_own % 4 == 0 && a.ld_other % 4 == 0 &&
                       (uintptr_t)a.own % 16 == 0 && (uintptr_t)a.other % 16 == 0;
     int rc;
-    if (vec4) rc = transposed ? launch_bwd_vec<4, true>(a, r, st)
-                              : launch_bwd_vec<4, false>(a, r, st);
-    else rc = transposed ? launch_bwd_vec<1, true>(a, r, st)
-                         : launch_bwd_vec<1, false>(a, r, st);
+    if (vec4) rc = transposed ? launch_bwd_vec<4, true>(a, r, phase, st)
+                              : launch_bwd_vec<4, false>(a, r, phase, st);
+    else rc = transposed ? launch_bwd_vec<1, true>(a, r, phase, st)
+                         : launch_bwd_vec<1, false>(a, r, phase, st);
     if (rc == NTP_EHIP) set_error("attention gradient kernel launch failed");
     return rc;
 }

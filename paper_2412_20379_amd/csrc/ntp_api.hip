@@ -577,45 +577,50 @@ int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float n
         set_error("the attention gradient needs every chunk of the topology device-resident");
         return NTP_EBUDGET;
     }
-    for (const Form* F : {&Fin, &Fout})
-        for (const Chunk& c : F->plan.chunks)
-            if (c.partial_row) { set_error("the attention gradient does not take a vertex whose edges span several chunks"); return NTP_EUNSUPPORTED; }
-    // scratch kept by the handle: dalpha of every edge + t of every destination
+    // scratch kept by the handle: dalpha of every edge, t of every destination, one partial sum
+    // per segment of a split row
     const int64_t nnz = g->g.csr.nnz;
+    const int64_t n_slots = std::max(Fin.plan.n_slots, Fout.plan.n_slots);
     if (!g->att_bwd) {
         void* ptr = nullptr;
-        const size_t bytes = ((size_t)nnz + (size_t)n) * 4 + 16;
+        const size_t bytes = ((size_t)nnz + (size_t)n + (size_t)n_slots) * 4 + 16;
         if (hipMalloc(&ptr, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes failed", bytes); return NTP_ENOMEM; }
         g->att_bwd = (float*)ptr;
         g->device_bytes += (int64_t)bytes;
     }
     float* park = g->att_bwd;
     float* t = g->att_bwd + nnz;
+    float* slots = t + n;
+    // chunk by chunk, phase by phase (a split row's segments may lie in several chunks)
     auto run = [&](const Form& F, bool transposed) -> int {
-        for (const Chunk& c : F.plan.chunks) {
-            AttBwdArgs a;
-            a.rowptr = reinterpret_cast<const int64_t*>(c.d_image + c.off_rowptr) - c.row_begin;
-            a.colidx = reinterpret_cast<const int32_t*>(c.d_image + c.img_off_colidx) - c.e_begin;
-            a.rows = reinterpret_cast<const int32_t*>(c.d_image + c.off_rows);
-            a.p = p; a.q = q;
-            a.alpha = transposed ? alpha_out : alpha_in;
-            a.own = transposed ? Z : dY;
-            a.ld_own = transposed ? ldz : lddy;
-            a.other = transposed ? dY : Z;
-            a.ld_other = transposed ? lddy : ldz;
-            a.t = t;
-            a.park = park;
-            a.out = transposed ? dp : dq;
-            a.slope = negative_slope;
-            a.m = (int32_t)m;
-            AttBwdRows r;
-            r.n_group_rows = c.bin_row_off[NBINS - 1];
-            r.n_block_rows = c.bin_count[NBINS - 1];
-            r.split_rows = reinterpret_cast<const ReduceItem*>(c.d_image + c.off_reduce);
-            r.n_split_rows = c.n_reduce;
-            const int rc = launch_attention_bwd(a, r, transposed, stream);
-            if (rc != NTP_OK) return rc;
-        }
+        for (int phase = 0; phase < (transposed ? 2 : 4); ++phase)
+            for (const Chunk& c : F.plan.chunks) {
+                AttBwdArgs a;
+                a.rowptr = reinterpret_cast<const int64_t*>(c.d_image + c.off_rowptr) - c.row_begin;
+                a.colidx = reinterpret_cast<const int32_t*>(c.d_image + c.img_off_colidx) - c.e_begin;
+                a.rows = reinterpret_cast<const int32_t*>(c.d_image + c.off_rows);
+                a.p = p; a.q = q;
+                a.alpha = transposed ? alpha_out : alpha_in;
+                a.own = transposed ? Z : dY;
+                a.ld_own = transposed ? ldz : lddy;
+                a.other = transposed ? dY : Z;
+                a.ld_other = transposed ? lddy : ldz;
+                a.t = t;
+                a.park = park;
+                a.out = transposed ? dp : dq;
+                a.slots = slots;
+                a.slope = negative_slope;
+                a.m = (int32_t)m;
+                AttBwdRows r;
+                r.n_group_rows = c.bin_row_off[NBINS - 1];
+                r.n_block_rows = c.bin_count[NBINS - 1];
+                r.segs = reinterpret_cast<const Segment*>(c.d_image + c.off_segs);
+                r.n_segs = c.n_segs;
+                r.split_rows = reinterpret_cast<const ReduceItem*>(c.d_image + c.off_reduce);
+                r.n_split_rows = c.n_reduce;
+                const int rc = launch_attention_bwd(a, r, transposed, phase, stream);
+                if (rc != NTP_OK) return rc;
+            }
         return NTP_OK;
     };
     int rc = run(Fin, false);           // dq and t first: the by-source pass reads t

@@ -195,18 +195,21 @@ struct AttBwdArgs {
     float* t;                  // per destination: sum of alpha * dalpha
     float* park;               // [nnz] dalpha per entry (by-destination pass)
     float* out;                // dq (by destination) or dp (by source)
+    float* slots;              // [n_slots] partial sums of the segments of split rows
     float slope;
     int32_t m;                 // feature width
 };
-// rows[0 .. n_group_rows): a group of 16 lanes each; rows[n_group_rows .. + n_block_rows) and the
-// split rows: a block each (the bin lists are stored by increasing entry count)
+// rows[0 .. n_group_rows): a group of 16 lanes each; rows[n_group_rows .. + n_block_rows): a block
+// each (the bin lists are stored by increasing entry count); split rows: a block per segment
 struct AttBwdRows {
     int n_group_rows;
     int n_block_rows;
-    const ReduceItem* split_rows;
+    const Segment* segs;
+    int n_segs;
+    const ReduceItem* split_rows;      // rows whose last segment lies in this chunk
     int n_split_rows;
 };
-int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transposed, void* stream);
+int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transposed, int phase, void* stream);
 
 int launch_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss, float* scratch,
                         int64_t n, int64_t c, int64_t ldz, int64_t lddz, void* stream);

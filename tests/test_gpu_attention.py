@@ -326,23 +326,18 @@ def test_score_gradient_symmetric_and_configs():
 
 
 def test_score_gradient_on_a_chunked_resident_graph(hub):
-    """whole rows in several resident chunks: the bits of the one-chunk graph; a vertex whose
-    edges span several chunks is refused"""
+    """several resident chunks: same plan of whole rows and segments -> the bits of the one-chunk
+    graph; smaller chunks cut the hub's rows into pieces that lie in several chunks"""
     import torch
     n, src, dst, g, og = hub
     d1 = _score_grad_case(g, og, 64, 0.2, 13, "one chunk")
-    gc = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=5003)
-    assert ntp.ntp_graph_info(gc)["n_chunks"] > 1
-    d2 = _score_grad_case(gc, og, 64, 0.2, 13, "chunks of 5003 edges")
-    assert torch.equal(d1[0], d2[0]) and torch.equal(d1[1], d2[1])
-    gc.close()
-    gs = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=700)
-    a = torch.zeros(og.csr.nnz, device="cuda:0")
-    v = torch.zeros(n, 8, device="cuda:0")
-    with pytest.raises(ntp.NtpError) as e:
-        ntp.ntp_edge_softmax_bwd(gs, v[:, 0].contiguous(), v[:, 1].contiguous(), 0.2, a, a, v, v, 8, 8, 8, torch.empty(n, device="cuda:0"), torch.empty(n, device="cuda:0"))
-    assert e.value.code == ntp.NTP_EUNSUPPORTED
-    gs.close()
+    for chunk_edges in (5003, 700, 101):
+        gc = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS, chunk_edges=chunk_edges)
+        assert ntp.ntp_graph_info(gc)["n_chunks"] > 1
+        d2 = _score_grad_case(gc, og, 64, 0.2, 13, "chunks of %d edges" % chunk_edges)
+        if chunk_edges == 5003:
+            assert torch.equal(d1[0], d2[0]) and torch.equal(d1[1], d2[1])
+        gc.close()
 
 
 def test_score_gradient_argument_errors(hub):
