@@ -212,7 +212,7 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
  * 1 <= m <= 1024 when both are 16-byte aligned with m and the strides multiples of 4, m <= 256
  * otherwise (NTP_EUNSUPPORTED); dp, dq [n] device fp32 outputs (every element written).
  * Needs every chunk device-resident (NTP_EBUDGET) and a by-source form (NTP_EUNSUPPORTED for
- * NTP_SCATTER_BWD graphs).  Deterministic.  The handle keeps 4 bytes per edge + 4 per vertex of
+ * NTP_SCATTER_BWD graphs).  Deterministic.  The handle keeps 4 bytes per edge + 8 per vertex of
  * scratch from the first call on; calls on one handle must not overlap.
  */
 int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float negative_slope,

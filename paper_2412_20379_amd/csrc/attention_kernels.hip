@@ -191,11 +191,15 @@ __global__ void __launch_bounds__(256) attention_segment_write_kernel(const AttA
 //   dp[u] = sum over out-edges of ds.
 // By-destination pass (rows v, own = dY[v,:], gathered = Z[u,:]): dalpha of every entry (parked in
 // scratch), t[v], dq[v].  By-source pass (rows u, own = Z[u,:], gathered = dY[v,:]): dalpha again
-// in that order, with t[v] and alpha in by-source order: dp[u].  A group of 16 lanes forms one dot
-// product at a time (16 x VEC x NJ columns, xor tree over the 16 lanes); rows beyond the split
-// threshold take one block (16 groups over the entries, partial sums combined through LDS in a
-// fixed order).  Every entry's parked dalpha is read back by the thread that wrote it.
-template <int VEC, int NJ>
+// in that order, with t[v] and alpha in by-source order: dp[u].  A group of L lanes (4, 8 or 16)
+// forms one dot product at a time (L x VEC x NJ columns, xor tree over the group).  Rows of more
+// than 128 entries take one block (its groups share the entries, partial sums combined through
+// LDS in a fixed order; one wavefront per such row measured slower); rows beyond the split
+// threshold one block per segment, the partial sums of the segments combined by a small kernel
+// in segment order.  Inside one kernel an entry's parked dalpha
+// is read back by the thread that wrote it.  Widest row: 1024 columns with 16-byte vectors, 256
+// otherwise.
+template <int VEC, int NJ, int L>
 struct DotRow {
     float own[NJ][VEC];
     int col[NJ];
@@ -203,7 +207,7 @@ struct DotRow {
     __device__ __forceinline__ void load_own(const float* row, int l, int m) {
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-            col[j] = (j * 16 + l) * VEC;
+            col[j] = (j * L + l) * VEC;
             on[j] = col[j] < m;
 #pragma unroll
             for (int i = 0; i < VEC; ++i) own[j][i] = 0.f;
@@ -232,8 +236,8 @@ struct DotRow {
     }
 };
 
-// WORK_GROUP  : four rows per wavefront (one group each), rows[first .. first + n_rows).
-// WORK_BLOCK  : one row per block of 16 groups, rows[first + blockIdx.x].
+// WORK_GROUP  : one row per group of L lanes, rows[first .. first + n_rows).
+// WORK_BLOCK  : one row per block (its 256 / L groups take the entries in turn), rows[first + blockIdx.x].
 // WORK_SEG    : one segment of a split row per block, segs[blockIdx.x]: the dot products of its
 //               entries; the partial t (by destination) or partial dp (by source) goes to the
 //               segment's slot.
@@ -241,16 +245,17 @@ struct DotRow {
 //               entries from the parked dalpha, partial dq to the slot.
 enum { WORK_GROUP = 0, WORK_BLOCK = 1, WORK_SEG = 2, WORK_SEG_DS = 3 };
 
-template <int VEC, int NJ, bool TRANSPOSED, int WORK>
+template <int VEC, int NJ, int L, bool TRANSPOSED, int WORK>
 __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, int first, int n_rows, const Segment* segs) {
-    __shared__ float red[16];
-    constexpr bool BLOCK = WORK != WORK_GROUP;
     constexpr bool SEG = WORK == WORK_SEG || WORK == WORK_SEG_DS;
+    constexpr int R = 64 / L;                                          // groups per wavefront
+    constexpr int NG = 256 / L;                                        // groups per block
+    constexpr int SHARE = WORK == WORK_GROUP ? 1 : NG;                  // groups on one row
     constexpr int U = 4;                                               // dot products in flight per group
+    __shared__ float red[NG];
     const int lane = threadIdx.x & 63;
-    const int l = lane & 15;
-    const int gi = BLOCK ? (int)(threadIdx.x >> 4) : (lane >> 4);      // group inside the block / wavefront
-    constexpr int GSTRIDE = BLOCK ? 16 : 1;                            // groups sharing a row
+    const int l = lane % L;
+    const int gi = SHARE == 1 ? 0 : (int)(threadIdx.x / L);            // group among those on the row
     int row = 0;
     int slot = 0;
     bool valid = true;
@@ -259,146 +264,153 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
         const Segment sg = segs[blockIdx.x];
         row = sg.row; slot = sg.slot; beg = sg.e_begin; d = sg.len;
     } else {
-        if constexpr (BLOCK) {
-            row = a.rows[first + blockIdx.x];
-        } else {
-            const int64_t idx = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + gi;
-            valid = idx < n_rows;
-            if (valid) row = a.rows[first + idx];
-        }
-        if (valid) { beg = a.rowptr[row]; d = a.rowptr[row + 1] - beg; }
+        const int64_t idx = WORK == WORK_BLOCK ? (int64_t)blockIdx.x : ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * R + lane / L;
+        valid = idx < n_rows;
+        if (valid) { row = a.rows[first + idx]; beg = a.rowptr[row]; d = a.rowptr[row + 1] - beg; }
     }
     const int32_t* ci = a.colidx + beg;
     const float* al = a.alpha + beg;
     float* park = a.park + beg;
-    // sum of one value per group over the block, in group order (every thread gets it)
-    auto block_sum = [&](float v) {
-        if (l == 0) red[gi] = v;
-        __syncthreads();
-        float s = 0.f;
-        for (int i = 0; i < 16; ++i) s += red[i];
-        __syncthreads();
-        return s;
+    // sum over the groups that share the row of a value all lanes of a group hold, in a fixed order
+    auto share_sum = [&](float v) {
+        if constexpr (SHARE == 1) {
+            return v;
+        } else {
+            if (l == 0) red[gi] = v;
+            __syncthreads();
+            float s = 0.f;
+            for (int i = 0; i < NG; ++i) s += red[i];
+            __syncthreads();
+            return s;
+        }
     };
+    const bool writer = SHARE == NG ? threadIdx.x == 0 : (valid && l == 0);
     if constexpr (WORK == WORK_SEG_DS) {
-        const float t = a.t[row];
+        const float t = a.t[2 * row];
         const float qv = a.q[row];
         float dqp = 0.f;
         for (int64_t k = threadIdx.x; k < d; k += 256) {
             const int cc = ci[k];
             dqp += al[k] * (park[k] - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
         }
-        dqp = block_sum(group_sum<16>(dqp, lane));
-        if (threadIdx.x == 0) a.slots[slot] = dqp;
+        dqp = share_sum(group_sum<L>(dqp, lane));
+        if (writer) a.slots[slot] = dqp;
         return;
     }
-    DotRow<VEC, NJ> dot;
+    DotRow<VEC, NJ, L> dot;
     dot.load_own(a.own + (int64_t)row * a.ld_own, l, valid ? a.m : 0);
-    const int k_first = BLOCK ? gi : 0;
-    // dalpha of entries k, k + GSTRIDE, ...: U gathers issued before the first xor tree
-    auto dots = [&](int64_t k, bool (&in)[U], int (&c)[U], float (&da)[U]) {
+    bool in[U];
+    int c[U], cn[U];
+    float da[U];
+    auto columns = [&](int64_t k, int (&cc)[U]) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) { in[u] = k + u * GSTRIDE < d; c[u] = in[u] ? ci[k + u * GSTRIDE] : row; }
+        for (int u = 0; u < U; ++u) cc[u] = k + u * SHARE < d ? ci[k + u * SHARE] : row;
+    };
+    // dalpha of entries k, k + SHARE, ...: U gathers issued before the first xor tree; the
+    // column ids of the next batch are fetched meanwhile
+    auto dots = [&](int64_t k) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) { in[u] = k + u * SHARE < d; c[u] = cn[u]; }
 #pragma unroll
         for (int u = 0; u < U; ++u) da[u] = dot.partial(a.other + (int64_t)c[u] * a.ld_other);
+        columns(k + U * SHARE, cn);
 #pragma unroll
-        for (int u = 0; u < U; ++u) da[u] = group_sum<16>(da[u], lane);
+        for (int u = 0; u < U; ++u) da[u] = group_sum<L>(da[u], lane);
     };
-    bool in[U];
-    int c[U];
-    float da[U];
+    columns(gi, cn);
     if constexpr (TRANSPOSED) {
         const float pu = valid ? a.p[row] : 0.f;
         float acc = 0.f;
-        for (int64_t k = k_first; __ballot(k < d) != 0; k += U * GSTRIDE) {   // the wavefront stays together for the shuffles
-            dots(k, in, c, da);
+        for (int64_t k = gi; __ballot(k < d) != 0; k += U * SHARE) {          // the wavefront stays together for the shuffles
+            dots(k);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (in[u]) acc += al[k + u * GSTRIDE] * (da[u] - a.t[c[u]]) * (pu + a.q[c[u]] > 0.f ? 1.f : a.slope);
+                if (in[u]) {
+                    const float2 tq = reinterpret_cast<const float2*>(a.t)[c[u]];      // (t, q) of the destination
+                    acc += al[k + u * SHARE] * (da[u] - tq.x) * (pu + tq.y > 0.f ? 1.f : a.slope);
+                }
         }
-        if constexpr (BLOCK) {
-            acc = block_sum(acc);
-            if (threadIdx.x == 0) { if constexpr (SEG) a.slots[slot] = acc; else a.out[row] = acc; }
-        } else {
-            if (valid && l == 0) a.out[row] = acc;
-        }
+        acc = share_sum(acc);
+        if (writer) { if constexpr (SEG) a.slots[slot] = acc; else a.out[row] = acc; }
         return;
     }
     // by destination: sweep 1 = dalpha of every entry (parked by the lane that reads it back), t
     float t = 0.f;
-    for (int64_t k = k_first; __ballot(k < d) != 0; k += U * GSTRIDE) {
-        dots(k, in, c, da);
+    for (int64_t k = gi; __ballot(k < d) != 0; k += U * SHARE) {
+        dots(k);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (in[u]) {
-                const int64_t ku = k + u * GSTRIDE;
+                const int64_t ku = k + u * SHARE;             // ku % SHARE == gi
                 t += al[ku] * da[u];
-                const int owner = BLOCK ? (int)((ku / 16) & 15) : (int)(ku & 15);
-                if (l == owner) park[ku] = da[u];
+                if (l == (int)((ku / SHARE) % L)) park[ku] = da[u];
             }
         }
     }
-    if constexpr (BLOCK) t = block_sum(t);
+    t = share_sum(t);
     if constexpr (SEG) {
-        if (threadIdx.x == 0) a.slots[slot] = t;
+        if (writer) a.slots[slot] = t;
         return;
     }
     // sweep 2: ds of the entries this lane parked, summed over the row
     const float qv = valid ? a.q[row] : 0.f;
     float dqp = 0.f;
-    for (int64_t k = BLOCK ? gi + 16 * l : l; k < d; k += BLOCK ? 256 : 16) {   // BLOCK: k % 16 == gi, (k / 16) % 16 == l
+    for (int64_t k = gi + SHARE * l; k < d; k += SHARE * L) {                // k % SHARE == gi, (k / SHARE) % L == l
         const int cc = ci[k];
         dqp += al[k] * (park[k] - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
     }
-    dqp = group_sum<16>(dqp, lane);
-    if constexpr (BLOCK) {
-        dqp = block_sum(dqp);
-        if (threadIdx.x == 0) { a.out[row] = dqp; a.t[row] = t; }
-    } else {
-        if (valid && l == 0) { a.out[row] = dqp; a.t[row] = t; }
-    }
+    dqp = share_sum(group_sum<L>(dqp, lane));
+    if (writer) { a.out[row] = dqp; reinterpret_cast<float2*>(a.t)[row] = make_float2(t, qv); }
 }
 
-// out[row] = sum of the row's slots, in segment order
-__global__ void __launch_bounds__(256) attention_bwd_combine_kernel(const ReduceItem* items, int n_items, const float* slots, float* out) {
+// out[row] = sum of the row's slots, in segment order; with q: the pair (sum, q[row]) at out[2 row]
+__global__ void __launch_bounds__(256) attention_bwd_combine_kernel(const ReduceItem* items, int n_items, const float* slots, float* out,
+                                                                    const float* q) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n_items) return;
     const ReduceItem it = items[i];
     float s = 0.f;
     for (int j = 0; j < it.n_slots; ++j) s += slots[it.first_slot + j];
-    out[it.row] = s;
+    if (q) reinterpret_cast<float2*>(out)[it.row] = make_float2(s, q[it.row]);
+    else out[it.row] = s;
 }
 
-template <int VEC, int NJ, bool T>
+template <int VEC, int NJ, int L, bool T>
 int launch_bwd_shape(const AttBwdArgs& a, const AttBwdRows& r, int phase, hipStream_t st) {
     const Segment* none = nullptr;
+    constexpr int ROWS_PER_BLOCK = 4 * (64 / L);
     if (phase == 0) {
         if (r.n_segs > 0)
-            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, WORK_SEG>), dim3((unsigned)r.n_segs), dim3(256), 0, st, a, 0, 0, r.segs);
+            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, L, T, WORK_SEG>), dim3((unsigned)r.n_segs), dim3(256), 0, st, a, 0, 0, r.segs);
         if (r.n_block_rows > 0)
-            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, WORK_BLOCK>), dim3((unsigned)r.n_block_rows), dim3(256), 0, st, a, r.n_group_rows, 0, none);
+            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, L, T, WORK_BLOCK>), dim3((unsigned)r.n_block_rows), dim3(256), 0, st, a,
+                               r.n_group_rows, r.n_block_rows, none);
         if (r.n_group_rows > 0)
-            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, T, WORK_GROUP>), dim3((unsigned)((r.n_group_rows + 15) / 16)), dim3(256), 0, st, a, 0,
-                               r.n_group_rows, none);
+            hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, L, T, WORK_GROUP>), dim3((unsigned)((r.n_group_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)),
+                               dim3(256), 0, st, a, 0, r.n_group_rows, none);
     } else if (phase == 2) {
         if constexpr (!T) {
             if (r.n_segs > 0)
-                hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, false, WORK_SEG_DS>), dim3((unsigned)r.n_segs), dim3(256), 0, st, a, 0, 0, r.segs);
+                hipLaunchKernelGGL((attention_bwd_kernel<VEC, NJ, L, false, WORK_SEG_DS>), dim3((unsigned)r.n_segs), dim3(256), 0, st, a, 0, 0, r.segs);
         }
     }
     return hipGetLastError() == hipSuccess ? NTP_OK : NTP_EHIP;
 }
 
+// lanes per group: the smallest of 4, 8, 16 whose vectors cover the row; wider rows take several
+// vectors per lane
 template <int VEC, bool T>
 int launch_bwd_vec(const AttBwdArgs& a, const AttBwdRows& r, int phase, hipStream_t st) {
-    const int per = 16 * VEC;
-    const int nj = (a.m + per - 1) / per;
-    if (nj <= 1) return launch_bwd_shape<VEC, 1, T>(a, r, phase, st);
-    if (nj <= 2) return launch_bwd_shape<VEC, 2, T>(a, r, phase, st);
-    if (nj <= 4) return launch_bwd_shape<VEC, 4, T>(a, r, phase, st);
-    if (nj <= 8) return launch_bwd_shape<VEC, 8, T>(a, r, phase, st);
-    if (nj <= 16) return launch_bwd_shape<VEC, 16, T>(a, r, phase, st);
-    set_error("feature width %d too large for the attention gradient (at most %d)", a.m, 16 * per);
+    const int nvec = (a.m + VEC - 1) / VEC;
+    if (nvec <= 4) return launch_bwd_shape<VEC, 1, 4, T>(a, r, phase, st);
+    if (nvec <= 8) return launch_bwd_shape<VEC, 1, 8, T>(a, r, phase, st);
+    const int nj = (nvec + 15) / 16;
+    if (nj <= 1) return launch_bwd_shape<VEC, 1, 16, T>(a, r, phase, st);
+    if (nj <= 2) return launch_bwd_shape<VEC, 2, 16, T>(a, r, phase, st);
+    if (nj <= 4) return launch_bwd_shape<VEC, 4, 16, T>(a, r, phase, st);
+    if (nj <= 8) return launch_bwd_shape<VEC, 8, 16, T>(a, r, phase, st);
+    if (nj <= 16) return launch_bwd_shape<VEC, 16, 16, T>(a, r, phase, st);
+    set_error("feature width %d too large for the attention gradient (at most %d)", a.m, 256 * VEC);
     return NTP_EUNSUPPORTED;
 }
 
@@ -460,7 +472,6 @@ int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t
     return rc;
 }
 
-// widest feature row the gradient kernels take: 1024 columns with 16-byte vectors, 256 otherwise
 // By destination: phase 0 = whole rows (dq, t) and the first sweep of the segments (partial t),
 // 1 = t of the split rows from their slots, 2 = second sweep of the segments (partial dq),
 // 3 = dq of the split rows.  By source: phase 0 = whole rows and segments (partial dp), 1 = dp of
@@ -469,9 +480,9 @@ int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transpos
     hipStream_t st = (hipStream_t)stream;
     if (phase == 1 || phase == 3) {
         if (r.n_split_rows == 0) return NTP_OK;
-        float* dst = (phase == 1 && !transposed) ? a.t : a.out;
+        const bool is_t = phase == 1 && !transposed;
         hipLaunchKernelGGL(attention_bwd_combine_kernel, dim3((unsigned)((r.n_split_rows + 255) / 256)), dim3(256), 0, st,
-                           r.split_rows, r.n_split_rows, a.slots, dst);
+                           r.split_rows, r.n_split_rows, a.slots, is_t ? a.t : a.out, is_t ? a.q : (const float*)nullptr);
         if (hipGetLastError() != hipSuccess) { set_error("attention gradient kernel launch failed"); return NTP_EHIP; }
         return NTP_OK;
     }

@@ -45,7 +45,7 @@ struct ntp_graph {
     float* partial = nullptr;
     size_t partial_bytes = 0;
     float* att_stats = nullptr;    // [4 n]: per-destination (q, maximum, 1 / sum, 0) of the last ntp_edge_softmax
-    float* att_bwd = nullptr;      // [nnz + n]: per-edge dalpha and per-destination t of ntp_edge_softmax_bwd
+    float* att_bwd = nullptr;      // scratch of ntp_edge_softmax_bwd: per-destination (t, q), per-segment partial sums, per-edge dalpha
     int64_t device_bytes = 0;
 
     // the by-source product runs as a scatter over the by-destination form
@@ -577,20 +577,20 @@ int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float n
         set_error("the attention gradient needs every chunk of the topology device-resident");
         return NTP_EBUDGET;
     }
-    // scratch kept by the handle: dalpha of every edge, t of every destination, one partial sum
-    // per segment of a split row
+    // scratch kept by the handle: (t, q) of every destination, one partial sum per segment of a
+    // split row, dalpha of every edge
     const int64_t nnz = g->g.csr.nnz;
     const int64_t n_slots = std::max(Fin.plan.n_slots, Fout.plan.n_slots);
     if (!g->att_bwd) {
         void* ptr = nullptr;
-        const size_t bytes = ((size_t)nnz + (size_t)n + (size_t)n_slots) * 4 + 16;
+        const size_t bytes = ((size_t)nnz + 2 * (size_t)n + (size_t)n_slots) * 4 + 16;
         if (hipMalloc(&ptr, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes failed", bytes); return NTP_ENOMEM; }
         g->att_bwd = (float*)ptr;
         g->device_bytes += (int64_t)bytes;
     }
-    float* park = g->att_bwd;
-    float* t = g->att_bwd + nnz;
-    float* slots = t + n;
+    float* t = g->att_bwd;              // (t, q) pairs
+    float* slots = t + 2 * n;
+    float* park = slots + n_slots;
     // chunk by chunk, phase by phase (a split row's segments may lie in several chunks)
     auto run = [&](const Form& F, bool transposed) -> int {
         for (int phase = 0; phase < (transposed ? 2 : 4); ++phase)

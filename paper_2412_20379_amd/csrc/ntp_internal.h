@@ -192,14 +192,14 @@ struct AttBwdArgs {
     const float* own;          // row vectors of this form's rows: dY (by destination) or Z (by source)
     const float* other;        // row vectors gathered by column id: Z (by destination) or dY (by source)
     int64_t ld_own, ld_other;
-    float* t;                  // per destination: sum of alpha * dalpha
+    float* t;                  // per destination, two floats (8-byte aligned): sum of alpha * dalpha, q
     float* park;               // [nnz] dalpha per entry (by-destination pass)
     float* out;                // dq (by destination) or dp (by source)
     float* slots;              // [n_slots] partial sums of the segments of split rows
     float slope;
     int32_t m;                 // feature width
 };
-// rows[0 .. n_group_rows): a group of 16 lanes each; rows[n_group_rows .. + n_block_rows): a block
+// rows[0 .. n_group_rows): a lane group each; rows[n_group_rows .. + n_block_rows): a wavefront
 // each (the bin lists are stored by increasing entry count); split rows: a block per segment
 struct AttBwdRows {
     int n_group_rows;
