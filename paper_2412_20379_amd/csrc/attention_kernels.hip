@@ -196,9 +196,9 @@ __global__ void __launch_bounds__(256) attention_segment_write_kernel(const AttA
 // than 128 entries take one block (its groups share the entries, partial sums combined through
 // LDS in a fixed order; one wavefront per such row measured slower); rows beyond the split
 // threshold one block per segment, the partial sums of the segments combined by a small kernel
-// in segment order.  Inside one kernel an entry's parked dalpha
-// is read back by the thread that wrote it.  Widest row: 1024 columns with 16-byte vectors, 256
-// otherwise.
+// in segment order.  Where both sweeps run in one kernel each lane keeps the dalpha of its first
+// entry in a register (short rows park nothing) and a parked dalpha is read back by the thread
+// that wrote it.  Widest row: 1024 columns with 16-byte vectors, 256 otherwise.
 template <int VEC, int NJ, int L>
 struct DotRow {
     float own[NJ][VEC];
@@ -218,11 +218,11 @@ struct DotRow {
         }
     }
     // this lane's share of own . other (columns outside the row contribute zero)
-    __device__ __forceinline__ float partial(const float* other) const {
+    __device__ __forceinline__ float partial(const float* other, bool live) const {
         float acc = 0.f;
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-            if (on[j]) {
+            if (on[j] && live) {
                 if constexpr (VEC == 4) {
                     const float4 t = *reinterpret_cast<const float4*>(other + col[j]);
                     acc = fmaf(own[j][0], t.x, acc); acc = fmaf(own[j][1], t.y, acc);
@@ -312,7 +312,7 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
 #pragma unroll
         for (int u = 0; u < U; ++u) { in[u] = k + u * SHARE < d; c[u] = cn[u]; }
 #pragma unroll
-        for (int u = 0; u < U; ++u) da[u] = dot.partial(a.other + (int64_t)c[u] * a.ld_other);
+        for (int u = 0; u < U; ++u) da[u] = dot.partial(a.other + (int64_t)c[u] * a.ld_other, in[u]);
         columns(k + U * SHARE, cn);
 #pragma unroll
         for (int u = 0; u < U; ++u) da[u] = group_sum<L>(da[u], lane);
@@ -336,6 +336,7 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
     }
     // by destination: sweep 1 = dalpha of every entry (parked by the lane that reads it back), t
     float t = 0.f;
+    float mine = 0.f;
     for (int64_t k = gi; __ballot(k < d) != 0; k += U * SHARE) {
         dots(k);
 #pragma unroll
@@ -343,7 +344,10 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
             if (in[u]) {
                 const int64_t ku = k + u * SHARE;             // ku % SHARE == gi
                 t += al[ku] * da[u];
-                if (l == (int)((ku / SHARE) % L)) park[ku] = da[u];
+                if (l == (int)((ku / SHARE) % L)) {
+                    if (!SEG && ku < SHARE * L) mine = da[u]; // the lane's first entry stays in a register
+                    else park[ku] = da[u];
+                }
             }
         }
     }
@@ -357,7 +361,8 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
     float dqp = 0.f;
     for (int64_t k = gi + SHARE * l; k < d; k += SHARE * L) {                // k % SHARE == gi, (k / SHARE) % L == l
         const int cc = ci[k];
-        dqp += al[k] * (park[k] - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
+        const float dak = k < SHARE * L ? mine : park[k];
+        dqp += al[k] * (dak - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
     }
     dqp = share_sum(group_sum<L>(dqp, lane));
     if (writer) { a.out[row] = dqp; reinterpret_cast<float2*>(a.t)[row] = make_float2(t, qv); }
