@@ -12,8 +12,9 @@ constant-vector closed form, the sqrt-degree fixed point, textbook graphs
 chunk/slice invariance, finite-difference gradients of the epoch loss, a
 hand-derived fixture under tests/golden/, and for the attention weights: rows
 summing to one, the slope-1 closed form, equal scores giving 1/degree, a dense
-brute force, and the transposed order against scipy's transpose.  No function
-here is unpinned.
+brute force, and the transposed order against scipy's transpose; the gradient
+of the attention scores and the whole GAT epoch by finite differences and by
+the reductions to a mean aggregation and to an MLP.  No function here is unpinned.
 """
 from .graph import (  # noqa: F401
     Graph, Sparse, build_graph, plan_chunks,
@@ -25,6 +26,7 @@ from .aggregate import (  # noqa: F401
 )
 from .sampled import rows_from_undirected_edges  # noqa: F401
 from .attention import edge_softmax, edge_softmax_bwd, leaky_relu, weighted  # noqa: F401
+from .gat import attention_scores, attention_scores_bwd, epoch_gat_decoupled  # noqa: F401
 from .gcn import (  # noqa: F401
     nn_fwd, nn_bwd, softmax_cross_entropy, epoch_layerwise, epoch_decoupled,
 )

@@ -200,3 +200,101 @@ def test_a9_score_gradient_invariants():
     # constant features: every dalpha of a row is the same number, so the softmax gradient vanishes
     dp, dq, _, _ = oracle.edge_softmax_bwd(g, p, q, np.ones((n, m)), dY, 0.2)
     assert np.abs(dp).max() <= 1e-12 and np.abs(dq).max() <= 1e-12
+
+
+# ---- A10-A12: the decoupled GAT epoch (Section 4.1 with the AGG of GAT, Section 2.1) ---------------
+def _tiny_gat(seed, directed, layers=2):
+    n = 50
+    if directed:
+        src, dst = gen.directed_random_edges(n, 260, seed)
+        g = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    else:
+        src, dst = gen.erdos_renyi_edges(n, 170, seed)
+        g = oracle.build_graph(n, src, dst)
+    dims = (8, 6, 5)[3 - layers - 1:]
+    rng = np.random.default_rng(seed)
+    X = rng.normal(size=(n, dims[0]))
+    Ws = [rng.normal(size=(dims[i], dims[i + 1])) * 0.6 for i in range(layers)]
+    a_src = rng.normal(size=dims[-1])
+    a_dst = rng.normal(size=dims[-1])
+    labels = rng.integers(0, dims[-1], size=n)
+    return g, X, Ws, a_src, a_dst, labels
+
+
+@pytest.mark.parametrize("directed", [False, True])
+@pytest.mark.parametrize("rounds,slope", [(1, 0.2), (2, 0.2), (3, 0.0), (2, 1.0)])
+def test_a10_gat_epoch_finite_differences(directed, rounds, slope):
+    """every parameter gradient of the epoch against central differences of its loss"""
+    g, X, Ws, a_s, a_d, labels = _tiny_gat(3, directed)
+    fn = lambda Ws_, s_, d_: oracle.epoch_gat_decoupled(g, X, Ws_, s_, d_, labels, rounds, slope)["loss"]
+    out = oracle.epoch_gat_decoupled(g, X, Ws, a_s, a_d, labels, rounds, slope)
+    eps = 1e-6
+    rng = np.random.default_rng(1)
+
+    def close(fd, an):
+        assert abs(fd - an) <= 2e-6 * max(1e-3, abs(fd)) + 1e-9, (fd, an)
+
+    for l, W in enumerate(Ws):
+        for _ in range(5):
+            i, j = rng.integers(W.shape[0]), rng.integers(W.shape[1])
+            Wp = [w.copy() for w in Ws]
+            Wm = [w.copy() for w in Ws]
+            Wp[l][i, j] += eps
+            Wm[l][i, j] -= eps
+            close((fn(Wp, a_s, a_d) - fn(Wm, a_s, a_d)) / (2 * eps), out["dW"][l][i, j])
+    for j in range(len(a_s)):
+        e = np.zeros_like(a_s)
+        e[j] = eps
+        close((fn(Ws, a_s + e, a_d) - fn(Ws, a_s - e, a_d)) / (2 * eps), out["da_src"][j])
+        close((fn(Ws, a_s, a_d + e) - fn(Ws, a_s, a_d - e)) / (2 * eps), out["da_dst"][j])
+
+
+def test_a11_gat_epoch_zero_attention_vectors_is_mean_aggregation():
+    """a_src = a_dst = 0: every score is equal, alpha = 1 / in-degree, and the forward pass is the
+    dense row-normalised (A + I)^rounds applied to the MLP output"""
+    g, X, Ws, a_s, a_d, labels = _tiny_gat(5, True)
+    out = oracle.epoch_gat_decoupled(g, X, Ws, 0 * a_s, 0 * a_d, labels, rounds=2)
+    n = g.n
+    M = np.zeros((n, n))
+    for v in range(n):
+        us = g.csr.colidx[g.csr.rowptr[v]:g.csr.rowptr[v + 1]]
+        M[v, us] = 1.0 / len(us)
+    H = np.maximum(X @ Ws[0], 0) @ Ws[1]
+    want = M @ (M @ H)
+    np.testing.assert_allclose(out["logits"], want, rtol=1e-12, atol=1e-14)
+    loss, _ = oracle.softmax_cross_entropy(want, labels)
+    assert abs(out["loss"] - loss) <= 1e-14
+    # the MLP's gradient is then that of the fixed linear map M^2 (alpha's own gradient only moves a)
+    dH = (M @ M).T @ oracle.softmax_cross_entropy(want, labels)[1]
+    np.testing.assert_allclose(out["dLhat"], dH, rtol=1e-11, atol=1e-14)
+
+
+def test_a12_gat_epoch_identity_graph_reduces_to_mlp():
+    """no edges but the self loops: alpha = 1 on every self loop, Z^k = Lhat, zero attention gradient"""
+    g, X, Ws, a_s, a_d, labels = _tiny_gat(7, True)
+    n = g.n
+    gi = oracle.build_graph(n, np.zeros(0, np.int32), np.zeros(0, np.int32), oracle.DIRECTED_GCN_FLAGS)
+    out = oracle.epoch_gat_decoupled(gi, X, Ws, a_s, a_d, labels, rounds=3)
+    H0 = X @ Ws[0]
+    H = np.maximum(H0, 0) @ Ws[1]
+    loss, dZ = oracle.softmax_cross_entropy(H, labels)
+    assert abs(out["loss"] - loss) <= 1e-14
+    np.testing.assert_allclose(out["alpha_in"], 1.0)
+    np.testing.assert_allclose(out["da_src"], 0.0, atol=1e-15)
+    np.testing.assert_allclose(out["da_dst"], 0.0, atol=1e-15)
+    np.testing.assert_allclose(out["dW"][1], np.maximum(H0, 0).T @ dZ, rtol=1e-12, atol=1e-15)
+
+
+def test_a12_attention_scores_bwd_is_the_adjoint():
+    """<dp, Z a_src> + <dq, Z a_dst> seen from the other side: sum(dZ_added * Z') for a direction Z'
+    equals the change of dp . p + dq . q; and the vector gradients are the matching contractions"""
+    rng = np.random.default_rng(0)
+    Z = rng.normal(size=(30, 7))
+    a_s, a_d = rng.normal(size=7), rng.normal(size=7)
+    dp, dq = rng.normal(size=30), rng.normal(size=30)
+    out, da_s, da_d = oracle.attention_scores_bwd(Z, a_s, a_d, dp, dq, np.zeros_like(Z))
+    Zd = rng.normal(size=Z.shape)
+    pd, qd = oracle.attention_scores(Zd, a_s, a_d)
+    assert abs(np.sum(out * Zd) - (dp @ pd + dq @ qd)) <= 1e-12
+    ad = rng.normal(size=7)
+    assert abs(da_s @ ad - dp @ (Z @ ad)) <= 1e-12 and abs(da_d @ ad - dq @ (Z @ ad)) <= 1e-12
