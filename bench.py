@@ -327,7 +327,7 @@ def main():
         dp = torch.empty(n, device=dev)
         dq = torch.empty(n, device=dev)
         dy = torch.randn(n, ld, generator=tg, device=dev)
-        t_sg = timed(lambda: ntp.ntp_edge_softmax_bwd(g, p, q, 0.2, a_in, a_out, x, dy, f, ld, ld, dp, dq, st))
+        t_sg = timed(lambda: ntp.ntp_edge_softmax_bwd(g, p, q, 0.2, a_in, a_out, x, dy, f, ld, ld, dp, dq, False, st))
         # algorithmic bytes: by-destination pass reads indices, writes weights (8 B per entry) plus
         # per-vertex arrays (row pointers, p, q, the two statistics); the by-source pass the same
         # per entry plus reads of the statistics

@@ -211,14 +211,40 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
  * p, q [n] device fp32: the scores the weights were computed from; alpha_in, alpha_out [nnz]: both
  * outputs of ntp_edge_softmax; Z, dY [n x m] device fp32, row strides ldz, lddy >= m,
  * 1 <= m <= 1024 when both are 16-byte aligned with m and the strides multiples of 4, m <= 256
- * otherwise (NTP_EUNSUPPORTED); dp, dq [n] device fp32 outputs (every element written).
+ * otherwise (NTP_EUNSUPPORTED); dp, dq [n] device fp32 outputs: every element written when
+ * accumulate is 0, every element added to when it is not (the same weights used by several
+ * aggregation rounds, Section 4.1: one call per round, the first with accumulate = 0).
  * Needs every chunk device-resident (NTP_EBUDGET) and a by-source form (NTP_EUNSUPPORTED for
  * NTP_SCATTER_BWD graphs).  Deterministic.  The handle keeps 4 bytes per edge + 8 per vertex of
  * scratch from the first call on; calls on one handle must not overlap.
  */
 int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float negative_slope,
                          const float* alpha_in, const float* alpha_out, const float* Z, const float* dY,
-                         int64_t m, int64_t ldz, int64_t lddy, float* dp, float* dq, void* stream);
+                         int64_t m, int64_t ldz, int64_t lddy, float* dp, float* dq, int accumulate, void* stream);
+
+/*
+ * The vertex-associated half of the attention of Section 2.1: a^T [W h_u || W h_v] is
+ * p[u] + q[v] with p[v] = Z[v,:] . a_src and q[v] = Z[v,:] . a_dst, Z = the transformed embeddings
+ * (the rows W h_v).  Both products from one read of Z.
+ * Z [n x m] device fp32, row stride ldz >= m, 1 <= m <= 1024; a_src, a_dst [m] device fp32;
+ * p, q [n] device fp32 outputs (what ntp_edge_softmax takes).  Deterministic.
+ */
+int ntp_attention_scores_fwd(const float* Z, const float* a_src, const float* a_dst, float* p, float* q,
+                             int64_t n, int64_t m, int64_t ldz, void* stream);
+
+/*
+ * Chain rule through ntp_attention_scores_fwd, given dp, dq [n] (from ntp_edge_softmax_bwd):
+ *     dZ[v,:] += dp[v] a_src + dq[v] a_dst        (added to what dZ holds: the gradient that
+ *                                                  reached Z along the aggregation)
+ *     da_src = Z^T dp,   da_dst = Z^T dq           ([m] device fp32 outputs, overwritten)
+ * dZ [n x m] device fp32 in/out, row stride lddz >= m; must not alias Z.  scratch: device memory of
+ * at least ntp_attention_scores_bwd_scratch_bytes(n, m) bytes (at most 4 MiB), contents
+ * irrelevant before and after.  Column sums are taken in a fixed order: deterministic.
+ */
+int ntp_attention_scores_bwd(const float* Z, const float* a_src, const float* a_dst, const float* dp, const float* dq,
+                             float* dZ, float* da_src, float* da_dst, int64_t n, int64_t m, int64_t ldz, int64_t lddz,
+                             void* scratch, int64_t scratch_bytes, void* stream);
+int64_t ntp_attention_scores_bwd_scratch_bytes(int64_t n, int64_t m);
 
 /*
  * ntp_aggregate_fwd / ntp_aggregate_bwd with caller-supplied edge weights in place of the

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_chunks",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
     "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_edge_softmax_bwd", "ntp_aggregate_weighted",
+    "ntp_attention_scores_fwd", "ntp_attention_scores_bwd", "ntp_attention_scores_bwd_scratch_bytes",
     "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent", "ntp_softmax_xent_scratch_bytes", "ntp_relu_fwd", "ntp_relu_bwd",
     "ntp_graph_free", "ntp_last_error",
 ]
@@ -61,7 +62,11 @@ def lib():
     L.ntp_chunked_aggregate.argtypes = [vp, ctypes.c_int, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_chunked_aggregate_multi.argtypes = [vp, ctypes.c_int, i32, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_edge_softmax.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp]
-    L.ntp_edge_softmax_bwd.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
+    L.ntp_edge_softmax_bwd.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i64, i64, i64, vp, vp, ctypes.c_int, vp]
+    L.ntp_attention_scores_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
+    L.ntp_attention_scores_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp, i64, vp]
+    L.ntp_attention_scores_bwd_scratch_bytes.argtypes = [i64, i64]
+    L.ntp_attention_scores_bwd_scratch_bytes.restype = i64
     L.ntp_aggregate_weighted.argtypes = [vp, ctypes.c_int, vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_nn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp]
     L.ntp_nn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, i64, vp]
@@ -77,7 +82,8 @@ def lib():
     L.ntp_last_error.restype = ctypes.c_char_p
     for name in EXPORTED_SYMBOLS:
         fn = getattr(L, name)
-        if name not in ("ntp_graph_free", "ntp_last_error", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent_scratch_bytes"):
+        if name not in ("ntp_graph_free", "ntp_last_error", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent_scratch_bytes",
+                        "ntp_attention_scores_bwd_scratch_bytes"):
             fn.restype = ctypes.c_int
     _lib = L
     return L
@@ -198,9 +204,26 @@ def ntp_edge_softmax(g: Graph, p, q, negative_slope, alpha_in, alpha_out=None, s
                                   _stream(stream)))
 
 
-def ntp_edge_softmax_bwd(g: Graph, p, q, negative_slope, alpha_in, alpha_out, Z, dY, m, ldz, lddy, dp, dq, stream=None):
+def ntp_edge_softmax_bwd(g: Graph, p, q, negative_slope, alpha_in, alpha_out, Z, dY, m, ldz, lddy, dp, dq, accumulate=False,
+                         stream=None):
     _check(lib().ntp_edge_softmax_bwd(g.handle, _ptr(p), _ptr(q), float(negative_slope), _ptr(alpha_in), _ptr(alpha_out),
-                                      _ptr(Z), _ptr(dY), int(m), int(ldz), int(lddy), _ptr(dp), _ptr(dq), _stream(stream)))
+                                      _ptr(Z), _ptr(dY), int(m), int(ldz), int(lddy), _ptr(dp), _ptr(dq), int(bool(accumulate)),
+                                      _stream(stream)))
+
+
+def ntp_attention_scores_fwd(Z, a_src, a_dst, p, q, n, m, ldz, stream=None):
+    _check(lib().ntp_attention_scores_fwd(_ptr(Z), _ptr(a_src), _ptr(a_dst), _ptr(p), _ptr(q), int(n), int(m), int(ldz),
+                                          _stream(stream)))
+
+
+def ntp_attention_scores_bwd_scratch_bytes(n, m) -> int:
+    return int(lib().ntp_attention_scores_bwd_scratch_bytes(int(n), int(m)))
+
+
+def ntp_attention_scores_bwd(Z, a_src, a_dst, dp, dq, dZ, da_src, da_dst, n, m, ldz, lddz, scratch, scratch_bytes, stream=None):
+    _check(lib().ntp_attention_scores_bwd(_ptr(Z), _ptr(a_src), _ptr(a_dst), _ptr(dp), _ptr(dq), _ptr(dZ), _ptr(da_src),
+                                          _ptr(da_dst), int(n), int(m), int(ldz), int(lddz), _ptr(scratch), int(scratch_bytes),
+                                          _stream(stream)))
 
 
 def ntp_aggregate_weighted(g: Graph, direction, weights, X, Y, f_slice, ldx, ldy, dtype=NTP_F32, stream=None):

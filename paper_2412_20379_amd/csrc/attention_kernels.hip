@@ -331,7 +331,7 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
                 }
         }
         acc = share_sum(acc);
-        if (writer) { if constexpr (SEG) a.slots[slot] = acc; else a.out[row] = acc; }
+        if (writer) { if constexpr (SEG) a.slots[slot] = acc; else a.out[row] = a.accumulate ? a.out[row] + acc : acc; }
         return;
     }
     // by destination: sweep 1 = dalpha of every entry (parked by the lane that reads it back), t
@@ -365,19 +365,20 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
         dqp += al[k] * (dak - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
     }
     dqp = share_sum(group_sum<L>(dqp, lane));
-    if (writer) { a.out[row] = dqp; reinterpret_cast<float2*>(a.t)[row] = make_float2(t, qv); }
+    if (writer) { a.out[row] = a.accumulate ? a.out[row] + dqp : dqp; reinterpret_cast<float2*>(a.t)[row] = make_float2(t, qv); }
 }
 
-// out[row] = sum of the row's slots, in segment order; with q: the pair (sum, q[row]) at out[2 row]
+// out[row] = sum of the row's slots, in segment order (added to out[row] when accumulate is set);
+// with q: the pair (sum, q[row]) at out[2 row]
 __global__ void __launch_bounds__(256) attention_bwd_combine_kernel(const ReduceItem* items, int n_items, const float* slots, float* out,
-                                                                    const float* q) {
+                                                                    const float* q, int accumulate) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n_items) return;
     const ReduceItem it = items[i];
     float s = 0.f;
     for (int j = 0; j < it.n_slots; ++j) s += slots[it.first_slot + j];
     if (q) reinterpret_cast<float2*>(out)[it.row] = make_float2(s, q[it.row]);
-    else out[it.row] = s;
+    else out[it.row] = accumulate ? out[it.row] + s : s;
 }
 
 template <int VEC, int NJ, int L, bool T>
@@ -487,7 +488,8 @@ int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transpos
         if (r.n_split_rows == 0) return NTP_OK;
         const bool is_t = phase == 1 && !transposed;
         hipLaunchKernelGGL(attention_bwd_combine_kernel, dim3((unsigned)((r.n_split_rows + 255) / 256)), dim3(256), 0, st,
-                           r.split_rows, r.n_split_rows, a.slots, is_t ? a.t : a.out, is_t ? a.q : (const float*)nullptr);
+                           r.split_rows, r.n_split_rows, a.slots, is_t ? a.t : a.out, is_t ? a.q : (const float*)nullptr,
+                           is_t ? 0 : a.accumulate);
         if (hipGetLastError() != hipSuccess) { set_error("attention gradient kernel launch failed"); return NTP_EHIP; }
         return NTP_OK;
     }

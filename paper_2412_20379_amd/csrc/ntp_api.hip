@@ -562,7 +562,7 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
 
 int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float negative_slope,
                          const float* alpha_in, const float* alpha_out, const float* Z, const float* dY,
-                         int64_t m, int64_t ldz, int64_t lddy, float* dp, float* dq, void* stream) {
+                         int64_t m, int64_t ldz, int64_t lddy, float* dp, float* dq, int accumulate, void* stream) {
     if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
     if (g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
     if (!(negative_slope >= 0.f) || !(negative_slope <= 1.f)) { set_error("negative_slope must be in [0, 1]"); return NTP_EINVAL; }
@@ -611,6 +611,7 @@ int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float n
                 a.slots = slots;
                 a.slope = negative_slope;
                 a.m = (int32_t)m;
+                a.accumulate = accumulate ? 1 : 0;
                 AttBwdRows r;
                 r.n_group_rows = c.bin_row_off[NBINS - 1];
                 r.n_block_rows = c.bin_count[NBINS - 1];
@@ -626,6 +627,35 @@ int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float n
     int rc = run(Fin, false);           // dq and t first: the by-source pass reads t
     if (rc == NTP_OK) rc = run(Fout, true);
     return rc;
+}
+
+int ntp_attention_scores_fwd(const float* Z, const float* a_src, const float* a_dst, float* p, float* q,
+                             int64_t n, int64_t m, int64_t ldz, void* stream) {
+    if (n < 0 || m < 1 || m > attention_scores_max_width() || ldz < m) {
+        set_error("bad shape n=%lld m=%lld ldz=%lld (1 <= m <= %lld)", (long long)n, (long long)m, (long long)ldz, (long long)attention_scores_max_width());
+        return NTP_EINVAL;
+    }
+    if (n == 0) return NTP_OK;
+    if (!Z || !a_src || !a_dst || !p || !q) { set_error("NULL buffer"); return NTP_EINVAL; }
+    return launch_attention_scores_fwd(Z, a_src, a_dst, p, q, n, m, ldz, stream);
+}
+
+int64_t ntp_attention_scores_bwd_scratch_bytes(int64_t n, int64_t m) { return attention_scores_bwd_scratch_bytes(n, m); }
+
+int ntp_attention_scores_bwd(const float* Z, const float* a_src, const float* a_dst, const float* dp, const float* dq,
+                             float* dZ, float* da_src, float* da_dst, int64_t n, int64_t m, int64_t ldz, int64_t lddz,
+                             void* scratch, int64_t scratch_bytes, void* stream) {
+    if (n < 0 || m < 1 || m > attention_scores_max_width() || ldz < m || lddz < m) {
+        set_error("bad shape n=%lld m=%lld ldz=%lld lddz=%lld (1 <= m <= %lld)", (long long)n, (long long)m, (long long)ldz, (long long)lddz,
+                  (long long)attention_scores_max_width());
+        return NTP_EINVAL;
+    }
+    if (!a_src || !a_dst || !da_src || !da_dst) { set_error("NULL buffer"); return NTP_EINVAL; }
+    if (n > 0 && (!Z || !dp || !dq || !dZ)) { set_error("NULL buffer"); return NTP_EINVAL; }
+    if (n == 0) return launch_zero_rows(da_src, 1, m, m, NTP_F32, stream) || launch_zero_rows(da_dst, 1, m, m, NTP_F32, stream);
+    const int64_t need = attention_scores_bwd_scratch_bytes(n, m);
+    if (!scratch || scratch_bytes < need) { set_error("scratch too small: need %lld bytes", (long long)need); return NTP_EINVAL; }
+    return launch_attention_scores_bwd(Z, a_src, a_dst, dp, dq, dZ, da_src, da_dst, n, m, ldz, lddz, (float*)scratch, stream);
 }
 
 int ntp_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,

@@ -198,6 +198,7 @@ struct AttBwdArgs {
     float* slots;              // [n_slots] partial sums of the segments of split rows
     float slope;
     int32_t m;                 // feature width
+    int32_t accumulate;        // add to out instead of overwriting it
 };
 // rows[0 .. n_group_rows): a lane group each; rows[n_group_rows .. + n_block_rows): a wavefront
 // each (the bin lists are stored by increasing entry count); split rows: a block per segment
@@ -210,6 +211,15 @@ struct AttBwdRows {
     int n_split_rows;
 };
 int launch_attention_bwd(const AttBwdArgs& a, const AttBwdRows& r, bool transposed, int phase, void* stream);
+
+// per-vertex attention scores and their chain rule (attention_scores_kernels.hip)
+int64_t attention_scores_max_width();
+int64_t attention_scores_bwd_scratch_bytes(int64_t n, int64_t m);
+int launch_attention_scores_fwd(const float* Z, const float* a_src, const float* a_dst, float* p, float* q,
+                                int64_t n, int64_t m, int64_t ldz, void* stream);
+int launch_attention_scores_bwd(const float* Z, const float* a_src, const float* a_dst, const float* dp, const float* dq,
+                                float* dZ, float* da_src, float* da_dst, int64_t n, int64_t m, int64_t ldz, int64_t lddz,
+                                float* scratch, void* stream);
 
 int launch_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss, float* scratch,
                         int64_t n, int64_t c, int64_t ldz, int64_t lddz, void* stream);
