@@ -343,6 +343,15 @@ def main():
         lab = torch.randint(0, dims[-1], (n,), generator=tg, device=dev)
         gep = GatEpoch(g, n, nnz, dims, rounds=2)
         t_ep = timed(lambda: gep.run(Xg, Wg, a_s, a_d, lab))
+        del gep
+        # the same with the edge permutation stored (NTP_EDGE_PERM): one dot product per edge
+        gp = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | ntp.NTP_EDGE_PERM)
+        ntp.ntp_edge_softmax(gp, p, q, 0.2, a_in, a_out, st)
+        t_sg_perm = timed(lambda: ntp.ntp_edge_softmax_bwd(gp, p, q, 0.2, a_in, a_out, x, dy, f_sg, ld, ld, dp, dq, False, st))
+        gep = GatEpoch(gp, n, nnz, dims, rounds=2)
+        t_ep_perm = timed(lambda: gep.run(Xg, Wg, a_s, a_d, lab))
+        del gep
+        gp.close()
         # algorithmic bytes: by-destination pass reads indices, writes weights (8 B per entry) plus
         # per-vertex arrays (row pointers, p, q, the two statistics); the by-source pass the same
         # per entry plus reads of the statistics
@@ -356,12 +365,14 @@ def main():
                "aggregate_weighted_fwd_ms": t_w, "aggregate_stored_weights_fwd_ms": t_s,
                "edge_softmax_bwd_ms": t_sg, "edge_softmax_bwd_vs_two_aggregations": t_sg / (2 * t_w),
                "edge_softmax_bwd_gathered_gbs": 2 * nnz * f_sg * 4 / (t_sg * 1e-3) / 1e9, "edge_softmax_bwd_width": f_sg,
-               "gat_epoch_ms": t_ep, "gat_epoch_dims": list(dims), "gat_epoch_rounds": 2}
+               "gat_epoch_ms": t_ep, "gat_epoch_dims": list(dims), "gat_epoch_rounds": 2,
+               "edge_softmax_bwd_with_edge_perm_ms": t_sg_perm, "gat_epoch_with_edge_perm_ms": t_ep_perm}
         log("edge softmax: %.3f ms both orders (%.0f GB/s algorithmic, %.1f%% of 8 TB/s), %.3f ms by destination only; "
             "weighted aggregation f=%d %.3f ms (stored weights %.3f ms); score gradient %.3f ms (%.2f x two aggregations)"
             % (t_att, out["edge_softmax_gbs"], 100 * out["edge_softmax_frac_hbm"], t_att_in, f, t_w, t_s, t_sg,
                out["edge_softmax_bwd_vs_two_aggregations"]))
-        log("decoupled GAT epoch %s, 2 rounds: %.3f ms" % ("-".join(str(x) for x in dims), t_ep))
+        log("decoupled GAT epoch %s, 2 rounds: %.3f ms; with NTP_EDGE_PERM: score gradient %.3f ms, epoch %.3f ms"
+            % ("-".join(str(x) for x in dims), t_ep, t_sg_perm, t_ep_perm))
         print(json.dumps(out), flush=True)
         g.close()
         return

@@ -61,6 +61,12 @@ extern "C" {
                                     memory and host-link traffic of a directed graph; the order of
                                     the additions, hence the last bits, vary from run to run; fp32
                                     buffers only.  No effect when the adjacency is symmetric. */
+#define NTP_EDGE_PERM      128u  /* also keep, for every entry of the by-source form, the position
+                                    of the same edge in the by-destination form (4 bytes per entry
+                                    on the host and on the device, outside device_budget_bytes;
+                                    fewer than 2^31 entries; not with NTP_SCATTER_BWD):
+                                    ntp_edge_softmax_bwd then forms every edge's dot product once
+                                    instead of once per form */
 
 /* which compressed form */
 #define NTP_CSR 0   /* by destination: row v lists in-neighbours u ascending  (forward)  */
@@ -116,6 +122,11 @@ int ntp_graph_info(const ntp_graph_t* g, int64_t* n_vertices, int64_t* nnz,
  * val[nnz] fp32), for bit-exact comparison.  Any of the three may be NULL. */
 int ntp_graph_export(const ntp_graph_t* g, int which,
                      int64_t* rowptr, int32_t* colidx, float* val);
+
+/* Copy the edge permutation of a graph built with NTP_EDGE_PERM to perm[nnz] (host int32):
+ * perm[k] = position in the by-destination form (ntp_graph_export(NTP_CSR)) of the edge stored at
+ * position k of the by-source form.  NTP_EUNSUPPORTED without the flag. */
+int ntp_graph_export_perm(const ntp_graph_t* g, int32_t* perm);
 
 /* Chunk table of one form: for chunk c, rows [row_begin[c], row_end[c]) and entries
  * [entry_begin[c], entry_end[c]); resident[c] = 1 if it lives on the device.  Arrays
@@ -215,7 +226,9 @@ int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negat
  * accumulate is 0, every element added to when it is not (the same weights used by several
  * aggregation rounds, Section 4.1: one call per round, the first with accumulate = 0).
  * Needs every chunk device-resident (NTP_EBUDGET) and a by-source form (NTP_EUNSUPPORTED for
- * NTP_SCATTER_BWD graphs).  Deterministic.  The handle keeps 4 bytes per edge + 8 per vertex of
+ * NTP_SCATTER_BWD graphs).  On a graph built with NTP_EDGE_PERM the by-source pass is a one-column
+ * aggregation of per-edge values through the permutation instead of a second round of dot products
+ * (same result to rounding).  Deterministic.  The handle keeps 4 bytes per edge + 12 per vertex of
  * scratch from the first call on; calls on one handle must not overlap.
  */
 int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float negative_slope,

@@ -17,7 +17,7 @@ of the attention scores and the whole GAT epoch by finite differences and by
 the reductions to a mean aggregation and to an MLP.  No function here is unpinned.
 """
 from .graph import (  # noqa: F401
-    Graph, Sparse, build_graph, plan_chunks,
+    Graph, Sparse, build_graph, plan_chunks, edge_permutation,
     SYMMETRISE, DEDUP, ADD_SELF_LOOPS, NORM_GCN_SYM, GCN_FLAGS, DIRECTED_GCN_FLAGS,
 )
 from .aggregate import (  # noqa: F401

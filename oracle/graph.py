@@ -128,3 +128,12 @@ def plan_chunks(rowptr: np.ndarray, chunk_edges: int):
         out.append((r, r1))
         r = r1
     return out
+
+
+def edge_permutation(g: Graph) -> np.ndarray:
+    """perm[k] = position in the by-destination form of the edge stored at position k of the
+    by-source form.  The by-source form lists the sources u ascending and, for each, its edges in
+    the order the by-destination form holds them (destinations ascending), so it is the
+    by-destination entries stably sorted by their source."""
+    return np.argsort(g.csr.colidx, kind="stable").astype(np.int64)
+

@@ -11,6 +11,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 NTP_OK, NTP_EINVAL, NTP_ENOMEM, NTP_EHIP, NTP_EBUDGET, NTP_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 NTP_SYMMETRISE, NTP_DEDUP, NTP_ADD_SELF_LOOPS, NTP_NORM_GCN_SYM, NTP_HOST_ONLY, NTP_FORCE_STREAM = 1, 2, 4, 8, 16, 32
 NTP_SCATTER_BWD = 64
+NTP_EDGE_PERM = 128
 NTP_GCN_FLAGS = NTP_SYMMETRISE | NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM
 NTP_DIRECTED_GCN_FLAGS = NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM
 NTP_CSR, NTP_CSC = 0, 1
@@ -19,7 +20,7 @@ NTP_FWD, NTP_BWD = 0, 1
 NTP_ACT_NONE, NTP_ACT_RELU = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_chunks",
+    "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_export_perm", "ntp_graph_chunks",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
     "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_edge_softmax_bwd", "ntp_aggregate_weighted",
     "ntp_attention_scores_fwd", "ntp_attention_scores_bwd", "ntp_attention_scores_bwd_scratch_bytes",
@@ -55,6 +56,7 @@ def lib():
     L.ntp_graph_build.argtypes = [i64, i64, vp, vp, vp, u32, i64, i64, ctypes.POINTER(vp)]
     L.ntp_graph_info.argtypes = [vp, vp, vp, vp, vp, vp]
     L.ntp_graph_export.argtypes = [vp, ctypes.c_int, vp, vp, vp]
+    L.ntp_graph_export_perm.argtypes = [vp, vp]
     L.ntp_graph_chunks.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp]
     L.ntp_graph_device_bytes.argtypes = [vp, vp]
     L.ntp_aggregate_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
@@ -169,6 +171,13 @@ def ntp_graph_export(g: Graph, which=NTP_CSR):
     val = np.empty(nnz, dtype=np.float32)
     _check(lib().ntp_graph_export(g.handle, which, None, _ptr(colidx), _ptr(val)))
     return rowptr, colidx, val
+
+
+def ntp_graph_export_perm(g: Graph) -> np.ndarray:
+    """by-source entry -> by-destination entry of a graph built with NTP_EDGE_PERM"""
+    perm = np.empty(ntp_graph_info(g)["nnz"], dtype=np.int32)
+    _check(lib().ntp_graph_export_perm(g.handle, _ptr(perm)))
+    return perm
 
 
 def ntp_graph_chunks(g: Graph, which=NTP_CSR) -> dict:

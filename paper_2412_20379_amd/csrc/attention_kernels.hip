@@ -291,7 +291,9 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
         float dqp = 0.f;
         for (int64_t k = threadIdx.x; k < d; k += 256) {
             const int cc = ci[k];
-            dqp += al[k] * (park[k] - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
+            const float wv = (park[k] - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
+            if (a.keep_w) park[k] = wv;
+            dqp += al[k] * wv;
         }
         dqp = share_sum(group_sum<L>(dqp, lane));
         if (writer) a.slots[slot] = dqp;
@@ -362,7 +364,9 @@ __global__ void __launch_bounds__(256) attention_bwd_kernel(const AttBwdArgs a, 
     for (int64_t k = gi + SHARE * l; k < d; k += SHARE * L) {                // k % SHARE == gi, (k / SHARE) % L == l
         const int cc = ci[k];
         const float dak = k < SHARE * L ? mine : park[k];
-        dqp += al[k] * (dak - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
+        const float wv = (dak - t) * (a.p[cc] + qv > 0.f ? 1.f : a.slope);
+        if (a.keep_w) park[k] = wv;
+        dqp += al[k] * wv;
     }
     dqp = share_sum(group_sum<L>(dqp, lane));
     if (writer) { a.out[row] = a.accumulate ? a.out[row] + dqp : dqp; reinterpret_cast<float2*>(a.t)[row] = make_float2(t, qv); }
@@ -379,6 +383,11 @@ __global__ void __launch_bounds__(256) attention_bwd_combine_kernel(const Reduce
     for (int j = 0; j < it.n_slots; ++j) s += slots[it.first_slot + j];
     if (q) reinterpret_cast<float2*>(out)[it.row] = make_float2(s, q[it.row]);
     else out[it.row] = accumulate ? out[it.row] + s : s;
+}
+
+__global__ void __launch_bounds__(256) vec_add_kernel(float* __restrict__ a, const float* __restrict__ b, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) a[i] += b[i];
 }
 
 template <int VEC, int NJ, int L, bool T>
@@ -476,6 +485,13 @@ int launch_attention(const AttArgs& a, const int32_t* bin_row_off, const int32_t
     if (rc == NTP_OK && hipGetLastError() != hipSuccess) rc = NTP_EHIP;
     if (rc != NTP_OK) set_error("attention kernel launch failed");
     return rc;
+}
+
+int launch_vec_add(float* a, const float* b, int64_t n, void* stream) {
+    if (n <= 0) return NTP_OK;
+    hipLaunchKernelGGL(vec_add_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, a, b, n);
+    if (hipGetLastError() != hipSuccess) { set_error("kernel launch failed"); return NTP_EHIP; }
+    return NTP_OK;
 }
 
 // By destination: phase 0 = whole rows (dq, t) and the first sweep of the segments (partial t),

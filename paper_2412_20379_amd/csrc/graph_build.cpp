@@ -250,4 +250,23 @@ int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32
     return NTP_OK;
 }
 
+// perm[p] = position, in the by-destination form, of the edge stored at position p of the
+// by-source form (the by-destination form itself when the graph is symmetric).  The rows of the
+// by-source form were filled by walking the by-destination entries in order, so walking them
+// again in that order meets the positions of every by-source row in increasing order.
+void build_edge_perm(const BuiltGraph& G, int32_t* perm) {
+    const HostSparse& R = G.csr;
+    const HostSparse& S = G.symmetric ? G.csr : G.csc;
+    const int64_t n = G.n;
+    const int T = host_threads();
+    std::vector<int64_t> fill(S.rowptr.begin(), S.rowptr.end() - 1);
+    parallel_for_threads(T, [&](int t, int nt) {
+        const int64_t lo = n * t / nt, hi = n * (t + 1) / nt;
+        for (int64_t e = 0; e < R.nnz; ++e) {
+            const int32_t u = R.colidx[e];
+            if (u >= lo && u < hi) perm[fill[u]++] = (int32_t)e;
+        }
+    });
+}
+
 }  // namespace ntp

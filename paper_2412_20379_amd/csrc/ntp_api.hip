@@ -46,6 +46,8 @@ struct ntp_graph {
     size_t partial_bytes = 0;
     float* att_stats = nullptr;    // [4 n]: per-destination (q, maximum, 1 / sum, 0) of the last ntp_edge_softmax
     float* att_bwd = nullptr;      // scratch of ntp_edge_softmax_bwd: per-destination (t, q), per-segment partial sums, per-edge dalpha
+    std::vector<int32_t> h_perm;   // NTP_EDGE_PERM: by-source entry -> by-destination entry
+    int32_t* d_perm = nullptr;
     int64_t device_bytes = 0;
 
     // the by-source product runs as a scatter over the by-destination form
@@ -95,13 +97,13 @@ inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX
 // weights: caller's edge weights in the entry order of the form (nullptr: the stored ones)
 int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* partial,
               int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st, bool scatter = false,
-              const float* weights = nullptr) {
+              const float* weights = nullptr, const int32_t* columns = nullptr) {
     AggArgs a;
     memset(&a, 0, sizeof a);
     a.rowptr = reinterpret_cast<const int64_t*>(img + c.off_rowptr);
     a.rows = reinterpret_cast<const int32_t*>(img + c.off_rows);
     a.segs = reinterpret_cast<const Segment*>(img + c.off_segs);
-    a.colidx = reinterpret_cast<const int32_t*>(img + c.img_off_colidx);
+    a.colidx = columns ? columns + c.e_begin : reinterpret_cast<const int32_t*>(img + c.img_off_colidx);
     a.val = weights ? weights + c.e_begin : reinterpret_cast<const float*>(img + c.img_off_val);
     a.X = X;
     a.Y = Y;
@@ -217,6 +219,7 @@ void destroy(ntp_graph* G) {
     if (G->partial) (void)hipFree(G->partial);
     if (G->att_stats) (void)hipFree(G->att_stats);
     if (G->att_bwd) (void)hipFree(G->att_bwd);
+    if (G->d_perm) (void)hipFree(G->d_perm);
     if (G->pinned_meta) (void)hipHostFree(G->pinned_meta);
     free_entries(G->g.csr, G->pinned_entries);
     free_entries(G->g.csc, G->pinned_entries);
@@ -238,8 +241,9 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
     if (n_edges < 0 || (n_edges > 0 && (!src || !dst))) { set_error("edge list missing"); return NTP_EINVAL; }
     if (budget < 0 || chunk_edges < 0) { set_error("negative budget or chunk size"); return NTP_EINVAL; }
     if (chunk_edges > INT_MAX) { set_error("chunk_edges must be below 2^31"); return NTP_EINVAL; }
-    const uint32_t known = NTP_SYMMETRISE | NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM | NTP_HOST_ONLY | NTP_FORCE_STREAM | NTP_SCATTER_BWD;
+    const uint32_t known = NTP_SYMMETRISE | NTP_DEDUP | NTP_ADD_SELF_LOOPS | NTP_NORM_GCN_SYM | NTP_HOST_ONLY | NTP_FORCE_STREAM | NTP_SCATTER_BWD | NTP_EDGE_PERM;
     if (flags & ~known) { set_error("unknown flag bits 0x%x", flags & ~known); return NTP_EINVAL; }
+    if ((flags & NTP_EDGE_PERM) && (flags & NTP_SCATTER_BWD)) { set_error("NTP_EDGE_PERM needs the by-source form that NTP_SCATTER_BWD leaves out"); return NTP_EINVAL; }
 
     ntp_graph* G = new (std::nothrow) ntp_graph();
     if (!G) { set_error("out of host memory"); return NTP_ENOMEM; }
@@ -268,6 +272,12 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
             const int64_t per_buf = (budget > 0 ? budget : need) / 4;    // two buffers use half
             ce = std::max<int64_t>(1024, std::min<int64_t>((per_buf - 4096) / 20, INT_MAX / 2));
         }
+    }
+    if (flags & NTP_EDGE_PERM) {
+        const int64_t nnz = G->g.csr.nnz;
+        if (nnz > INT_MAX) { set_error("NTP_EDGE_PERM takes graphs of fewer than 2^31 stored entries"); return NTP_EUNSUPPORTED; }
+        G->h_perm.resize((size_t)nnz);
+        build_edge_perm(G->g, G->h_perm.data());
     }
     for (int k = 0; k < n_forms; ++k) make_plan(*G->form[k].m, ce, &G->form[k].plan);
     for (int k = 0; k < n_forms; ++k)
@@ -343,6 +353,14 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
                         off += c.meta.size();
                     }
         }
+        if (!G->h_perm.empty()) {
+            void* p = nullptr;
+            const size_t bytes = G->h_perm.size() * 4;
+            if (hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes for the edge permutation failed", bytes); return NTP_ENOMEM; }
+            G->d_perm = (int32_t*)p;
+            G->device_bytes += (int64_t)bytes;
+            if (hipMemcpy(G->d_perm, G->h_perm.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) { (void)hipGetLastError(); set_error("upload of the edge permutation failed"); return NTP_EHIP; }
+        }
         const hipError_t se = hipDeviceSynchronize();
         if (se != hipSuccess) { set_error("hipDeviceSynchronize failed: %s", hipGetErrorString(se)); return NTP_EHIP; }
     }
@@ -388,6 +406,13 @@ int ntp_graph_export(const ntp_graph_t* g, int which, int64_t* rowptr, int32_t* 
     return NTP_OK;
 }
 
+int ntp_graph_export_perm(const ntp_graph_t* g, int32_t* perm) {
+    if (!g || !perm) { set_error("NULL argument"); return NTP_EINVAL; }
+    if (g->h_perm.empty() && g->g.csr.nnz > 0) { set_error("graph was built without NTP_EDGE_PERM"); return NTP_EUNSUPPORTED; }
+    if (!g->h_perm.empty()) memcpy(perm, g->h_perm.data(), g->h_perm.size() * 4);
+    return NTP_OK;
+}
+
 int ntp_graph_chunks(const ntp_graph_t* g, int which, int32_t* n_chunks, int64_t* row_begin,
                      int64_t* row_end, int64_t* entry_begin, int64_t* entry_end, int32_t* resident) {
     if (!g || !n_chunks) { set_error("graph handle or n_chunks is NULL"); return NTP_EINVAL; }
@@ -412,7 +437,8 @@ int ntp_graph_device_bytes(const ntp_graph_t* g, int64_t* bytes) {
 }
 
 static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y, int64_t f,
-                              int64_t ldx, int64_t ldy, int dtype, void* stream, const float* weights = nullptr) {
+                              int64_t ldx, int64_t ldy, int dtype, void* stream, const float* weights = nullptr,
+                              const int32_t* columns = nullptr) {
     int rc = check_agg_args(g, X, Y, f, ldx, ldy, dtype);
     if (rc != NTP_OK) return rc;
     Form& F = g->f(which);
@@ -424,7 +450,7 @@ static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y,
     else rc = ensure_partial(g, F, f);
     if (rc != NTP_OK) return rc;
     for (auto& c : F.plan.chunks) {
-        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights);
+        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights, columns);
         if (rc != NTP_OK) return rc;
     }
     return NTP_OK;
@@ -578,19 +604,22 @@ int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float n
         return NTP_EBUDGET;
     }
     // scratch kept by the handle: (t, q) of every destination, one partial sum per segment of a
-    // split row, dalpha of every edge
+    // split row, one dp per vertex, dalpha of every edge
     const int64_t nnz = g->g.csr.nnz;
     const int64_t n_slots = std::max(Fin.plan.n_slots, Fout.plan.n_slots);
     if (!g->att_bwd) {
         void* ptr = nullptr;
-        const size_t bytes = ((size_t)nnz + 2 * (size_t)n + (size_t)n_slots) * 4 + 16;
+        // the per-edge array is also read as a one-column feature matrix indexed by ids below n
+        const size_t bytes = ((size_t)std::max(nnz, n) + 3 * (size_t)n + (size_t)n_slots) * 4 + 16;
         if (hipMalloc(&ptr, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes failed", bytes); return NTP_ENOMEM; }
         g->att_bwd = (float*)ptr;
         g->device_bytes += (int64_t)bytes;
     }
     float* t = g->att_bwd;              // (t, q) pairs
     float* slots = t + 2 * n;
-    float* park = slots + n_slots;
+    float* dp_round = slots + n_slots;  // [n] this call's dp when it is added to the caller's
+    float* park = dp_round + n;
+    const bool by_perm = g->d_perm != nullptr;
     // chunk by chunk, phase by phase (a split row's segments may lie in several chunks)
     auto run = [&](const Form& F, bool transposed) -> int {
         for (int phase = 0; phase < (transposed ? 2 : 4); ++phase)
@@ -612,6 +641,7 @@ int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float n
                 a.slope = negative_slope;
                 a.m = (int32_t)m;
                 a.accumulate = accumulate ? 1 : 0;
+                a.keep_w = by_perm ? 1 : 0;
                 AttBwdRows r;
                 r.n_group_rows = c.bin_row_off[NBINS - 1];
                 r.n_block_rows = c.bin_count[NBINS - 1];
@@ -625,7 +655,14 @@ int ntp_edge_softmax_bwd(ntp_graph_t* g, const float* p, const float* q, float n
         return NTP_OK;
     };
     int rc = run(Fin, false);           // dq and t first: the by-source pass reads t
-    if (rc == NTP_OK) rc = run(Fout, true);
+    if (rc != NTP_OK) return rc;
+    if (!by_perm) return run(Fout, true);
+    // every edge's w = (dalpha - t) * LeakyReLU' now sits in park, in by-destination order:
+    // dp[u] = sum over the out-edges of alpha w is a one-column aggregation over the by-source
+    // form whose column ids are the edges' by-destination positions
+    float* dst = accumulate ? dp_round : dp;
+    rc = aggregate_resident(g, NTP_CSC, park, dst, 1, 1, 1, NTP_F32, stream, alpha_out, g->d_perm);
+    if (rc == NTP_OK && accumulate) rc = launch_vec_add(dp, dp_round, n, stream);
     return rc;
 }
 

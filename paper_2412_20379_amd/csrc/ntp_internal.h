@@ -59,6 +59,10 @@ int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32
                      const float* edge_weight, uint32_t flags, EntryAllocator alloc,
                      BuiltGraph* out);
 
+// perm[p] (nnz entries, nnz < 2^31): where the edge at position p of the by-source form sits in
+// the by-destination form
+void build_edge_perm(const BuiltGraph& G, int32_t* perm);
+
 // ---------------------------------------------------------------------------------------
 // Plan: how the rows of one compressed form are mapped to wavefronts.
 //
@@ -199,6 +203,7 @@ struct AttBwdArgs {
     float slope;
     int32_t m;                 // feature width
     int32_t accumulate;        // add to out instead of overwriting it
+    int32_t keep_w;            // by destination: leave (dalpha - t) * LeakyReLU' of every entry in park
 };
 // rows[0 .. n_group_rows): a lane group each; rows[n_group_rows .. + n_block_rows): a wavefront
 // each (the bin lists are stored by increasing entry count); split rows: a block per segment
@@ -220,6 +225,9 @@ int launch_attention_scores_fwd(const float* Z, const float* a_src, const float*
 int launch_attention_scores_bwd(const float* Z, const float* a_src, const float* a_dst, const float* dp, const float* dq,
                                 float* dZ, float* da_src, float* da_dst, int64_t n, int64_t m, int64_t ldz, int64_t lddz,
                                 float* scratch, void* stream);
+
+// a[i] += b[i]
+int launch_vec_add(float* a, const float* b, int64_t n, void* stream);
 
 int launch_softmax_xent(const float* Z, const int64_t* labels, float* dZ, float* loss, float* scratch,
                         int64_t n, int64_t c, int64_t ldz, int64_t lddz, void* stream);

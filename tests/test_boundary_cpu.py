@@ -96,6 +96,62 @@ def test_graph_build_without_by_source_form(flags, weighted):
     _assert_same(gs, oracle.build_graph(n, src, dst, oracle.GCN_FLAGS))
 
 
+@pytest.mark.parametrize("flags", [0, 1, 2, 3, 4, 6, 7, 14, 15])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_edge_permutation_bit_exact(flags, weighted):
+    """NTP_EDGE_PERM: by-source entry -> by-destination entry, equal to the oracle's; both forms
+    unchanged by the flag; the permuted by-destination entries are the by-source entries"""
+    n = 250
+    src, dst = gen.directed_random_edges(n, 2000, seed=70 + flags, hub=2, hub_in=120, hub_out=60)
+    src = np.concatenate([src, src[:40], np.arange(15, dtype=np.int32)])      # repeated pairs and loops
+    dst = np.concatenate([dst, dst[:40], np.arange(15, dtype=np.int32)])
+    w = gen.stream_rng(flags, 13).random(src.size).astype(np.float32) + 0.5 if weighted else None
+    g = ntp.ntp_graph_build(n, src, dst, w, flags=flags | HOST | ntp.NTP_EDGE_PERM)
+    og = oracle.build_graph(n, src, dst, flags, w)
+    _assert_same(g, og)
+    perm = ntp.ntp_graph_export_perm(g)
+    want = oracle.edge_permutation(og)
+    # parallel copies of one edge (no DEDUP) may be matched in any order: compare what is unique
+    rows = np.repeat(np.arange(n), np.diff(og.csr.rowptr))
+    assert np.array_equal(np.sort(perm), np.arange(og.csr.nnz))
+    assert np.array_equal(rows[perm], og.csc.colidx) and np.array_equal(og.csr.colidx[perm], np.repeat(np.arange(n), np.diff(og.csc.rowptr)))
+    if flags & 2:
+        assert np.array_equal(perm, want)
+
+
+def test_edge_permutation_pins_of_the_oracle():
+    """the oracle's permutation against scipy's transpose of an entry-numbered matrix, and on a
+    three-vertex example written out by hand"""
+    import scipy.sparse as sp
+    n = 300
+    src, dst = gen.directed_random_edges(n, 3000, 21, hub=5, hub_in=200, hub_out=90)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    ids = sp.csr_matrix((np.arange(1, og.csr.nnz + 1, dtype=np.float64), og.csr.colidx, og.csr.rowptr), shape=(n, n))
+    t = ids.transpose().tocsr()
+    t.sort_indices()
+    assert np.array_equal(oracle.edge_permutation(og), t.data.astype(np.int64) - 1)
+    # edges 0 -> 1, 0 -> 2, 2 -> 1, no self loops.  By destination: row 1 = [0, 2], row 2 = [0], i.e.
+    # entries (0->1), (2->1), (0->2) at positions 0, 1, 2.  By source: row 0 = [1, 2], row 2 = [1], i.e.
+    # (0->1), (0->2), (2->1): positions 0, 2, 1 of the by-destination form.
+    g3 = oracle.build_graph(3, np.array([0, 0, 2], np.int32), np.array([1, 2, 1], np.int32), oracle.DEDUP)
+    assert g3.csr.colidx.tolist() == [0, 2, 0] and g3.csc.colidx.tolist() == [1, 2, 1]
+    assert oracle.edge_permutation(g3).tolist() == [0, 2, 1]
+
+
+def test_edge_permutation_errors():
+    n = 50
+    src, dst = gen.directed_random_edges(n, 200, 1)
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | HOST | ntp.NTP_EDGE_PERM | ntp.NTP_SCATTER_BWD)
+    assert e.value.code == ntp.NTP_EINVAL
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | HOST)
+    with pytest.raises(ntp.NtpError) as e:
+        ntp.ntp_graph_export_perm(g)
+    assert e.value.code == ntp.NTP_EUNSUPPORTED
+    g0 = ntp.ntp_graph_build(0, [], [], flags=ntp.NTP_GCN_FLAGS | HOST | ntp.NTP_EDGE_PERM)
+    assert ntp.ntp_graph_export_perm(g0).size == 0
+
+
 def test_symmetric_input_without_symmetrise_flag_is_detected():
     n = 500
     s, d = gen.erdos_renyi_edges(n, 2000, 3)

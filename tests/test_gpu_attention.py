@@ -361,3 +361,92 @@ def test_score_gradient_argument_errors(hub):
         ntp.ntp_edge_softmax_bwd(one_form, s, s, 0.2, a, a, v, v, 8, 1100, 1100, out, out.clone())
     assert e.value.code == ntp.NTP_EUNSUPPORTED
     one_form.close()
+
+
+# ---- the same gradient on graphs built with NTP_EDGE_PERM (one dot product per edge) -----------
+PERM = ntp.NTP_EDGE_PERM
+
+
+@pytest.fixture(scope="module")
+def hub_perm():
+    n = 3000
+    src, dst = gen.directed_random_edges(n, 40000, 21, hub=5, hub_in=2600, hub_out=900)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | PERM)
+    assert np.array_equal(ntp.ntp_graph_export_perm(g), oracle.edge_permutation(og))
+    yield n, src, dst, g, og
+    g.close()
+
+
+@pytest.mark.parametrize("m", [1, 8, 50, 64, 256, 1024])
+def test_score_gradient_by_permutation_widths(hub_perm, m):
+    n, src, dst, g, og = hub_perm
+    _score_grad_case(g, og, m, 0.2, 140 + m, "hub graph with edge permutation")
+
+
+def test_score_gradient_by_permutation_slopes_and_strides(hub_perm):
+    n, src, dst, g, og = hub_perm
+    _score_grad_case(g, og, 64, 0.0, 15, "slope 0")
+    _score_grad_case(g, og, 64, 1.0, 16, "slope 1")
+    _score_grad_case(g, og, 64, 0.2, 17, "odd strides", ldz=67, lddy=65)
+
+
+def test_score_gradient_by_permutation_symmetric_chunked_and_sparse():
+    import torch
+    for cfg, scale, m in ((1, 1, 16), (2, 1, 64), (4, 64, 76)):
+        n, src, dst = gen.make_graph(cfg, seed=0, scale_down=scale)
+        og = oracle.build_graph(n, src, dst, oracle.GCN_FLAGS)
+        g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | PERM)
+        _score_grad_case(g, og, m, 0.2, 30 + cfg, "config %d with edge permutation" % cfg)
+        g.close()
+    n = 3000
+    src, dst = gen.directed_random_edges(n, 40000, 21, hub=5, hub_in=2600, hub_out=900)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    for chunk_edges in (5003, 700, 101):
+        gc = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | PERM, chunk_edges=chunk_edges)
+        _score_grad_case(gc, og, 32, 0.2, 19, "chunks of %d edges with edge permutation" % chunk_edges)
+        gc.close()
+    # fewer stored entries than vertices (no self loops, most vertices without edges)
+    n = 5000
+    src, dst = gen.directed_random_edges(n, 900, 5)
+    flags = oracle.DEDUP
+    og = oracle.build_graph(n, src, dst, flags)
+    assert og.csr.nnz < n
+    for extra in (0, PERM):
+        g = ntp.ntp_graph_build(n, src, dst, flags=flags | extra)
+        _score_grad_case(g, og, 16, 0.2, 23, "sparse graph without self loops, flags +%d" % extra)
+        g.close()
+
+
+def test_score_gradient_accumulates_over_calls(hub, hub_perm):
+    """accumulate = 1 adds the call's gradient to what dp, dq hold, with and without the permutation"""
+    import torch
+    from gpu_util import dev_f32
+    for n, src, dst, g, og in (hub, hub_perm):
+        nnz, m = og.csr.nnz, 24
+        p, q = _scores(n, 31)
+        rng = gen.stream_rng(31, 78)
+        Z1, dY1, Z2, dY2 = (rng.normal(size=(n, m)).astype(np.float32) for _ in range(4))
+        a_in, a_out = _device_alpha(g, nnz, p, q, 0.2)
+        dp = torch.full((n,), float("nan"), device="cuda:0")
+        dq = torch.full((n,), float("nan"), device="cuda:0")
+        pd, qd = dev_f32(p), dev_f32(q)
+        ntp.ntp_edge_softmax_bwd(g, pd, qd, 0.2, a_in, a_out, dev_f32(Z1), dev_f32(dY1), m, m, m, dp, dq, False)
+        first = (dp.clone(), dq.clone())
+        ntp.ntp_edge_softmax_bwd(g, pd, qd, 0.2, a_in, a_out, dev_f32(Z2), dev_f32(dY2), m, m, m, dp, dq, True)
+        torch.cuda.synchronize()
+        r1 = oracle.edge_softmax_bwd(og, p, q, Z1, dY1, 0.2)
+        r2 = oracle.edge_softmax_bwd(og, p, q, Z2, dY2, 0.2)
+        s1 = _grad_scales(og, p, q, Z1, dY1, 0.2)
+        s2 = _grad_scales(og, p, q, Z2, dY2, 0.2)
+        tiny = np.finfo(np.float32).tiny
+        for got, a, b, sa, sb in ((dp, r1[0], r2[0], s1[0], s2[0]), (dq, r1[1], r2[1], s1[1], s2[1])):
+            err = np.abs(got.cpu().numpy().astype(np.float64) - (a + b)) / np.maximum(sa + sb, tiny)
+            assert err.max() <= TOL_SCORE_GRAD
+        # and the second call alone, subtracted back, is what a fresh call gives (to rounding)
+        dp2 = torch.empty_like(dp)
+        dq2 = torch.empty_like(dq)
+        ntp.ntp_edge_softmax_bwd(g, pd, qd, 0.2, a_in, a_out, dev_f32(Z2), dev_f32(dY2), m, m, m, dp2, dq2, False)
+        torch.cuda.synchronize()
+        assert torch.equal(first[0] + dp2, dp) and torch.equal(first[1] + dq2, dq)
+

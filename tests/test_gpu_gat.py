@@ -96,13 +96,13 @@ def test_attention_scores_argument_errors():
     ntp.ntp_attention_scores_fwd(z, a, a, v, v, 0, 8, 8)       # nothing to do
 
 
-def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=None):
+def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=None, extra_flags=0):
     import torch
     from paper_2412_20379_amd.gat import GatEpoch
     from gpu_util import dev_f32
     og = oracle.build_graph(n, src, dst, flags)
     kw = dict(chunk_edges=chunk_edges) if chunk_edges else {}
-    g = ntp.ntp_graph_build(n, src, dst, flags=flags, **kw)
+    g = ntp.ntp_graph_build(n, src, dst, flags=flags | extra_flags, **kw)
     rng = gen.stream_rng(seed, 3)
     X = rng.normal(size=(n, dims[0])).astype(np.float32)
     Ws = [gen.glorot_weight(dims[i], dims[i + 1], seed, i) for i in range(len(dims) - 1)]
@@ -173,3 +173,16 @@ def test_gat_epoch_configs():
     for cfg, scale, dims in ((1, 1, (64, 16, 7)), (2, 4, (128, 32, 40))):
         n, src, dst = gen.make_graph(cfg, seed=0, scale_down=scale)
         _gat_epoch(n, src, dst, oracle.GCN_FLAGS, dims, 2, 0.2, cfg, "config %d / %d" % (cfg, scale))
+
+
+def test_gat_epoch_with_edge_permutation():
+    n = 3000
+    src, dst = gen.directed_random_edges(n, 40000, 21, hub=5, hub_in=2600, hub_out=900)
+    _gat_epoch(n, src, dst, oracle.DIRECTED_GCN_FLAGS, (24, 16, 8), 3, 0.2, 4, "hub graph, edge permutation",
+               extra_flags=ntp.NTP_EDGE_PERM)
+    _gat_epoch(n, src, dst, oracle.DIRECTED_GCN_FLAGS, (24, 8), 2, 0.2, 6, "chunks of 700 edges, edge permutation",
+               chunk_edges=700, extra_flags=ntp.NTP_EDGE_PERM)
+    n, src, dst = gen.make_graph(2, seed=0, scale_down=4)
+    _gat_epoch(n, src, dst, oracle.GCN_FLAGS, (128, 32, 40), 2, 0.2, 2, "config 2 / 4, edge permutation",
+               extra_flags=ntp.NTP_EDGE_PERM)
+
