@@ -11,6 +11,11 @@ import torch
 from . import binding as ntp
 
 
+def padded_width(c: int) -> int:
+    """whole 128-byte lines of floats, or whole 16-byte vectors below one line"""
+    return -(-c // 32) * 32 if c >= 32 else -(-c // 4) * 4
+
+
 class GcnEpoch:
     """One forward + backward pass of an L-layer GCN on one GPU (no optimiser step).
 
@@ -26,7 +31,15 @@ class GcnEpoch:
     """
 
     def __init__(self, graph: ntp.Graph, n: int, dims, device="cuda:0", order="layerwise", chunked=False,
-                 overlap_dw=False):
+                 overlap_dw=False, pad_classes=True):
+        # A class count that is not a multiple of four floats makes every row of the logits (and of
+        # whatever is aggregated at that width) start off a 16-byte boundary.  The last transform
+        # then gets zero columns appended up to whole 128-byte lines (16-byte vectors below 32
+        # classes): logits and gradients carry zero padding columns that change no sum, and only
+        # the loss is told the real count.
+        self.classes = dims[-1]
+        if pad_classes and dims[-1] % 4:
+            dims = tuple(dims[:-1]) + (padded_width(dims[-1]),)
         self.g, self.n, self.dims, self.order, self.chunked = graph, n, tuple(dims), order, chunked
         # overlap_dw: in the layer-wise backward, dW of a layer runs on a second stream beside
         # dA and the backward aggregation that follows it (matrix cores beside the memory system)
@@ -45,14 +58,16 @@ class GcnEpoch:
         self.aggs = [None if self.transform_first[l] else torch.empty(n, dims[l], **f32) for l in range(L)] if lw else []
         self.tbuf = [torch.empty(n, dims[l + 1], **f32) if self.transform_first[l] else None for l in range(L)] if lw else []
         self.hid = [torch.empty(n, dims[l + 1], **f32) for l in range(L)]
-        self.dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
+        self.dW_buf = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
+        self.dW = self.dW_buf[:-1] + [self.dW_buf[-1][:, :self.classes]]      # views without the padding columns
+        self.w_last = torch.zeros(dims[-2], dims[-1], **f32) if dims[-1] != self.classes else None
         wmax = max(dims)
         self.tmp = [torch.empty(n, wmax, **f32) for _ in range(3 if overlap_dw else 2)]
         self.logits_buf = torch.empty(n, dims[-1], **f32) if order == "decoupled" else None
         ws = max(ntp.ntp_nn_bwd_workspace_bytes(n, dims[l], dims[l + 1]) for l in range(L))
         self.ws_bytes = ws
         self.ws = torch.empty(max(ws, 4), dtype=torch.uint8, device=device)
-        self.dlogits = torch.empty(n, dims[-1], **f32)
+        self.dlogits = torch.zeros(n, dims[-1], **f32)       # padding columns stay zero
         self.loss_buf = torch.zeros(1, **f32)
         self.loss_scratch = torch.empty(ntp.ntp_softmax_xent_scratch_bytes(n) // 4, **f32)
         self.copy_stream = torch.cuda.Stream(device=device) if chunked else None
@@ -95,16 +110,22 @@ class GcnEpoch:
         return self.tmp[i].view(-1)[: self.n * f].view(self.n, f)
 
     def _loss_grad(self, Z, labels):
-        c = self.dims[-1]
+        c, ld = self.classes, self.dims[-1]
         self._timed("softmax_xent %d" % c, ntp.ntp_softmax_xent, Z, labels, self.dlogits, self.loss_buf, self.loss_scratch,
-                    self.loss_scratch.numel() * 4, self.n, c, c, c, torch.cuda.current_stream())
+                    self.loss_scratch.numel() * 4, self.n, c, ld, ld, torch.cuda.current_stream())
         self.loss = self.loss_buf[0]
         return self.dlogits
 
     def run(self, X, weights, labels):
+        if self.w_last is not None:
+            self.w_last[:, :self.classes].copy_(weights[-1])
+            weights = list(weights[:-1]) + [self.w_last]
         if self.order in ("layerwise", "reordered", "auto"):
-            return self._layerwise(X, weights, labels)
-        return self._decoupled(X, weights, labels)
+            loss = self._layerwise(X, weights, labels)
+        else:
+            loss = self._decoupled(X, weights, labels)
+        self.logits = self.logits[:, :self.classes]
+        return loss
 
     def _other_view(self, t, f):
         """a scratch view of width f that does not share memory with tensor t"""
@@ -146,7 +167,7 @@ class GcnEpoch:
                 dT = self.tbuf[l]  # dT = A_hat^T dZ at the output width; then dW = H_in^T dT, dH_in = dT W^T
                 self._agg(ntp.NTP_BWD, dH, dT, d[l + 1])
                 dHin = self._view(0, d[l]) if l > 0 else None
-                self._nn_bwd(ins[l], Ws[l], self.hid[l], dT, dHin, self.dW[l], n, d[l], d[l + 1],
+                self._nn_bwd(ins[l], Ws[l], self.hid[l], dT, dHin, self.dW_buf[l], n, d[l], d[l + 1],
                              ntp.NTP_ACT_NONE, ntp.NTP_F32, self.ws, self.ws_bytes, st)
                 dH = dHin
             elif self.overlap_dw and l > 0:
@@ -156,7 +177,7 @@ class GcnEpoch:
                 ready = torch.cuda.Event()
                 ready.record(st)
                 self.dw_stream.wait_event(ready)
-                ntp.ntp_nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, None, self.dW[l], n, d[l], d[l + 1], act,
+                ntp.ntp_nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, None, self.dW_buf[l], n, d[l], d[l + 1], act,
                                ntp.NTP_F32, self.ws2, self.ws_bytes, self.dw_stream)
                 done = torch.cuda.Event()
                 done.record(self.dw_stream)
@@ -179,7 +200,7 @@ class GcnEpoch:
                 if pending is not None:
                     st.wait_event(pending)
                     pending = None
-                self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
+                self._nn_bwd(self.aggs[l], Ws[l], self.hid[l], dH, dA, self.dW_buf[l], n, d[l], d[l + 1], act,
                              ntp.NTP_F32, self.ws, self.ws_bytes, st)
                 if l > 0:
                     dH = self._other_view(dA, d[l])
@@ -218,7 +239,7 @@ class GcnEpoch:
             if l > 0:
                 # the two scratch views are free again except the one holding dH
                 dA = self._view(0 if dH.data_ptr() != self.tmp[0].data_ptr() else 1, d[l])
-            self._nn_bwd(ins[l], Ws[l], self.hid[l], dH, dA, self.dW[l], n, d[l], d[l + 1], act,
+            self._nn_bwd(ins[l], Ws[l], self.hid[l], dH, dA, self.dW_buf[l], n, d[l], d[l + 1], act,
                          ntp.NTP_F32, self.ws, self.ws_bytes, st)
             dH = dA
         return self.loss
