@@ -380,6 +380,7 @@ def main():
     if args.mode == "agg":
         widths = [int(w) for w in args.widths.split(",")] if args.widths else list(spec.agg_slices)
         res = []
+        scrub = None
         for f in widths:
             x0 = torch.from_numpy(gen.normal_features(n, f, args.seed)).to(dev)
             code, elem = ntp.NTP_F32, 4
@@ -404,12 +405,25 @@ def main():
                     evs.append((e0, e1))
                 torch.cuda.synchronize()
                 ms = np.array([a.elapsed_time(b) for a, b in evs])
+                # the repetitions above start with whatever the previous one left in the caches;
+                # one more call after 1 GiB of unrelated writes gives the cache-cold time
+                if scrub is None:
+                    scrub = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+                scrub.fill_(1.0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn(g, x, y, f, ld, ld, code, st)
+                e1.record()
+                torch.cuda.synchronize()
+                cold_ms = e0.elapsed_time(e1)
                 balg = agg_bytes(n, nnz, f, elem)
                 r = dict(width=f, row_stride=ld, direction=direction, dtype=args.agg_dtype, avg_ms=float(ms.mean()), min_ms=float(ms.min()),
+                         median_ms=float(np.median(ms)), cache_cold_ms=float(cold_ms),
                          geps=nnz * f / (ms.mean() * 1e-3) / 1e9, alg_gbs=balg / (ms.mean() * 1e-3) / 1e9,
                          frac_hbm=balg / (ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS)
-                log("agg %s f=%d %s: %.3f ms  %.0f GEPS  %.0f GB/s algorithmic (%.1f%% of 8 TB/s)"
-                    % (direction, f, args.agg_dtype, r["avg_ms"], r["geps"], r["alg_gbs"], 100 * r["frac_hbm"]))
+                log("agg %s f=%d %s: %.3f ms (median %.3f, min %.3f, cache-cold %.3f)  %.0f GEPS  %.0f GB/s algorithmic (%.1f%% of 8 TB/s)"
+                    % (direction, f, args.agg_dtype, r["avg_ms"], r["median_ms"], r["min_ms"], r["cache_cold_ms"], r["geps"], r["alg_gbs"],
+                       100 * r["frac_hbm"]))
                 res.append(r)
         print(json.dumps({"mode": "agg", "config": args.config, "n_vertices": n, "nnz": nnz,
                           "max_degree": info["max_degree"], "results": res}), flush=True)
