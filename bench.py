@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--chunk-edges", type=int, default=0, help="entries per chunk for --mode chunk (default nnz/8)")
     ap.add_argument("--widths", default="", help="comma-separated slice widths for --mode agg")
     ap.add_argument("--agg-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--parity-rows", type=int, default=2000,
+                    help="--mode gat: uniformly sampled destinations checked against the oracle (0: no check)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -331,6 +333,72 @@ def main():
         t_sg = timed(lambda: ntp.ntp_edge_softmax_bwd(g, p, q, 0.2, a_in, a_out, x, dy, f_sg, ld, ld, dp, dq, False, st))
         if f_sg != f:
             t_w = timed(lambda: ntp.ntp_aggregate_weighted(g, ntp.NTP_FWD, a_in, x, y, f_sg, ld, ld, ntp.NTP_F32, st))
+        # parity at this size on sampled vertices, each built by the oracle from the edge list:
+        # weights and dq of sampled destinations (uniform + the largest), dp of sampled sources
+        # (all their neighbours' rows are needed for that)
+        def gat_parity(tag):
+            import oracle as orc          # the cpu-side check is the only user of the oracle here
+            t0 = time.time()
+            rng = gen.stream_rng(args.seed, 123)
+            deg = np.bincount(src, minlength=n) + np.bincount(dst, minlength=n) + 1
+            rowptr = np.zeros(n + 1, dtype=np.int64)
+            np.cumsum(deg, out=rowptr[1:])
+            order = np.argsort(deg)
+            ph, qh = p.cpu().numpy(), q.cpu().numpy()
+            Zh, dYh = x[:, :f_sg].cpu().numpy(), dy[:, :f_sg].cpu().numpy()
+            a_h, dq_h, dp_h = a_in.cpu().numpy(), dq.cpu().numpy(), dp.cpu().numpy()
+
+            def abs_scale(m, rows, o):
+                sc = np.zeros(rows.size)
+                per_entry = np.zeros(int(m.rowptr[-1]))
+                for i, v in enumerate(rows):
+                    b, e = int(m.rowptr[i]), int(m.rowptr[i + 1])
+                    A = np.abs(Zh[m.colidx[b:e]]).astype(np.float64) @ np.abs(dYh[v]).astype(np.float64)
+                    a = o["alpha"][b:e]
+                    per_entry[b:e] = a * (A + float(a @ A))
+                    sc[i] = per_entry[b:e].sum()
+                return sc, per_entry
+
+            vs = np.unique(np.concatenate([rng.choice(n, size=min(n, args.parity_rows), replace=False), order[-50:]])).astype(np.int64)
+            mv = orc.rows_from_undirected_edges(n, src, dst, vs)
+            ov = orc.edge_softmax_bwd_rows(mv, vs, ph, qh, Zh, dYh, 0.2)
+            err_a = 0.0
+            for i, v in enumerate(vs):
+                got = a_h[rowptr[v]:rowptr[v + 1]].astype(np.float64)
+                ref = ov["alpha"][mv.rowptr[i]:mv.rowptr[i + 1]]
+                err_a = max(err_a, float((np.abs(got - ref) / ref).max()))
+            sc_q, _ = abs_scale(mv, vs, ov)
+            err_q = float((np.abs(dq_h[vs] - ov["dq"]) / np.maximum(sc_q, 1e-300)).max())
+            us = np.unique(np.concatenate([rng.choice(n, size=min(n, 100), replace=False), order[-2:]])).astype(np.int64)
+            mu = orc.rows_from_undirected_edges(n, src, dst, us)          # symmetric graph: a row lists the out-neighbours too
+            allv = np.unique(mu.colidx).astype(np.int64)
+            mn = orc.rows_from_undirected_edges(n, src, dst, allv)
+            on = orc.edge_softmax_bwd_rows(mn, allv, ph, qh, Zh, dYh, 0.2)
+            _, mag = abs_scale(mn, allv, on)
+            where = {int(v): i for i, v in enumerate(allv)}
+            err_p = 0.0
+            for j, u in enumerate(us):
+                tot = sc = 0.0
+                for v in mu.colidx[mu.rowptr[j]:mu.rowptr[j + 1]]:
+                    i = where[int(v)]
+                    b, e = int(mn.rowptr[i]), int(mn.rowptr[i + 1])
+                    k = b + int(np.searchsorted(mn.colidx[b:e], u))
+                    tot += on["ds"][k]
+                    sc += mag[k]
+                err_p = max(err_p, abs(float(dp_h[u]) - tot) / max(sc, 1e-300))
+            res = {"destinations": int(vs.size), "sources": int(us.size), "neighbour_rows_for_dp": int(allv.size),
+                   "alpha_max_rel_err": err_a, "dq_max_err_over_sum_of_magnitudes": err_q,
+                   "dp_max_err_over_sum_of_magnitudes": err_p, "seconds": time.time() - t0}
+            log("GAT parity (%s) on %d destinations, %d sources (%d neighbour rows): alpha %.1e, dq %.1e, dp %.1e  (%.0fs)"
+                % (tag, vs.size, us.size, allv.size, err_a, err_q, err_p, res["seconds"]))
+            assert err_a <= 1e-5 and err_q <= 1e-5 and err_p <= 1e-5, "GAT parity failed (%s)" % tag
+            return res
+
+        parity = None
+        if args.parity_rows > 0:
+            ntp.ntp_edge_softmax_bwd(g, p, q, 0.2, a_in, a_out, x, dy, f_sg, ld, ld, dp, dq, False, st)
+            torch.cuda.synchronize()
+            parity = {"two_dot_product_passes": gat_parity("two dot-product passes")}
         # a whole decoupled GAT epoch (Section 4.1): MLP to the class width, attention weights, two
         # weighted aggregation rounds, loss, and the exact backward pass
         from paper_2412_20379_amd.gat import GatEpoch
@@ -348,6 +416,10 @@ def main():
         gp = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | ntp.NTP_EDGE_PERM)
         ntp.ntp_edge_softmax(gp, p, q, 0.2, a_in, a_out, st)
         t_sg_perm = timed(lambda: ntp.ntp_edge_softmax_bwd(gp, p, q, 0.2, a_in, a_out, x, dy, f_sg, ld, ld, dp, dq, False, st))
+        if parity is not None:
+            ntp.ntp_edge_softmax_bwd(gp, p, q, 0.2, a_in, a_out, x, dy, f_sg, ld, ld, dp, dq, False, st)
+            torch.cuda.synchronize()
+            parity["with_edge_permutation"] = gat_parity("edge permutation")
         gep = GatEpoch(gp, n, nnz, dims, rounds=2)
         t_ep_perm = timed(lambda: gep.run(Xg, Wg, a_s, a_d, lab))
         del gep
@@ -366,7 +438,8 @@ def main():
                "edge_softmax_bwd_ms": t_sg, "edge_softmax_bwd_vs_two_aggregations": t_sg / (2 * t_w),
                "edge_softmax_bwd_gathered_gbs": 2 * nnz * f_sg * 4 / (t_sg * 1e-3) / 1e9, "edge_softmax_bwd_width": f_sg,
                "gat_epoch_ms": t_ep, "gat_epoch_dims": list(dims), "gat_epoch_rounds": 2,
-               "edge_softmax_bwd_with_edge_perm_ms": t_sg_perm, "gat_epoch_with_edge_perm_ms": t_ep_perm}
+               "edge_softmax_bwd_with_edge_perm_ms": t_sg_perm, "gat_epoch_with_edge_perm_ms": t_ep_perm,
+               "parity_sample": parity}
         log("edge softmax: %.3f ms both orders (%.0f GB/s algorithmic, %.1f%% of 8 TB/s), %.3f ms by destination only; "
             "weighted aggregation f=%d %.3f ms (stored weights %.3f ms); score gradient %.3f ms (%.2f x two aggregations)"
             % (t_att, out["edge_softmax_gbs"], 100 * out["edge_softmax_frac_hbm"], t_att_in, f, t_w, t_s, t_sg,

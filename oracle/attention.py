@@ -113,3 +113,40 @@ def edge_softmax_bwd(g: Graph, p, q, Z, dY, negative_slope: float = 0.2):
         np.add.at(dp, us, ds)
         np.add.at(sp, us, mag)
     return dp, dq, sp, sq
+
+
+def edge_softmax_bwd_rows(m: Sparse, rows, p, q, Z, dY, negative_slope: float = 0.2):
+    """The same quantities for selected destinations only, for graphs too large to walk whole:
+    `m` holds the in-edge lists of the destinations `rows` (row i of m = in-neighbours of rows[i],
+    self loop included; its weights are not used).  Per entry, in the order of m: alpha, dalpha,
+    ds; per row: t and dq.  Returns dict(alpha, dalpha, ds, t, dq, scale) with `scale` the per-row
+    sum of |alpha| (|dalpha| + |t|)."""
+    p = np.asarray(p, dtype=np.float64)
+    q = np.asarray(q, dtype=np.float64)
+    rows = np.asarray(rows, dtype=np.int64)
+    nnz = int(m.rowptr[-1])
+    alpha = np.zeros(nnz)
+    dalpha = np.zeros(nnz)
+    ds = np.zeros(nnz)
+    t = np.zeros(rows.size)
+    dq = np.zeros(rows.size)
+    scale = np.zeros(rows.size)
+    for i, v in enumerate(rows):
+        b, e = int(m.rowptr[i]), int(m.rowptr[i + 1])
+        if e == b:
+            continue
+        us = m.colidx[b:e]
+        s = leaky_relu(p[us] + q[v], negative_slope)
+        w = np.exp(s - s.max())
+        a = w / w.sum()
+        alpha[b:e] = a
+        if Z is None:
+            continue
+        da = np.asarray(Z[us], dtype=np.float64) @ np.asarray(dY[v], dtype=np.float64)
+        dalpha[b:e] = da
+        t[i] = float(np.dot(a, da))
+        de = a * (da - t[i])
+        ds[b:e] = de * np.where(p[us] + q[v] > 0, 1.0, negative_slope)
+        dq[i] = ds[b:e].sum()
+        scale[i] = (a * (np.abs(da) + abs(t[i]))).sum()
+    return dict(alpha=alpha, dalpha=dalpha, ds=ds, t=t, dq=dq, scale=scale)

@@ -298,3 +298,36 @@ def test_a12_attention_scores_bwd_is_the_adjoint():
     assert abs(np.sum(out * Zd) - (dp @ pd + dq @ qd)) <= 1e-12
     ad = rng.normal(size=7)
     assert abs(da_s @ ad - dp @ (Z @ ad)) <= 1e-12 and abs(da_d @ ad - dq @ (Z @ ad)) <= 1e-12
+
+
+def test_a13_row_restricted_score_gradient_matches_the_whole_graph_oracle():
+    """edge_softmax_bwd_rows on rows built one by one from the edge list gives, for those rows, what
+    the whole-graph functions (pinned above) give; dp of a vertex follows from the ds of its
+    out-edges found in its neighbours' rows"""
+    n = 400
+    src, dst = gen.erdos_renyi_edges(n, 2500, 8)
+    g = oracle.build_graph(n, src, dst)
+    rng = np.random.default_rng(2)
+    p, q = rng.normal(size=n), rng.normal(size=n)
+    Z, dY = rng.normal(size=(n, 6)), rng.normal(size=(n, 6))
+    a_in, _ = oracle.edge_softmax(g, p, q, 0.2)
+    dp, dq, _, sq = oracle.edge_softmax_bwd(g, p, q, Z, dY, 0.2)
+    rows = np.sort(rng.choice(n, size=60, replace=False))
+    m = oracle.rows_from_undirected_edges(n, src, dst, rows)
+    out = oracle.edge_softmax_bwd_rows(m, rows, p, q, Z, dY, 0.2)
+    for i, v in enumerate(rows):
+        b, e = g.csr.rowptr[v], g.csr.rowptr[v + 1]
+        assert np.array_equal(m.colidx[m.rowptr[i]:m.rowptr[i + 1]], g.csr.colidx[b:e])
+        np.testing.assert_allclose(out["alpha"][m.rowptr[i]:m.rowptr[i + 1]], a_in[b:e], rtol=1e-13)
+    np.testing.assert_allclose(out["dq"], dq[rows], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(out["scale"], sq[rows], rtol=1e-12)
+    # dp[u] for one vertex: every neighbour's row, the entry whose column is u
+    u = int(rows[0])
+    nb = g.csr.colidx[g.csr.rowptr[u]:g.csr.rowptr[u + 1]].astype(np.int64)       # symmetric graph: out-neighbours
+    mu = oracle.rows_from_undirected_edges(n, src, dst, nb)
+    ou = oracle.edge_softmax_bwd_rows(mu, nb, p, q, Z, dY, 0.2)
+    total = 0.0
+    for i in range(nb.size):
+        cols = mu.colidx[mu.rowptr[i]:mu.rowptr[i + 1]]
+        total += ou["ds"][mu.rowptr[i]:mu.rowptr[i + 1]][cols == u].sum()
+    assert abs(total - dp[u]) <= 1e-12 * max(1.0, abs(dp[u]))
