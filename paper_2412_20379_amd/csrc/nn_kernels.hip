@@ -464,14 +464,24 @@ constexpr int split_lds_bytes() {
     return 2 * (BK / 8) * 16 * (Pieces<TA>::n * (BM + 4) + Pieces<TB>::n * (BN + 4));
 }
 
-// One block per compute unit (the two LDS buffers take 100-126 KB for fp32 operands).  In
-// step s a wavefront multiplies the tile in buffer s%2 while it cuts tile s+1 (already in
-// registers) into pieces and writes it to the other buffer, and tile s+2 is on its way from
-// memory: matrix instructions, vector arithmetic, LDS and memory traffic of three tiles
-// overlap inside every wavefront, with one barrier per step.
+// Two schedules of the same step (fetch a tile to registers, cut it into pieces and write it
+// to LDS, multiply it):
+//   OCC >= 2 (the default for fp32 operands): one LDS buffer (50-63 KB), OCC blocks per compute
+//     unit.  A block stores tile s, multiplies it while tile s+1 is on its way from memory, and
+//     meets a barrier on either side of the store; what overlaps the cutting, the LDS traffic
+//     and the waiting of one block is the other block on the same compute unit.  Measured
+//     against the schedule below (169,343 rows): forward 128->256 0.132 -> 0.103 ms, 256->256
+//     0.202 -> 0.183 ms, dA 0.242 -> 0.190 ms, dW (with twice the row splits) 0.228 -> 0.208 ms.
+//   OCC == 1: two LDS buffers (100-126 KB for fp32 operands), one block per compute unit.  In
+//     step s a wavefront multiplies the tile in buffer s%2 while it cuts tile s+1 (already in
+//     registers) into pieces and writes it to the other buffer, and tile s+2 is on its way from
+//     memory: the three tiles overlap inside every wavefront, with one barrier per step.  Kept
+//     for bf16 operands with narrow outputs, where it measured faster (dW 256x40: 0.047 against
+//     0.074 ms).
 template <class TA, class TB, class TC, bool A_KCONTIG, bool B_KCONTIG, bool MASK_A, bool MASK_B,
-          int BM, int BN, int WM, int WN>
-__global__ void __launch_bounds__(NTHREADS) gemm_split_kernel(const GemmArgs g) {
+          int BM, int BN, int WM, int WN, int OCC = 1>
+__global__ void __launch_bounds__(NTHREADS, OCC) gemm_split_kernel(const GemmArgs g) {
+    constexpr bool ONEBUF = OCC > 1;      // one LDS buffer, OCC blocks per compute unit
     static_assert(WM * WN == 4, "four wavefronts per block");
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int NPA = Pieces<TA>::n, NPB = Pieces<TB>::n;
@@ -481,8 +491,9 @@ __global__ void __launch_bounds__(NTHREADS) gemm_split_kernel(const GemmArgs g) 
     extern __shared__ uint4 smem[];
     typedef uint4 (*TileA)[BK / 8][LDA_S];
     typedef uint4 (*TileB)[BK / 8][LDB_S];
+    // two buffers: [A0 | A1 | B0 | B1]; one buffer: [A0 | B0]
     const TileA As0 = reinterpret_cast<TileA>(smem), As1 = As0 + NPA;
-    const TileB Bs0 = reinterpret_cast<TileB>(As1 + NPA), Bs1 = Bs0 + NPB;
+    const TileB Bs0 = reinterpret_cast<TileB>(ONEBUF ? As1 : As1 + NPA), Bs1 = Bs0 + NPB;
     using LA = Loader<TA, A_KCONTIG, MASK_A, BM>;
     using LB = Loader<TB, B_KCONTIG, MASK_B, BN>;
 
@@ -549,7 +560,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_split_kernel(const GemmArgs g) 
 
     int64_t k0 = kbeg;
     const bool fast = LA::can_be_fast(A, mA, g.lda, g.Mdim) && LB::can_be_fast(B, mB, g.ldb, g.Ndim);
-    if (fast && kend - kbeg >= 2 * BK) {
+    if (!ONEBUF && fast && kend - kbeg >= 2 * BK) {
         // An even number of whole steps.  Every fetch is issued unconditionally (past the end
         // it re-reads a tile already taken, and what is stashed from it is never multiplied)
         // so that the number of loads in flight is known at compile time and a stash waits
@@ -598,16 +609,21 @@ __global__ void __launch_bounds__(NTHREADS) gemm_split_kernel(const GemmArgs g) 
     if (k0 < kend) {
         typename LA::Regs ra;
         typename LB::Regs rb;
-        LA::template fetch<false>(A, mA, g.lda, m0, k0, g.Mdim, kend, ra);
-        LB::template fetch<false>(B, mB, g.ldb, n0, k0, g.Ndim, kend, rb);
+        auto fetch1 = [&](int64_t k) {
+            if (ONEBUF && fast && k + BK <= kend) {
+                LA::template fetch<true>(A, mA, g.lda, m0, k, g.Mdim, kend, ra);
+                LB::template fetch<true>(B, mB, g.ldb, n0, k, g.Ndim, kend, rb);
+            } else {
+                LA::template fetch<false>(A, mA, g.lda, m0, k, g.Mdim, kend, ra);
+                LB::template fetch<false>(B, mB, g.ldb, n0, k, g.Ndim, kend, rb);
+            }
+        };
+        fetch1(k0);
         for (; k0 < kend; k0 += BK) {
             __syncthreads();
             stash(As0, Bs0, ra, rb);
             __syncthreads();
-            if (k0 + BK < kend) {
-                LA::template fetch<false>(A, mA, g.lda, m0, k0 + BK, g.Mdim, kend, ra);
-                LB::template fetch<false>(B, mB, g.ldb, n0, k0 + BK, g.Ndim, kend, rb);
-            }
+            if (k0 + BK < kend) fetch1(k0 + BK);
             multiply(As0, Bs0);
         }
     }
@@ -667,6 +683,27 @@ bool use_split_core() {
     return v;
 }
 
+// NTP_NN_SCHEDULE=1 / 2 forces the two-buffer / one-buffer schedule of the split core (for comparison)
+int split_schedule() {
+    static const int v = [] {
+        const char* e = getenv("NTP_NN_SCHEDULE");
+        return e ? atoi(e) : 0;
+    }();
+    return v;
+}
+
+// launch a split-core kernel with LDS bytes of dynamic LDS (more than the 64 KB a kernel may use
+// without asking, so the limit is raised once per kernel and device)
+template <auto kernel, int LDS>
+void launch_split(int64_t blocks, hipStream_t st, const GemmArgs& g) {
+    static bool allowed[64] = {};              // one table per kernel instantiation
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev >= 0 && dev < 64 && !allowed[dev])
+        allowed[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, LDS) == hipSuccess;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(NTHREADS), LDS, st, g);
+}
+
 template <class TA, class TB, class TC, bool AK, bool BKC, bool MA, bool MB, int BM, int BN, int WM, int WN>
 void launch_tiles(GemmArgs g, int n_splits, hipStream_t st) {
     g.tiles_m = (int)((g.Mdim + BM - 1) / BM);
@@ -676,23 +713,20 @@ void launch_tiles(GemmArgs g, int n_splits, hipStream_t st) {
     const int64_t n_major = g.share_splits ? n_splits : g.tiles_m;
     const int64_t n_minor = g.share_splits ? (int64_t)g.tiles_m * g.tiles_n : g.tiles_n;
     const int64_t blocks = (n_major + 7) / 8 * 8 * n_minor;
-    // The split core pays off when a block runs several whole contraction steps through its
-    // two-buffer pipeline and the output tile is wide enough to be compute bound; short
-    // contractions and narrow outputs (memory bound) stay on the plain core.  bf16 operands
-    // need one piece product only and always take the bf16 instructions.
+    // The split core pays off from two contraction steps per block on and for output tiles of at
+    // least 64 columns; shorter contractions and narrower outputs (memory bound) stay on the plain
+    // core.  bf16 operands need one piece product only and always take the bf16 instructions.
     const int64_t k_len = std::min<int64_t>(g.k_per_split, g.Kdim);
-    const bool split_pays = sizeof(TA) == 2 || (k_len >= 4 * BK && BN >= 128);
-    if (use_split_core() && split_pays) {
+    const bool split_pays = sizeof(TA) == 2 || (k_len >= 2 * BK && BN >= 64);
+    // fp32 operands: one LDS buffer and two blocks per compute unit; bf16 operands (one piece,
+    // small tiles in LDS either way): the same for wide outputs, the two-buffer schedule otherwise
+    const bool one_buffer = split_schedule() == 0 ? (sizeof(TA) == 4 || BN >= 128) : split_schedule() == 2;
+    if (use_split_core() && split_pays && one_buffer) {
+        constexpr int lds = split_lds_bytes<TA, TB, BM, BN>() / 2;
+        launch_split<gemm_split_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN, 2>, lds>(blocks, st, g);
+    } else if (use_split_core() && split_pays) {
         constexpr int lds = split_lds_bytes<TA, TB, BM, BN>();
-        auto kernel = gemm_split_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>;
-        static bool allowed[64] = {};          // per device: the kernel may use more than 64 KB of LDS
-        int dev = 0;
-        (void)hipGetDevice(&dev);
-        if (dev >= 0 && dev < 64 && !allowed[dev]) {
-            allowed[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
-        }
-        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(NTHREADS), lds, st, g);
+        launch_split<gemm_split_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN, 1>, lds>(blocks, st, g);
     } else
         hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, AK, BKC, MA, MB, BM, BN, WM, WN>), dim3((unsigned)blocks), dim3(NTHREADS), 0, st, g);
 }
@@ -719,11 +753,11 @@ int dw_splits(int64_t n, int64_t k, int64_t m) {
     const int64_t bm = m > 64 ? 128 : 256;
     const int64_t bn = m > 64 ? 128 : (m > 32 ? 64 : 32);
     const int64_t tiles = ((k + bm - 1) / bm) * ((m + bn - 1) / bn);
-    // one round of blocks: one block per compute unit (256 CUs) for the 128-wide tiles of the
-    // split core (its two LDS buffers fill a CU), two per CU for the narrow tiles of the fp32 core
-    const int64_t target = (m > 64 && use_split_core()) ? 256 : 512;
+    // one round of blocks with two blocks per compute unit (256 CUs), each block with at least
+    // sixteen contraction steps (measured on 29,121 x 602 x 128: more, shorter splits cost 8 %)
+    const int64_t target = 512;
     int64_t s = std::max<int64_t>(1, target / tiles);
-    const int64_t max_s = std::max<int64_t>(1, n / (BK * 8));
+    const int64_t max_s = std::max<int64_t>(1, n / (BK * 16));
     s = std::max<int64_t>(1, std::min(s, max_s));
     return (int)std::min<int64_t>(s, 1024);
 }
