@@ -16,7 +16,7 @@ def say(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, overlap_dw=False):
+def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, overlap_dw=False, dims=None):
     import torch
     from paper_2412_20379_amd.gcn import GcnEpoch
     from gpu_util import dev_f32
@@ -28,7 +28,7 @@ def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, over
     og = oracle.build_graph(n, src, dst, flags)
     kw = dict(device_budget_bytes=8 << 20, chunk_edges=200_000) if chunked else {}
     g = ntp.ntp_graph_build(n, src, dst, flags=flags | (ntp.NTP_SCATTER_BWD if scatter else 0), **kw)
-    dims = spec.layers
+    dims = dims or spec.layers
     X = gen.make_features(cfg, dims[0], seed=0, scale_down=scale)
     Ws = [gen.glorot_weight(dims[i], dims[i + 1], 0, i) for i in range(len(dims) - 1)]
     labels = gen.uniform_labels(n, dims[-1], 0)
@@ -104,6 +104,14 @@ def test_epoch_config2_dw_on_a_second_stream(order):
     """dW of a layer issued beside dA and the backward aggregation: same gradients"""
     _run(2, order, overlap_dw=True)
     _run(1, order, overlap_dw=True, directed=True)
+
+
+def test_epoch_class_count_padded_to_whole_lines():
+    """41 classes: the harness appends zero columns to the last transform up to 64 and tells only
+    the loss the real count; logits and gradients are those of the 41-class model"""
+    for order in ("layerwise", "decoupled", "auto"):
+        _run(1, order, dims=(1433, 32, 41))
+    _run(1, "layerwise", directed=True, dims=(1433, 48, 35))
 
 
 def test_epoch_auto_order_mixed_widths():
