@@ -132,7 +132,7 @@ def main():
         out.update(nnz=nnz, max_degree=info["max_degree"], n_chunks=info["n_chunks"])
         log("cold graph built in %.1fs: nnz=%d chunks=%d" % (out["build_cold_s"], nnz, info["n_chunks"]))
         ch = ntp.ntp_graph_chunks(gc)
-        b_pcie = int(((ch["entry_end"] - ch["entry_begin"]) * 8 + (ch["row_end"] - ch["row_begin"]) * 12).sum())
+        b_pcie = ntp.ntp_graph_stream_bytes(gc)
         out["t_cold_ms"] = timeit(lambda: ntp.ntp_chunked_aggregate(gc, ntp.NTP_FWD, x, y, f, f, f, ntp.NTP_F32, cs, xs), 2)
         out["cold_pcie_bytes"] = b_pcie
         out["cold_pcie_gbs"] = b_pcie / (out["t_cold_ms"] * 1e-3) / 1e9
@@ -253,7 +253,7 @@ def main():
         g_half = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=int(total_bytes * 0.62), chunk_edges=ce)
         chh = ntp.ntp_graph_chunks(g_half)
         streamed = ~chh["resident"].astype(bool)
-        b_pcie_half = int(((chh["entry_end"] - chh["entry_begin"])[streamed] * 8 + (chh["row_end"] - chh["row_begin"])[streamed] * 12).sum())
+        b_pcie_half = ntp.ntp_graph_stream_bytes(g_half)
         out["t_warm_ms"] = timeit(g_half, True)
         assert torch.equal(y, ref)
         out["warm_resident_chunks"] = "%d of %d" % (int(chh["resident"].sum()), len(streamed))
@@ -262,7 +262,7 @@ def main():
         g_half.close()
         g_cold = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | ntp.NTP_FORCE_STREAM, chunk_edges=ce)
         chc = ntp.ntp_graph_chunks(g_cold)
-        b_pcie = int(((chc["entry_end"] - chc["entry_begin"]) * 8 + (chc["row_end"] - chc["row_begin"]) * 12).sum())
+        b_pcie = ntp.ntp_graph_stream_bytes(g_cold)
         out["t_cold_ms"] = timeit(g_cold, True)
         assert torch.equal(y, ref)
         out["cold_pcie_bytes"] = b_pcie

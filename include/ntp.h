@@ -135,6 +135,13 @@ int ntp_graph_chunks(const ntp_graph_t* g, int which, int32_t* n_chunks,
                      int64_t* row_begin, int64_t* row_end,
                      int64_t* entry_begin, int64_t* entry_end, int32_t* resident);
 
+/* Bytes one chunked pass over the form `which` copies from host to device: for every chunk that
+ * is not resident its row pointers and row lists plus 4 bytes per entry (column ids), and 4 more
+ * (weights) only when the graph was built with caller weights.  Without caller weights the weights
+ * of a streamed chunk are rebuilt on the device from the degrees (bit-identical to the stored
+ * ones), which halves the host-link traffic of the chunk schedule. */
+int ntp_graph_stream_bytes(const ntp_graph_t* g, int which, int64_t* bytes);
+
 /* Device bytes held by the handle (resident topology, staging buffers, scratch). */
 int ntp_graph_device_bytes(const ntp_graph_t* g, int64_t* bytes);
 

@@ -20,7 +20,7 @@ NTP_FWD, NTP_BWD = 0, 1
 NTP_ACT_NONE, NTP_ACT_RELU = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_export_perm", "ntp_graph_chunks",
+    "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_export_perm", "ntp_graph_chunks", "ntp_graph_stream_bytes",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
     "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_edge_softmax_bwd", "ntp_aggregate_weighted",
     "ntp_attention_scores_fwd", "ntp_attention_scores_bwd", "ntp_attention_scores_bwd_scratch_bytes",
@@ -57,6 +57,7 @@ def lib():
     L.ntp_graph_info.argtypes = [vp, vp, vp, vp, vp, vp]
     L.ntp_graph_export.argtypes = [vp, ctypes.c_int, vp, vp, vp]
     L.ntp_graph_export_perm.argtypes = [vp, vp]
+    L.ntp_graph_stream_bytes.argtypes = [vp, ctypes.c_int, vp]
     L.ntp_graph_chunks.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp]
     L.ntp_graph_device_bytes.argtypes = [vp, vp]
     L.ntp_aggregate_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
@@ -171,6 +172,13 @@ def ntp_graph_export(g: Graph, which=NTP_CSR):
     val = np.empty(nnz, dtype=np.float32)
     _check(lib().ntp_graph_export(g.handle, which, None, _ptr(colidx), _ptr(val)))
     return rowptr, colidx, val
+
+
+def ntp_graph_stream_bytes(g: Graph, which=NTP_CSR) -> int:
+    """host-to-device bytes of one chunked pass over the form (0 when every chunk is resident)"""
+    b = ctypes.c_int64()
+    _check(lib().ntp_graph_stream_bytes(g.handle, int(which), ctypes.byref(b)))
+    return int(b.value)
 
 
 def ntp_graph_export_perm(g: Graph) -> np.ndarray:

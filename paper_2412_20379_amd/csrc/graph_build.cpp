@@ -247,6 +247,14 @@ int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32
     out->n = n;
     out->symmetric = sym;
     out->has_csc = sym || want_csc;
+    // weights that follow from the structure alone need not travel with a streamed chunk
+    out->val_mode = edge_weight ? VAL_STORED : (norm ? VAL_GCN : VAL_ONES);
+    if (out->val_mode == VAL_GCN) {
+        const std::vector<int64_t>& d_out = known_symmetric ? len : dout;
+        out->din.resize((size_t)n);
+        out->dout.resize((size_t)n);
+        for (int64_t v = 0; v < n; ++v) { out->din[v] = (int32_t)len[v]; out->dout[v] = (int32_t)d_out[v]; }
+    }
     return NTP_OK;
 }
 

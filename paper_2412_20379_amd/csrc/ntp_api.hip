@@ -47,9 +47,13 @@ struct ntp_graph {
     float* att_stats = nullptr;    // [4 n]: per-destination (q, maximum, 1 / sum, 0) of the last ntp_edge_softmax
     float* att_bwd = nullptr;      // scratch of ntp_edge_softmax_bwd: per-destination (t, q), per-segment partial sums, per-edge dalpha
     std::vector<int32_t> h_perm;   // NTP_EDGE_PERM: by-source entry -> by-destination entry
+    int32_t* d_din = nullptr;      // by-destination / by-source row lengths on the device: weights of streamed
+    int32_t* d_dout = nullptr;     // chunks are rebuilt from them (VAL_GCN graphs with streamed chunks only)
     int32_t* d_perm = nullptr;
     int64_t device_bytes = 0;
 
+    // streamed chunks carry column ids only; their weights are rebuilt after the copy
+    bool streams_without_weights() const { return g.val_mode == VAL_ONES || (g.val_mode == VAL_GCN && d_din != nullptr); }
     // the by-source product runs as a scatter over the by-destination form
     bool scatter_bwd() const { return !g.has_csc; }
     Form& f(int which) { return form[(which == NTP_CSC && !g.symmetric && g.has_csc) ? 1 : 0]; }
@@ -72,13 +76,14 @@ void free_entries(HostSparse& m, bool pinned) {
     m.val = nullptr;
 }
 
-int upload_chunk(const HostSparse& m, Chunk& c, char* dst, hipStream_t st, bool async, const char* meta_src) {
+// with_val = false: the weights are rebuilt on the device after the copy (launch_rebuild_weights)
+int upload_chunk(const HostSparse& m, Chunk& c, char* dst, hipStream_t st, bool async, const char* meta_src, bool with_val = true) {
     const size_t ne = (size_t)(c.e_end - c.e_begin);
     if (async) {
         HIP_TRY(hipMemcpyAsync(dst, meta_src, c.meta.size(), hipMemcpyHostToDevice, st));
         if (ne) {
             HIP_TRY(hipMemcpyAsync(dst + c.img_off_colidx, m.colidx + c.e_begin, ne * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(hipMemcpyAsync(dst + c.img_off_val, m.val + c.e_begin, ne * 4, hipMemcpyHostToDevice, st));
+            if (with_val) HIP_TRY(hipMemcpyAsync(dst + c.img_off_val, m.val + c.e_begin, ne * 4, hipMemcpyHostToDevice, st));
         }
     } else {
         HIP_TRY(hipMemcpy(dst, meta_src, c.meta.size(), hipMemcpyHostToDevice));
@@ -220,6 +225,8 @@ void destroy(ntp_graph* G) {
     if (G->att_stats) (void)hipFree(G->att_stats);
     if (G->att_bwd) (void)hipFree(G->att_bwd);
     if (G->d_perm) (void)hipFree(G->d_perm);
+    if (G->d_din) (void)hipFree(G->d_din);
+    if (G->d_dout && G->d_dout != G->d_din) (void)hipFree(G->d_dout);
     if (G->pinned_meta) (void)hipHostFree(G->pinned_meta);
     free_entries(G->g.csr, G->pinned_entries);
     free_entries(G->g.csc, G->pinned_entries);
@@ -353,6 +360,22 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
                         off += c.meta.size();
                     }
         }
+        bool any_streamed = false;
+        for (int k = 0; k < n_forms; ++k) any_streamed = any_streamed || !G->form[k].all_resident;
+        if (any_streamed && G->g.val_mode == VAL_GCN && n > 0) {
+            // degrees on the device: a streamed chunk then travels without its weights
+            const size_t bytes = (size_t)n * 4;
+            const bool same = G->g.din == G->g.dout;
+            for (int k = 0; k < (same ? 1 : 2); ++k) {
+                void* p = nullptr;
+                if (hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes for the degrees failed", bytes); return NTP_ENOMEM; }
+                (k == 0 ? G->d_din : G->d_dout) = (int32_t*)p;
+                G->device_bytes += (int64_t)bytes;
+                const std::vector<int32_t>& src_deg = k == 0 ? G->g.din : G->g.dout;
+                if (hipMemcpy(p, src_deg.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) { (void)hipGetLastError(); set_error("upload of the degrees failed"); return NTP_EHIP; }
+            }
+            if (same) G->d_dout = G->d_din;
+        }
         if (!G->h_perm.empty()) {
             void* p = nullptr;
             const size_t bytes = G->h_perm.size() * 4;
@@ -427,6 +450,19 @@ int ntp_graph_chunks(const ntp_graph_t* g, int which, int32_t* n_chunks, int64_t
         if (entry_end) entry_end[i] = chunks[i].e_end;
         if (resident) resident[i] = chunks[i].d_image ? 1 : 0;
     }
+    return NTP_OK;
+}
+
+int ntp_graph_stream_bytes(const ntp_graph_t* g, int which, int64_t* bytes) {
+    if (!g || !bytes) { set_error("NULL argument"); return NTP_EINVAL; }
+    if (which != NTP_CSR && which != NTP_CSC) { set_error("which must be NTP_CSR or NTP_CSC"); return NTP_EINVAL; }
+    const Form& F = (which == NTP_CSC && g->scatter_bwd()) ? g->form[0] : g->f(which);
+    const int64_t per_entry = g->streams_without_weights() ? 4 : 8;
+    int64_t total = 0;
+    if (!g->host_only)
+        for (const Chunk& c : F.plan.chunks)
+            if (!c.d_image) total += (int64_t)c.meta.size() + (c.e_end - c.e_begin) * per_entry;
+    *bytes = total;
     return NTP_OK;
 }
 
@@ -512,10 +548,20 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
         g->next_stage ^= 1;
         // the buffer may still be read by the kernels of the chunk that used it last
         if (g->stage_used[b]) HIP_TRY(hipStreamWaitEvent(xs, g->ev_free[b], 0));
-        rc = upload_chunk(*F.m, c, g->stage[b], xs, true, c.h_meta_pinned);
+        const bool rebuild = g->streams_without_weights();
+        rc = upload_chunk(*F.m, c, g->stage[b], xs, true, c.h_meta_pinned, !rebuild);
         if (rc != NTP_OK) return rc;
         HIP_TRY(hipEventRecord(g->ev_ready[b], xs));
         HIP_TRY(hipStreamWaitEvent(cs, g->ev_ready[b], 0));
+        if (rebuild) {
+            const bool by_source = &F == &g->form[1];          // rows are sources: row degree = dout, column degree = din
+            char* img = g->stage[b];
+            rc = launch_rebuild_weights(reinterpret_cast<const int64_t*>(img + c.off_rowptr), c.row_begin, c.row_end - c.row_begin,
+                                        c.e_begin, c.e_end - c.e_begin, reinterpret_cast<const int32_t*>(img + c.img_off_colidx),
+                                        reinterpret_cast<float*>(img + c.img_off_val), by_source ? g->d_dout : g->d_din,
+                                        by_source ? g->d_din : g->d_dout, g->g.val_mode, cs);
+            if (rc != NTP_OK) return rc;
+        }
         rc = run_all(c, g->stage[b]);
         if (rc != NTP_OK) return rc;
         HIP_TRY(hipEventRecord(g->ev_free[b], cs));

@@ -45,7 +45,15 @@ struct BuiltGraph {
     HostSparse csc;    // by source (empty when symmetric: use csr)
     bool symmetric = false;
     bool has_csc = true;    // false: built with NTP_SCATTER_BWD and not symmetric (backward = scatter over csr)
+    // How the stored weights follow from the structure, when they do (no caller weights):
+    //   VAL_STORED: only the stored arrays know them
+    //   VAL_GCN:    val(u -> v) = (float)(1 / sqrt((double)din[v] * (double)dout[u])), the formula they were built with
+    //   VAL_ONES:   every weight is 1
+    // din / dout: by-destination and by-source row lengths (empty unless VAL_GCN).
+    int val_mode = 0;
+    std::vector<int32_t> din, dout;
 };
+enum { VAL_STORED = 0, VAL_GCN = 1, VAL_ONES = 2 };
 
 // allocator hooks so that graph_build.cpp stays free of HIP: returns nullptr on failure
 struct EntryAllocator {
@@ -225,6 +233,12 @@ int launch_attention_scores_fwd(const float* Z, const float* a_src, const float*
 int launch_attention_scores_bwd(const float* Z, const float* a_src, const float* a_dst, const float* dp, const float* dq,
                                 float* dZ, float* da_src, float* da_dst, int64_t n, int64_t m, int64_t ldz, int64_t lddz,
                                 float* scratch, void* stream);
+
+// val[e] of a chunk's entries from the structure (VAL_GCN / VAL_ONES): rowptr is the chunk's slice
+// (global entry offsets), colidx / val its entry arrays, deg_row / deg_col indexed by vertex id
+int launch_rebuild_weights(const int64_t* rowptr, int64_t row_base, int64_t n_rows, int64_t e_base, int64_t n_entries,
+                           const int32_t* colidx, float* val, const int32_t* deg_row, const int32_t* deg_col, int mode,
+                           void* stream);
 
 // a[i] += b[i]
 int launch_vec_add(float* a, const float* b, int64_t n, void* stream);
