@@ -729,6 +729,13 @@ def main():
             best = dt if best is None else min(best, dt)
         cpu_baseline = dict(value=done / best / 1e9, unit="GEPS", cores=oracle.num_threads(), kind="oracle",
                             sample=sample + ", fp64, best of 3 (%.3fs)" % best)
+        if args.config <= 2:        # small enough to time on one core as well
+            all_cores = oracle.num_threads()
+            oracle.set_num_threads(1)
+            t1 = time.perf_counter()
+            oracle.aggregate(m, xo)
+            cpu_baseline["single_core_value"] = done / (time.perf_counter() - t1) / 1e9
+            oracle.set_num_threads(all_cores)
         log("oracle baseline: %.2f GEPS on %d threads (%.1fs incl. graph build)" % (cpu_baseline["value"], cpu_baseline["cores"], time.time() - t0))
 
     out = {

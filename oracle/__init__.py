@@ -22,7 +22,7 @@ from .graph import (  # noqa: F401
 )
 from .aggregate import (  # noqa: F401
     aggregate, aggregate_fwd, aggregate_bwd, aggregate_bwd_scatter,
-    chunked_aggregate, round_bf16, num_threads, build_native,
+    chunked_aggregate, round_bf16, num_threads, set_num_threads, build_native,
 )
 from .sampled import rows_from_undirected_edges  # noqa: F401
 from .attention import edge_softmax, edge_softmax_bwd, edge_softmax_bwd_rows, leaky_relu, weighted  # noqa: F401

@@ -74,3 +74,14 @@ int oracle_num_threads(void)
     return 1;
 #endif
 }
+
+/* Threads the row loop uses from now on (timing on one core beside all cores; the result does not
+ * depend on it: every row is summed sequentially). */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

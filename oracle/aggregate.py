@@ -40,12 +40,19 @@ def _load():
         lib.oracle_aggregate_transposed_scatter.argtypes = [i64, i64, p, p, p, p, i64, i64, p, i64]
         lib.oracle_aggregate_transposed_scatter.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        lib.oracle_set_num_threads.restype = None
         _lib = lib
     return _lib
 
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """threads of the row loop from now on (results do not depend on it)"""
+    _load().oracle_set_num_threads(int(n))
 
 
 def _ptr(a):
