@@ -186,3 +186,47 @@ def test_gat_epoch_with_edge_permutation():
     _gat_epoch(n, src, dst, oracle.GCN_FLAGS, (128, 32, 40), 2, 0.2, 2, "config 2 / 4, edge permutation",
                extra_flags=ntp.NTP_EDGE_PERM)
 
+
+
+def test_gat_epoch_captured_in_a_hip_graph_replays_identically():
+    """every library call of the GAT epoch is capturable once its scratch exists (no allocation
+    after the first call, fill kernels instead of memset nodes): replays with eager work between
+    them give the bits of the eager run, with and without the edge permutation"""
+    import torch
+    from paper_2412_20379_amd.gat import GatEpoch
+    from gpu_util import dev_f32
+    n = 3000
+    src, dst = gen.directed_random_edges(n, 40000, 21, hub=5, hub_in=2600, hub_out=900)
+    dims = (24, 16, 7)
+    rng = gen.stream_rng(8, 3)
+    X = dev_f32(rng.normal(size=(n, dims[0])))
+    Ws = [dev_f32(gen.glorot_weight(dims[i], dims[i + 1], 8, i)) for i in range(2)]
+    a_s, a_d = dev_f32(rng.normal(size=dims[-1])), dev_f32(rng.normal(size=dims[-1]))
+    labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], 8).astype(np.int64)).to("cuda:0")
+    for extra in (0, ntp.NTP_EDGE_PERM):
+        g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS | extra)
+        nnz = ntp.ntp_graph_info(g)["nnz"]
+        ep = GatEpoch(g, n, nnz, dims, rounds=2)
+        ep.run(X, Ws, a_s, a_d, labels)                 # scratch is allocated here
+        torch.cuda.synchronize()
+        want = [float(ep.loss)] + [t.clone() for t in (ep.dW[0], ep.dW[1], ep.da_src, ep.da_dst)]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ep.run(X, Ws, a_s, a_d, labels)
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ep.run(X, Ws, a_s, a_d, labels)
+        for r in range(3):
+            for t in (ep.dW_buf[0], ep.dW_buf[1], ep.da_buf, ep.dp, ep.dq):
+                t.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert float(ep.loss) == want[0], "replay %d" % r
+            for a, b in zip((ep.dW[0], ep.dW[1], ep.da_src, ep.da_dst), want[1:]):
+                assert torch.equal(a, b), "replay %d" % r
+            _ = float((X * 2).sum())                    # eager work between the replays
+        del graph, ep
+        g.close()
