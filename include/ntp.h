@@ -202,15 +202,15 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
  *     e(u -> v)     = LeakyReLU(p[u] + q[v])              (negative_slope for e < 0)
  *     alpha(u -> v) = exp(e(u -> v)) / sum over the in-edges u' -> v of exp(e(u' -> v))
  * p[u] = a_src . (W h_u) and q[v] = a_dst . (W h_v) are the two halves of a^T [W h_u || W h_v]:
- * contiguous device fp32 arrays of n_vertices, e.g. the outputs of two ntp_nn_fwd calls with one
- * output column each (Z a_src and Z a_dst).
+ * contiguous device fp32 arrays of n_vertices (the outputs of ntp_attention_scores_fwd).
  * alpha_in  [nnz] device fp32: the weights in the entry order of the by-destination form
  *           (ntp_graph_export(NTP_CSR)): what ntp_aggregate_weighted(NTP_FWD) takes.
  * alpha_out [nnz] device fp32, nullable: the same numbers (bit for bit) in the entry order of
  *           the by-source form: what ntp_aggregate_weighted(NTP_BWD) takes.
  * Needs every chunk of the topology device-resident (NTP_EBUDGET otherwise); alpha_out is not
- * available for graphs built with NTP_SCATTER_BWD (NTP_EUNSUPPORTED).  Deterministic.  The handle keeps 16 bytes per vertex
- * of scratch from the first call on; calls on one handle must not overlap.
+ * available for graphs built with NTP_SCATTER_BWD (NTP_EUNSUPPORTED).  Deterministic.  The
+ * handle keeps 16 bytes per vertex of scratch from the first call on; calls on one handle must
+ * not overlap.
  */
 int ntp_edge_softmax(ntp_graph_t* g, const float* p, const float* q, float negative_slope,
                      float* alpha_in, float* alpha_out, void* stream);
