@@ -237,3 +237,13 @@ def test_inputs_are_reproducible():
     n, s, d = gen.make_graph(3, seed=0, scale_down=64)
     deg = np.bincount(np.concatenate([s, d]), minlength=n)
     assert deg.max() > 50 * deg.mean()                              # power-law hubs
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """the benchmark is a one-GPU program: asking for more ends with a message, not a run"""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
