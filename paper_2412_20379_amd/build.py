@@ -13,7 +13,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libntp.so")
 
 SOURCES = ["graph_build.cpp", "plan.cpp", "ntp_api.hip", "agg_kernels.hip", "scatter_kernels.hip", "chunk_kernels.hip", "attention_kernels.hip", "attention_scores_kernels.hip", "loss_kernels.hip", "nn_kernels.hip"]
-HEADERS = [os.path.join(CSRC, "ntp_internal.h"), os.path.join(ROOT, "include", "ntp.h")]
+HEADERS = [os.path.join(CSRC, "ntp_internal.h"), os.path.join(CSRC, "lane_util.h"), os.path.join(ROOT, "include", "ntp.h")]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
           "-ffp-contract=off", "-Wall", "-Wno-unused-function"]

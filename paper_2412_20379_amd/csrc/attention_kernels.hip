@@ -15,15 +15,13 @@
 
 #include <cmath>
 
+#include "lane_util.h"
 #include "ntp_internal.h"
 
 namespace ntp {
 
 namespace {
 
-__device__ __forceinline__ float bperm_f(int src_lane, float v) {
-    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
-}
 __device__ __forceinline__ float lrelu(float x, float slope) { return x > 0.f ? x : slope * x; }
 
 template <int L> __device__ __forceinline__ float group_max(float v, int lane) {

@@ -13,6 +13,7 @@
 
 #include <algorithm>
 
+#include "lane_util.h"
 #include "ntp_internal.h"
 
 namespace ntp {
@@ -22,9 +23,6 @@ namespace {
 constexpr int MAXC = 4;            // column slots per thread in the backward kernel: widths up to 4 * 256
 constexpr int MAX_BLOCKS = 512;    // partial column sums kept per call
 
-__device__ __forceinline__ float bperm_f(int src_lane, float v) {
-    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
-}
 
 template <int L>
 __global__ void __launch_bounds__(256) scores_fwd_kernel(const float* __restrict__ Z, const float* __restrict__ a_src,

@@ -9,15 +9,12 @@
 
 #include <cmath>
 
+#include "lane_util.h"
 #include "ntp_internal.h"
 
 namespace ntp {
 
 namespace {
-
-__device__ __forceinline__ float bperm_f(int src_lane, float v) {
-    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
-}
 
 template <int L>
 __global__ void __launch_bounds__(256) xent_rows_kernel(const float* __restrict__ Z, const int64_t* __restrict__ labels,

@@ -14,23 +14,12 @@
 
 #include <algorithm>
 
+#include "lane_util.h"
 #include "ntp_internal.h"
 
 namespace ntp {
 
 namespace {
-
-__device__ __forceinline__ int bperm_i(int src_lane, int v) {
-    return __builtin_amdgcn_ds_bpermute(src_lane << 2, v);
-}
-__device__ __forceinline__ float bperm_f(int src_lane, float v) {
-    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
-}
-__device__ __forceinline__ int64_t uniform64(int64_t v) {
-    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v & 0xffffffff));
-    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((uint64_t)v >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
 
 // L lanes per feature row, lane l owns columns l, l + L, ... (NACC of them) of the pass
 // blockIdx.y, so one atomic instruction of a lane group covers L consecutive floats of
