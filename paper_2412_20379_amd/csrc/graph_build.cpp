@@ -142,7 +142,10 @@ int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32
     R.n = n;
     R.nnz = prefix(len, R.rowptr);
     R.colidx = (int32_t*)alloc.alloc(std::max<size_t>(4, (size_t)R.nnz * 4), alloc.ctx);
-    R.val = (float*)alloc.alloc(std::max<size_t>(4, (size_t)R.nnz * 4), alloc.ctx);
+    // without caller weights the values follow from the structure and are rebuilt on the device for
+    // streamed chunks: they need not sit in pinned memory
+    auto alloc_val = edge_weight ? alloc.alloc : alloc.alloc_val;
+    R.val = (float*)alloc_val(std::max<size_t>(4, (size_t)R.nnz * 4), alloc.ctx);
     if (!R.colidx || !R.val) { set_error("out of host memory for %lld entries", (long long)R.nnz); return NTP_ENOMEM; }
 
     // ---- pass 3: write the final rows; the self loop goes after every entry with id <= v
@@ -195,7 +198,7 @@ int build_host_graph(int64_t n, int64_t n_edges, const int32_t* src, const int32
         C.n = n;
         C.nnz = prefix(ccnt, C.rowptr);
         C.colidx = (int32_t*)alloc.alloc(std::max<size_t>(4, (size_t)C.nnz * 4), alloc.ctx);
-        C.val = (float*)alloc.alloc(std::max<size_t>(4, (size_t)C.nnz * 4), alloc.ctx);
+        C.val = (float*)alloc_val(std::max<size_t>(4, (size_t)C.nnz * 4), alloc.ctx);
         if (!C.colidx || !C.val) { set_error("out of host memory for %lld entries", (long long)C.nnz); return NTP_ENOMEM; }
         std::vector<int64_t> fill(C.rowptr.begin(), C.rowptr.end() - 1);
         parallel_for_threads(T, [&](int t, int nt) {

@@ -33,6 +33,7 @@ struct ntp_graph {
     Form form[2];                  // NTP_CSR, NTP_CSC (unused when symmetric)
     bool host_only = false;
     bool pinned_entries = false;
+    bool val_pinned = false;       // the weights are in pinned memory too (caller weights on a graph that may stream)
     // staging for streamed chunks
     char* stage[2] = {nullptr, nullptr};
     size_t stage_bytes = 0;
@@ -69,9 +70,10 @@ void* alloc_pinned(size_t bytes, void*) {
     return p;
 }
 
-void free_entries(HostSparse& m, bool pinned) {
-    if (pinned) { if (m.colidx) (void)hipHostFree(m.colidx); if (m.val) (void)hipHostFree(m.val); }
-    else { free(m.colidx); free(m.val); }
+// colidx lives in pinned memory when chunks may be streamed; val only if it has to travel too
+void free_entries(HostSparse& m, bool pinned, bool val_pinned) {
+    if (m.colidx) { if (pinned) (void)hipHostFree(m.colidx); else free(m.colidx); }
+    if (m.val) { if (val_pinned) (void)hipHostFree(m.val); else free(m.val); }
     m.colidx = nullptr;
     m.val = nullptr;
 }
@@ -228,8 +230,8 @@ void destroy(ntp_graph* G) {
     if (G->d_din) (void)hipFree(G->d_din);
     if (G->d_dout && G->d_dout != G->d_din) (void)hipFree(G->d_dout);
     if (G->pinned_meta) (void)hipHostFree(G->pinned_meta);
-    free_entries(G->g.csr, G->pinned_entries);
-    free_entries(G->g.csc, G->pinned_entries);
+    free_entries(G->g.csr, G->pinned_entries, G->val_pinned);
+    free_entries(G->g.csc, G->pinned_entries, G->val_pinned);
     delete G;
 }
 
@@ -259,11 +261,12 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
     const bool force_stream = flags & NTP_FORCE_STREAM;
     // entries go to pinned memory whenever chunks may have to be streamed
     G->pinned_entries = !G->host_only && (budget > 0 || force_stream);
-    EntryAllocator alloc{G->pinned_entries ? alloc_pinned : alloc_plain, nullptr};
+    G->val_pinned = G->pinned_entries && edge_weight != nullptr;
+    EntryAllocator alloc{G->pinned_entries ? alloc_pinned : alloc_plain, nullptr, alloc_plain};
 
     int rc = build_host_graph(n, n_edges, src, dst, edge_weight, flags, alloc, &G->g);
     if (rc != NTP_OK) { return rc; }
-    if (G->g.symmetric && G->g.csc.colidx) { free_entries(G->g.csc, G->pinned_entries); G->g.csc = HostSparse(); }
+    if (G->g.symmetric && G->g.csc.colidx) { free_entries(G->g.csc, G->pinned_entries, G->val_pinned); G->g.csc = HostSparse(); }
 
     const int n_forms = (G->g.symmetric || !G->g.has_csc) ? 1 : 2;
     G->form[0].m = &G->g.csr;

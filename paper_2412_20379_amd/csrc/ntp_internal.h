@@ -35,7 +35,8 @@ struct HostSparse {
     std::vector<int64_t> rowptr;   // n + 1
     int32_t* colidx = nullptr;     // nnz
     float* val = nullptr;          // nnz
-    bool pinned = false;           // colidx/val allocated with hipHostMalloc
+    bool pinned = false;           // colidx allocated with hipHostMalloc
+    bool val_pinned = false;       // val allocated with hipHostMalloc (false: malloc)
     int64_t max_degree = 0;
 };
 
@@ -57,8 +58,9 @@ enum { VAL_STORED = 0, VAL_GCN = 1, VAL_ONES = 2 };
 
 // allocator hooks so that graph_build.cpp stays free of HIP: returns nullptr on failure
 struct EntryAllocator {
-    void* (*alloc)(size_t bytes, void* ctx);
+    void* (*alloc)(size_t bytes, void* ctx);            // column ids (and weights that have to travel)
     void* ctx;
+    void* (*alloc_val)(size_t bytes, void* ctx);        // weights that never travel (rebuilt on the device)
 };
 
 // Build both compressed forms from an edge list (see ntp.h for the processing order).
