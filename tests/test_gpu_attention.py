@@ -450,3 +450,41 @@ def test_score_gradient_accumulates_over_calls(hub, hub_perm):
         torch.cuda.synchronize()
         assert torch.equal(first[0] + dp2, dp) and torch.equal(first[1] + dq2, dq)
 
+
+
+def test_two_heads_on_column_blocks(hub):
+    """several attention heads = one call per head on its block of columns of a wider matrix
+    (row strides, offset base pointers): each head's results equal those of a separate compact run"""
+    import torch
+    from gpu_util import dev_f32
+    n, src, dst, g, og = hub
+    nnz, c = og.csr.nnz, 12                 # two heads of 12 columns in rows of 24 (+ 8 padding)
+    ld = 32
+    rng = gen.stream_rng(55, 3)
+    Z = rng.normal(size=(n, 2 * c)).astype(np.float32)
+    dY = rng.normal(size=(n, 2 * c)).astype(np.float32)
+    Zd = torch.full((n, ld), float("nan"), device="cuda:0")
+    dYd = torch.full((n, ld), float("nan"), device="cuda:0")
+    Zd[:, :2 * c] = dev_f32(Z)
+    dYd[:, :2 * c] = dev_f32(dY)
+    Yd = torch.full((n, ld), float("nan"), device="cuda:0")
+    for h in range(2):
+        p, q = _scores(n, 60 + h)
+        a_in, a_out = _device_alpha(g, nnz, p, q, 0.2)
+        cols = slice(h * c, (h + 1) * c)
+        # forward aggregation of the head's columns with its weights, in place in the wide buffers
+        ntp.ntp_aggregate_weighted(g, ntp.NTP_FWD, a_in, Zd[:, cols], Yd[:, cols], c, ld, ld)
+        dp = torch.empty(n, device="cuda:0")
+        dq = torch.empty(n, device="cuda:0")
+        ntp.ntp_edge_softmax_bwd(g, dev_f32(p), dev_f32(q), 0.2, a_in, a_out, Zd[:, cols], dYd[:, cols], c, ld, ld, dp, dq)
+        torch.cuda.synchronize()
+        r_in, r_out = oracle.edge_softmax(og, p, q, 0.2)
+        ref, ref_abs = oracle.aggregate(oracle.weighted(og, r_in, r_out).csr, Z[:, cols], with_abs=True)
+        got = Yd[:, cols].cpu().numpy().astype(np.float64)
+        assert (np.abs(got - ref) / np.maximum(ref_abs, 1e-300)).max() <= 2e-5, "head %d forward" % h
+        r_dp, r_dq, _, _ = oracle.edge_softmax_bwd(og, p, q, Z[:, cols], dY[:, cols], 0.2)
+        sp, sq = _grad_scales(og, p, q, Z[:, cols], dY[:, cols], 0.2)
+        tiny = np.finfo(np.float32).tiny
+        assert (np.abs(dp.cpu().numpy() - r_dp) / np.maximum(sp, tiny)).max() <= TOL_SCORE_GRAD, "head %d dp" % h
+        assert (np.abs(dq.cpu().numpy() - r_dq) / np.maximum(sq, tiny)).max() <= TOL_SCORE_GRAD, "head %d dq" % h
+    assert torch.isnan(Yd[:, 2 * c:]).all()          # padding columns untouched
