@@ -93,6 +93,18 @@ template <int VEC> struct IoBf16 {
     static __device__ __forceinline__ void store1(unsigned short* p, float v) { *p = (unsigned short)f32_to_bf16_rne(v); }
 };
 
+// Wavefronts per SIMD the register allocation must allow.  The gather loop lives on loads in
+// flight across wavefronts: the line-wide fp32 shape (8 lanes x 16 bytes) fits 8 per SIMD in 59
+// registers without spilling (67 and 7 per SIMD when left alone; measured 1.5-2.5 % faster on
+// the low-degree config, 0.6 % on config 3); the other shapes keep the compiler's choice.
+template <class IO, int L, int NACC>
+constexpr int agg_min_waves() {
+    if (sizeof(typename IO::elem) == 4 && IO::kVec == 4 && NACC == 1) {
+        if (L == 8) return 8;
+    }
+    return 1;
+}
+
 // ---- the aggregation kernel -----------------------------------------------------------
 // L lanes per feature row, NACC vectors per lane (columns l*VEC + j*L*VEC), 4 wavefronts
 // per block, every wavefront an independent unit of work.  blockIdx.y walks column passes
@@ -104,7 +116,7 @@ template <int VEC> struct IoBf16 {
 // the slice reads the first column of its pass, an entry that does not exist reads the row's own vertex, and
 // what such a load returns is replaced by zero before it is used.
 template <class IO, int L, int NACC>
-__global__ void __launch_bounds__(256) agg_kernel(const AggArgs a) {
+__global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kernel(const AggArgs a) {
     using T = typename IO::elem;
     constexpr int VEC = IO::kVec;
     constexpr int R = 64 / L;
