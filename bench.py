@@ -743,6 +743,18 @@ def main():
             oracle.aggregate(m, xo)
             cpu_baseline["single_core_value"] = done / (time.perf_counter() - t1) / 1e9
             oracle.set_num_threads(all_cores)
+            if args.order == "layerwise" and not args.full_width:
+                # the same step as `value` (one whole layer-wise epoch: every aggregation and every
+                # transform, fp64) through the oracle, and its rate by the same definition
+                Xo = gen.make_features(args.config, dims[0], args.seed, args.scale_down)
+                Wo = [gen.glorot_weight(dims[i], dims[i + 1], args.seed, i) for i in range(L)]
+                lo = gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)
+                t1 = time.perf_counter()
+                oracle.epoch_layerwise(og, Xo, Wo, lo)
+                dt = time.perf_counter() - t1
+                cpu_baseline["epoch_s"] = dt
+                cpu_baseline["epoch_value"] = edge_feats / dt / 1e9
+                cpu_baseline["sample"] += "; epoch_value: one whole layer-wise epoch of the same model (%.2fs)" % dt
         log("oracle baseline: %.2f GEPS on %d threads (%.1fs incl. graph build)" % (cpu_baseline["value"], cpu_baseline["cores"], time.time() - t0))
 
     out = {
