@@ -127,6 +127,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
     constexpr int UMAX = NACC == 4 ? 2 : 4;
     constexpr int U = L < UMAX ? L : UMAX;
 
+    __shared__ float quarter[3][PASS_W];     // block-per-row mode: sums of wavefronts 1..3
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
     if (wave >= a.wave_start[a.n_groups]) return;
@@ -248,7 +249,16 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
     int row;
     int64_t beg, end;
     float* pout = nullptr;
-    if (mode == MODE_SEGMENT) {
+    if (mode == MODE_BLOCK_PER_ROW) {
+        // the block's four wavefronts take a quarter of the row each; the group is the first of
+        // the launch, so item0 / 4 is the block and item0 % 4 the wavefront inside it
+        row = __builtin_amdgcn_readfirstlane(a.split_rows[a.item_off[grp] + (item0 >> 2)].row);
+        const int64_t b0 = uniform64(a.rowptr[row - a.row_base]);
+        const int64_t d = uniform64(a.rowptr[row - a.row_base + 1]) - b0;
+        const int q = item0 & 3;
+        beg = b0 + d * q / 4;
+        end = b0 + d * (q + 1) / 4;
+    } else if (mode == MODE_SEGMENT) {
         const Segment* sp = a.segs + a.item_off[grp] + item0;
         row = __builtin_amdgcn_readfirstlane(sp->row);
         beg = uniform64(sp->e_begin);
@@ -317,6 +327,28 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[j][i] += bperm_f(lane ^ off, acc[j][i]);
 
+    if (mode == MODE_BLOCK_PER_ROW) {
+        // wavefronts 1..3 hand their sums to wavefront 0, which adds them in a fixed order
+        const int q = item0 & 3;
+        if (q > 0 && g == 0) {
+#pragma unroll
+            for (int j = 0; j < NACC; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) quarter[q - 1][(j * VEC + i) * L + l] = acc[j][i];
+        }
+        __syncthreads();
+        if (q == 0 && g == 0) {
+#pragma unroll
+            for (int j = 0; j < NACC; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    const int s = (j * VEC + i) * L + l;
+                    acc[j][i] = (acc[j][i] + quarter[0][s]) + (quarter[1][s] + quarter[2][s]);
+                }
+            store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase);
+        }
+        return;
+    }
     if (g == 0) {
         if (mode == MODE_SEGMENT) {     // scratch rows are padded to whole vectors
 #pragma unroll

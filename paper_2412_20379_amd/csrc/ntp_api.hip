@@ -122,7 +122,7 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
     a.f = (int32_t)f;
     a.fp = (int32_t)((f + 7) / 8 * 8);
 
-    int L, nacc, passes;
+    int L, nacc = 1, passes = 1;
     if (scatter) {
         L = scatter_lanes(f);
     } else {
@@ -143,8 +143,20 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
         waves += nw;
         ++ng;
     };
-    // heaviest work first: segments, then bins from long rows to short rows
-    if (c.n_segs > 0) add_group(MODE_SEGMENT, 0, c.n_segs, c.n_segs);
+    // Split rows.  While the chip is loaded a wavefront gets its share of the compute unit's
+    // gather rate: one 8192nd of the chip's (256 compute units x up to 32 wavefronts).  A split
+    // row handled by one block (four wavefronts, a quarter of the row each, sums combined through
+    // LDS: no partial sums in memory, no second kernel) therefore lasts as long as a chunk of
+    // 2048 x its length on the whole chip; it must stay well inside the column pass it belongs
+    // to.  Longer rows go to wavefronts all over the chip as segments, and reduce_kernel adds
+    // the pieces.  Measured on MI355X: 2.3 % faster on a 114 M-entry graph whose longest row has
+    // 20 k entries; block rows of 10 k entries on a 2.5 M-entry graph cost 9 %.
+    const bool block_rows = !scatter && c.n_reduce > 0 && !c.partial_row &&
+                            (int64_t)c.max_split_len * 4096 <= c.e_end - c.e_begin;
+    a.split_rows = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
+    // heaviest work first: split rows, then bins from long rows to short rows
+    if (block_rows) add_group(MODE_BLOCK_PER_ROW, 0, c.n_reduce, 4 * (int64_t)c.n_reduce);   // first: block-aligned
+    else if (c.n_segs > 0) add_group(MODE_SEGMENT, 0, c.n_segs, c.n_segs);
     for (int b = NBINS - 1; b >= 0; --b) {
         const int cnt = c.bin_count[b];
         if (cnt == 0) continue;
@@ -160,7 +172,7 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
         const int rc = scatter ? launch_scatter(a, st) : launch_aggregate(a, dtype, st);
         if (rc != NTP_OK) return rc;
     }
-    if (c.n_reduce > 0 && !scatter) {
+    if (c.n_reduce > 0 && !scatter && !block_rows) {
         ReduceArgs r;
         r.items = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
         r.partial = partial;

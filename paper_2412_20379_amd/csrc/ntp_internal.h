@@ -113,6 +113,7 @@ struct Chunk {
     int32_t bin_row_off[NBINS] = {0};          // offset of each bin's row list inside rows[]
     int32_t n_segs = 0;
     int32_t n_reduce = 0;
+    int32_t max_split_len = 0;                 // entries of the longest split row that ends in this chunk
     // device image layout: [meta | colidx | val], each part 256-byte aligned
     size_t img_off_colidx = 0, img_off_val = 0, img_bytes = 0;
     // residency
@@ -140,6 +141,7 @@ struct AggArgs {
     const float* val;
     const int32_t* rows;       // bin row lists (global row ids)
     const Segment* segs;
+    const ReduceItem* split_rows;   // the chunk's split rows (block-per-row mode)
     const void* X;
     void* Y;
     float* partial;            // [n_slots x fp] partial sums of split rows
@@ -155,7 +157,7 @@ struct AggArgs {
     int32_t item_count[NGROUPS];       // rows / segments in the group
     int32_t mode[NGROUPS];             // MODE_*
 };
-enum { MODE_GROUP_PER_ROW = 0, MODE_WAVE_PER_ROW = 1, MODE_SEGMENT = 2 };
+enum { MODE_GROUP_PER_ROW = 0, MODE_WAVE_PER_ROW = 1, MODE_SEGMENT = 2, MODE_BLOCK_PER_ROW = 3 };
 
 struct ReduceArgs {
     const ReduceItem* items;

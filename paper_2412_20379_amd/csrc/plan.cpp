@@ -4,6 +4,7 @@
 #include "ntp_internal.h"
 
 #include <algorithm>
+#include <climits>
 #include <cstring>
 
 namespace ntp {
@@ -107,6 +108,7 @@ void make_plan(const HostSparse& m, int64_t chunk_edges, Plan* plan) {
                     const int64_t base = d / nseg, extra = d % nseg;
                     int64_t e = m.rowptr[v];
                     cb.reduce.push_back(ReduceItem{(int32_t)v, next_slot, (int32_t)nseg, 0});
+                    c.max_split_len = (int32_t)std::max<int64_t>(c.max_split_len, std::min<int64_t>(d, INT32_MAX));
                     for (int64_t i = 0; i < nseg; ++i) {
                         const int64_t l = base + (i < extra ? 1 : 0);
                         cb.segs.push_back(Segment{e, (int32_t)l, (int32_t)v, next_slot++, 0});

@@ -263,3 +263,30 @@ def test_degenerate_graphs_on_device():
     g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_GCN_FLAGS | ntp.NTP_FORCE_STREAM, chunk_edges=9000)
     check_agg(g, og, x, "fwd", "f32", "star streamed", chunked=True)
     g.close()
+
+
+def test_split_rows_handled_by_one_block_each():
+    """Rows above the split threshold that are short against the whole graph (entries >= 4096 x the
+    longest row) are summed by one block each instead of segments plus a second kernel: a directed
+    graph with a few such rows in both forms, all shapes of the kernel."""
+    from gpu_util import check_agg
+    n = 60000
+    src, dst = gen.directed_random_edges(n, 2_600_000, 77)
+    rng = gen.stream_rng(77, 5)
+    extra_s, extra_d = [], []
+    for hub, k_in, k_out in ((11, 530, 0), (4097, 545, 520), (59999, 0, 560), (30000, 560, 540)):
+        extra_s += [rng.integers(0, n, size=k_in), np.full(k_out, hub)]
+        extra_d += [np.full(k_in, hub), rng.integers(0, n, size=k_out)]
+    src = np.concatenate([src] + [a.astype(np.int32) for a in extra_s])
+    dst = np.concatenate([dst] + [a.astype(np.int32) for a in extra_d])
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    for m in (og.csr, og.csc):
+        longest = int(np.diff(m.rowptr).max())
+        assert 512 < longest and longest * 4096 <= og.nnz, (longest, og.nnz)
+    for f, ld, dt in ((32, 32, "f32"), (256, 256, "f32"), (76, 76, "f32"), (13, 13, "f32"), (76, 128, "bf16"), (40, 40, "bf16")):
+        for direction in ("fwd", "bwd"):
+            say("block rows", f, ld, dt, direction)
+            x = gen.normal_features(n, f, seed=f)
+            check_agg(g, og, x, direction, dt, "block rows f=%d %s %s" % (f, dt, direction), ld_in=ld, ld_out=ld)
+    g.close()
