@@ -1,5 +1,6 @@
 """Seeded random sweep: graphs, flags, widths, strides, dtypes, chunkings and call variants drawn
 at random (fixed seeds), each compared with the oracle.  Complements the hand-picked cases."""
+import os
 import sys
 
 import numpy as np
@@ -16,7 +17,16 @@ def say(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-@pytest.mark.parametrize("seed", list(range(24)))
+def seeds(count):
+    """0..count-1, or the range "first:last" of NTP_SWEEP_SEEDS for a wider sweep"""
+    v = os.environ.get("NTP_SWEEP_SEEDS")
+    if v:
+        a, b = v.split(":")
+        return list(range(int(a), int(b)))
+    return list(range(count))
+
+
+@pytest.mark.parametrize("seed", seeds(24))
 def test_random_aggregation_case(seed):
     from gpu_util import check_agg
     rng = gen.stream_rng(seed, 99)
@@ -58,7 +68,7 @@ def test_random_aggregation_case(seed):
     g.close()
 
 
-@pytest.mark.parametrize("seed", list(range(12)))
+@pytest.mark.parametrize("seed", seeds(12))
 def test_random_transform_case(seed):
     import torch
     from gpu_util import dev_f32
