@@ -106,3 +106,32 @@ def test_random_transform_case(seed):
     ntp.ntp_nn_bwd(dev_f32(A), dev_f32(W), dev_f32(Href), dev_f32(dH), None, dW2, n, k, m, act, ntp.NTP_F32, ws, wsb)
     torch.cuda.synchronize()
     assert torch.equal(dA, dA2) and torch.equal(dW, dW2)
+
+
+@pytest.mark.parametrize("seed", seeds(16))
+def test_random_attention_case(seed):
+    """attention weights in both orders and the gradient of the scores on a random graph: flags,
+    chunking, edge permutation, width, strides and slope drawn at random"""
+    from test_gpu_attention import _scores, _device_alpha, _check_alpha, _score_grad_case
+    rng = gen.stream_rng(seed, 97)
+    n = int(rng.integers(1, 3000))
+    m_edges = int(rng.integers(0, 10 * n + 1))
+    src, dst = gen.directed_random_edges(n, m_edges, seed, hub=int(rng.integers(0, n)),
+                                         hub_in=int(rng.integers(0, max(1, n - 1))), hub_out=int(rng.integers(0, max(1, n // 2))))
+    flags = int(rng.choice([oracle.GCN_FLAGS, oracle.DIRECTED_GCN_FLAGS, oracle.DEDUP | oracle.ADD_SELF_LOOPS, oracle.DEDUP]))
+    og = oracle.build_graph(n, src, dst, flags)
+    dev_flags = flags | (ntp.NTP_EDGE_PERM if rng.integers(0, 2) else 0)
+    kw = dict(chunk_edges=int(rng.integers(1, max(2, og.csr.nnz)))) if rng.integers(0, 3) == 0 else {}
+    slope = float(rng.choice([0.2, 0.0, 1.0, 0.01]))
+    m = int(rng.choice([1, 2, 4, 7, 8, 16, 24, 32, 40, 47, 64, 76, 128, 172, 256, 600]))
+    pad_z, pad_dy = int(rng.choice([0, 0, 1, 4, 8, 32])), int(rng.choice([0, 0, 3, 4, 16]))
+    if m > 256:          # wider than 256 columns needs 16-byte aligned rows (documented limit)
+        pad_z, pad_dy = pad_z // 4 * 4, pad_dy // 4 * 4
+    say("  seed %d: n=%d nnz=%d flags=%d dev_flags=%d %s slope=%g m=%d ld=(%d,%d)" % (seed, n, og.csr.nnz, flags, dev_flags, kw, slope, m, m + pad_z, m + pad_dy))
+    g = ntp.ntp_graph_build(n, src, dst, flags=dev_flags, **kw)
+    p, q = _scores(n, seed, scale=float(rng.choice([0.5, 1.5, 6.0])))
+    if og.csr.nnz > 0:
+        a_in, a_out = _device_alpha(g, og.csr.nnz, p, q, slope)
+        _check_alpha(og, a_in, a_out, p, q, slope, "random seed %d" % seed)
+        _score_grad_case(g, og, m, slope, seed, "random seed %d" % seed, ldz=m + pad_z, lddy=m + pad_dy)
+    g.close()
