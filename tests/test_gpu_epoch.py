@@ -17,21 +17,30 @@ def say(*a):
 
 
 def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, overlap_dw=False, dims=None):
-    import torch
-    from paper_2412_20379_amd.gcn import GcnEpoch
-    from gpu_util import dev_f32
     spec = gen.CONFIGS[cfg]
     n, src, dst = gen.make_graph(cfg, seed=0, scale_down=scale)
     flags = oracle.GCN_FLAGS
     if directed:                       # keep the edges one-way so the transpose matters
         flags = oracle.DIRECTED_GCN_FLAGS
-    og = oracle.build_graph(n, src, dst, flags)
-    kw = dict(device_budget_bytes=8 << 20, chunk_edges=200_000) if chunked else {}
-    g = ntp.ntp_graph_build(n, src, dst, flags=flags | (ntp.NTP_SCATTER_BWD if scatter else 0), **kw)
     dims = dims or spec.layers
     X = gen.make_features(cfg, dims[0], seed=0, scale_down=scale)
-    Ws = [gen.glorot_weight(dims[i], dims[i + 1], 0, i) for i in range(len(dims) - 1)]
-    labels = gen.uniform_labels(n, dims[-1], 0)
+    kw = dict(device_budget_bytes=8 << 20, chunk_edges=200_000) if chunked else {}
+    run_epoch_case(n, src, dst, flags, X, dims, order, chunked=chunked, scatter=scatter, overlap_dw=overlap_dw, build_kw=kw, what="config %d" % cfg)
+
+
+def run_epoch_case(n, src, dst, flags, X, dims, order, chunked=False, scatter=False, overlap_dw=False, build_kw=None, what="", seed=0,
+                   scale_floor=0.0):
+    """one epoch on the device against the oracle: loss, logits, every dW.  scale_floor: entries of dW whose
+    sum of |terms| is below this fraction of the largest one are measured against that fraction (the inputs of
+    the product carry the rounding of the calls before it, which is relative to THEIR sums of magnitudes and can
+    exceed a cancelled entry's own)"""
+    import torch
+    from paper_2412_20379_amd.gcn import GcnEpoch
+    from gpu_util import dev_f32
+    og = oracle.build_graph(n, src, dst, flags)
+    g = ntp.ntp_graph_build(n, src, dst, flags=flags | (ntp.NTP_SCATTER_BWD if scatter else 0), **(build_kw or {}))
+    Ws = [gen.glorot_weight(dims[i], dims[i + 1], seed, i) for i in range(len(dims) - 1)]
+    labels = gen.uniform_labels(n, dims[-1], seed)
     ep = GcnEpoch(g, n, dims, order=order, chunked=chunked, overlap_dw=overlap_dw)
     loss = ep.run(dev_f32(X), [dev_f32(w) for w in Ws], torch.from_numpy(labels.astype(np.int64)).to("cuda:0"))
     torch.cuda.synchronize()
@@ -47,14 +56,14 @@ def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, over
         flips = mk != (own["hidden"][l] > 0)
         frac = flips.mean()
         say("  layer %d: %d ReLU decisions differ (%.1e of all)" % (l, int(flips.sum()), frac))
-        assert frac <= 1e-4
+        assert frac <= 1e-4 or flips.sum() <= 1
     ref = fn(og, X, Ws, labels, relu_masks=masks)
     for l, mk in enumerate(masks):
         flips = mk != (own["hidden"][l] > 0)
         if flips.any():      # a differing decision is only allowed on a value that is ~0
             near0 = np.maximum(np.abs(ref["hidden"][l][flips]), np.abs(own["hidden"][l][flips])).max()
             assert near0 <= 1e-4 * np.abs(own["hidden"][l]).max()
-    say(cfg, order, "loss", float(loss), "oracle", ref["loss"])
+    say(what, order, "loss", float(loss), "oracle", ref["loss"])
     assert abs(float(loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
     Z = ep.logits.cpu().numpy().astype(np.float64)
     zs = np.abs(ref["logits"]).max()
@@ -67,7 +76,8 @@ def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, over
         got = dW.cpu().numpy().astype(np.float64)
         dZ = ref["dH"][l] * (ref["hidden"][l] > 0) if l < L - 1 else ref["dH"][l]
         scale_l = np.abs(ref["nn_in"][l]).T @ np.abs(dZ)
-        err = (np.abs(got - ref["dW"][l]) / scale_l).max()
+        scale_l = np.maximum(scale_l, scale_floor * scale_l.max())
+        err = (np.abs(got - ref["dW"][l]) / np.maximum(scale_l, np.finfo(np.float64).tiny)).max()
         nerr = np.abs(got - ref["dW"][l]).max() / np.abs(ref["dW"][l]).max()
         say("  dW[%d] error vs sum of |terms| %.2e, vs max|dW| %.2e" % (l, err, nerr))
         assert err <= 5e-5, "dW[%d]" % l

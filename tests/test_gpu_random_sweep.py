@@ -135,3 +135,25 @@ def test_random_attention_case(seed):
         _check_alpha(og, a_in, a_out, p, q, slope, "random seed %d" % seed)
         _score_grad_case(g, og, m, slope, seed, "random seed %d" % seed, ldz=m + pad_z, lddy=m + pad_dy)
     g.close()
+
+
+@pytest.mark.parametrize("seed", seeds(12))
+def test_random_epoch_case(seed):
+    """a whole GCN epoch on a random graph: depth, widths, order, flags and chunking drawn at random"""
+    from test_gpu_epoch import run_epoch_case
+    rng = gen.stream_rng(seed, 96)
+    n = int(rng.integers(50, 3000))
+    src, dst = gen.directed_random_edges(n, int(rng.integers(n, 10 * n)), seed, hub=int(rng.integers(0, n)),
+                                         hub_in=int(rng.integers(0, n - 1)), hub_out=int(rng.integers(0, n // 2)))
+    flags = int(rng.choice([oracle.GCN_FLAGS, oracle.DIRECTED_GCN_FLAGS]))
+    depth = int(rng.integers(1, 5))
+    dims = [int(rng.choice([3, 8, 16, 32, 40, 64, 100, 128, 130, 256, 300]))]
+    dims += [int(rng.choice([4, 16, 32, 64, 128, 256])) for _ in range(depth - 1)]
+    dims += [int(rng.choice([2, 7, 16, 40, 41, 47, 64, 172]))]
+    order = str(rng.choice(["layerwise", "decoupled", "reordered", "auto"]))
+    chunked = bool(rng.integers(0, 3) == 0)
+    kw = dict(chunk_edges=int(rng.integers(500, 20000))) if chunked else {}
+    overlap = bool(order in ("layerwise", "auto") and not chunked and rng.integers(0, 2))
+    say("  seed %d: n=%d flags=%d dims=%s order=%s chunked=%s %s overlap_dw=%s" % (seed, n, flags, dims, order, chunked, kw, overlap))
+    X = gen.normal_features(n, dims[0], seed=seed)
+    run_epoch_case(n, src, dst, flags, X, dims, order, chunked=chunked, overlap_dw=overlap, build_kw=kw, what="random seed %d" % seed, seed=seed, scale_floor=1e-2)
