@@ -157,3 +157,25 @@ def test_random_epoch_case(seed):
     say("  seed %d: n=%d flags=%d dims=%s order=%s chunked=%s %s overlap_dw=%s" % (seed, n, flags, dims, order, chunked, kw, overlap))
     X = gen.normal_features(n, dims[0], seed=seed)
     run_epoch_case(n, src, dst, flags, X, dims, order, chunked=chunked, overlap_dw=overlap, build_kw=kw, what="random seed %d" % seed, seed=seed, scale_floor=1e-2)
+
+
+@pytest.mark.parametrize("seed", seeds(8))
+def test_random_gat_epoch_case(seed):
+    """a whole decoupled GAT epoch on a random graph: depth, widths, rounds, slope, flags, chunking
+    and the edge permutation drawn at random"""
+    from test_gpu_gat import _gat_epoch
+    rng = gen.stream_rng(seed, 95)
+    n = int(rng.integers(200, 3000))
+    src, dst = gen.directed_random_edges(n, int(rng.integers(n, 10 * n)), seed, hub=int(rng.integers(0, n)),
+                                         hub_in=int(rng.integers(0, n - 1)), hub_out=int(rng.integers(0, n // 2)))
+    flags = int(rng.choice([oracle.GCN_FLAGS, oracle.DIRECTED_GCN_FLAGS]))
+    depth = int(rng.integers(1, 4))
+    dims = [int(rng.choice([8, 16, 32, 64, 100, 128, 256]))]
+    dims += [int(rng.choice([16, 32, 64, 128])) for _ in range(depth - 1)]
+    dims += [int(rng.choice([2, 7, 16, 40, 41, 47, 64, 172]))]
+    rounds = int(rng.integers(1, 4))
+    slope = float(rng.choice([0.2, 0.0, 0.05]))
+    chunk_edges = int(rng.integers(500, 20000)) if rng.integers(0, 3) == 0 else None
+    extra = ntp.NTP_EDGE_PERM if rng.integers(0, 2) else 0
+    _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, "random seed %d, chunk_edges %s, extra flags %d" % (seed, chunk_edges, extra),
+               chunk_edges=chunk_edges, extra_flags=extra, scale_floor=1e-2)
