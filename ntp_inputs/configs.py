@@ -46,8 +46,12 @@ CONFIGS = {
 }
 
 
-def make_graph(cfg: int, seed: int = 0, scale_down: int = 1):
+def make_graph(cfg: int, seed: int = 0, scale_down: int = 1, permute: bool = True):
     """Undirected edge list (each edge once) for config ``cfg``.
+
+    permute = False keeps the generator's own vertex numbering (R-MAT: low ids
+    are the hubs; Zipf: ids sorted by degree) instead of relabelling the vertices
+    at random: the best case for locality, not what the configs ask for.
 
     Returns (n_vertices, src, dst).  With scale_down = k the vertex and edge
     counts are divided by k (same generator, same parameters); the dense
@@ -65,9 +69,9 @@ def make_graph(cfg: int, seed: int = 0, scale_down: int = 1):
     elif spec.graph == "rmat":
         # exact configs keep the first m distinct edges; the others keep every
         # distinct edge of the batches drawn (a little above m; callers print it)
-        src, dst = g.rmat_edges(n, m, seed, exact=spec.exact_edges)
+        src, dst = g.rmat_edges(n, m, seed, exact=spec.exact_edges, permute=permute)
     elif spec.graph == "zipf":
-        src, dst = g.zipf_configuration_edges(n, 2 * m, seed, s=1.1, cap=max(1, n // 8))
+        src, dst = g.zipf_configuration_edges(n, 2 * m, seed, s=1.1, cap=max(1, n // 8), permute=permute)
     else:
         raise ValueError(spec.graph)
     return n, src, dst
