@@ -172,7 +172,10 @@ def test_wide_dynamic_range_keeps_fp32_accuracy(n, k, m):
         assert comp <= 2e-6 and norm <= 2e-6, name
 
 
-@pytest.mark.parametrize("n,c", [(1, 1), (7, 3), (1000, 7), (2708, 16), (5000, 40), (3001, 47), (999, 172), (70000, 41), (4099, 300)])
+@pytest.mark.parametrize("n,c", [(1, 1), (7, 3), (1000, 7), (2708, 16), (5000, 40), (3001, 47), (999, 172), (70000, 41), (4099, 300),
+                                 # more than 16384 block sums (1024 partial sums in between); a row that does not
+                                 # fit eight classes per lane; exactly eight per lane
+                                 (600000, 10), (3000, 600), (2000, 512), (2000, 64), (2000, 65)])
 def test_softmax_cross_entropy(n, c):
     """loss of the downstream task and its gradient against the oracle; strided logits,
     large logits (no overflow), determinism"""
