@@ -250,7 +250,13 @@ def main():
                "pcie_h2d_gbs": pcie_gbs, "t_inmem_ms": t_inmem}
         g_all = ntp.ntp_graph_build(n, src, dst, chunk_edges=ce)
         out["t_chunked_all_resident_ms"] = timeit(g_all, True)
-        assert torch.equal(y, ref)
+        # the chunked plan cuts long rows into pieces sized for a chunk's launch, the in-memory plan for
+        # the whole graph: the same sums in another order, equal to rounding; the streamed variants below
+        # share the chunked plan and must reproduce its bits
+        diff = float((y - ref).abs().max() / ref.abs().max())
+        assert diff <= 1e-5, diff
+        out["chunked_vs_inmem_max_rel_diff"] = diff
+        ref = y.clone()
         g_all.close()
         total_bytes = nnz * 8 + n * 12
         g_half = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=int(total_bytes * 0.62), chunk_edges=ce)

@@ -26,6 +26,11 @@ struct Form {
     HostSparse* m = nullptr;
     Plan plan;
     bool all_resident = false;
+    // forms of several chunks: the reduce items of all chunks that sum their split rows from
+    // segments, in chunk order, on the device (one reduce_kernel launch per pass)
+    ReduceItem* d_all_reduce = nullptr;
+    int n_all_reduce = 0;
+    bool one_reduce() const { return d_all_reduce != nullptr; }
 };
 
 struct ntp_graph {
@@ -104,7 +109,7 @@ inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX
 // weights: caller's edge weights in the entry order of the form (nullptr: the stored ones)
 int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* partial,
               int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st, bool scatter = false,
-              const float* weights = nullptr, const int32_t* columns = nullptr) {
+              const float* weights = nullptr, const int32_t* columns = nullptr, bool defer_reduce = false) {
     AggArgs a;
     memset(&a, 0, sizeof a);
     a.rowptr = reinterpret_cast<const int64_t*>(img + c.off_rowptr);
@@ -143,16 +148,7 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
         waves += nw;
         ++ng;
     };
-    // Split rows.  While the chip is loaded a wavefront gets its share of the compute unit's
-    // gather rate: one 8192nd of the chip's (256 compute units x up to 32 wavefronts).  A split
-    // row handled by one block (four wavefronts, a quarter of the row each, sums combined through
-    // LDS: no partial sums in memory, no second kernel) therefore lasts as long as a chunk of
-    // 2048 x its length on the whole chip; it must stay well inside the column pass it belongs
-    // to.  Longer rows go to wavefronts all over the chip as segments, and reduce_kernel adds
-    // the pieces.  Measured on MI355X: 2.3 % faster on a 114 M-entry graph whose longest row has
-    // 20 k entries; block rows of 10 k entries on a 2.5 M-entry graph cost 9 %.
-    const bool block_rows = !scatter && c.n_reduce > 0 && !c.partial_row &&
-                            (int64_t)c.max_split_len * 4096 <= c.e_end - c.e_begin;
+    const bool block_rows = !scatter && c.block_rows;      // split rows summed by one block each (see make_plan)
     a.split_rows = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
     // heaviest work first: split rows, then bins from long rows to short rows
     if (block_rows) add_group(MODE_BLOCK_PER_ROW, 0, c.n_reduce, 4 * (int64_t)c.n_reduce);   // first: block-aligned
@@ -172,7 +168,7 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
         const int rc = scatter ? launch_scatter(a, st) : launch_aggregate(a, dtype, st);
         if (rc != NTP_OK) return rc;
     }
-    if (c.n_reduce > 0 && !scatter && !block_rows) {
+    if (c.n_reduce > 0 && !scatter && !block_rows && !defer_reduce) {
         ReduceArgs r;
         r.items = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
         r.partial = partial;
@@ -185,6 +181,21 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
         if (rc != NTP_OK) return rc;
     }
     return NTP_OK;
+}
+
+// One reduce_kernel launch for the split rows of every chunk of a form (their items were
+// gathered on the device at build time): replaces one launch per chunk when a form has several.
+int reduce_all(const Form& F, float* partial, void* Y, int64_t f, int64_t ldy, int dtype, hipStream_t st) {
+    if (F.n_all_reduce == 0) return NTP_OK;
+    ReduceArgs r;
+    r.items = F.d_all_reduce;
+    r.partial = partial;
+    r.Y = Y;
+    r.ldy = ldy;
+    r.f = (int32_t)f;
+    r.fp = (int32_t)((f + 7) / 8 * 8);
+    r.n_items = F.n_all_reduce;
+    return launch_reduce(r, dtype, st);
 }
 
 // floats of scratch one right-hand side needs for the partial sums of split rows
@@ -231,6 +242,7 @@ void destroy(ntp_graph* G) {
     for (int k = 0; k < 2; ++k) {
         for (auto& c : G->form[k].plan.chunks)
             if (c.d_image) (void)hipFree(c.d_image);
+        if (G->form[k].d_all_reduce) (void)hipFree(G->form[k].d_all_reduce);
         if (G->stage[k]) (void)hipFree(G->stage[k]);
         if (G->ev_ready[k]) (void)hipEventDestroy(G->ev_ready[k]);
         if (G->ev_free[k]) (void)hipEventDestroy(G->ev_free[k]);
@@ -361,6 +373,24 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
             bool allr = true;
             for (auto& c : G->form[k].plan.chunks) allr = allr && c.d_image;
             G->form[k].all_resident = allr;
+        }
+        for (int k = 0; k < n_forms; ++k) {
+            Form& F = G->form[k];
+            if (F.plan.chunks.size() < 2) continue;
+            std::vector<ReduceItem> all;
+            for (auto& c : F.plan.chunks)
+                if (c.n_reduce > 0 && !c.block_rows) {
+                    const ReduceItem* it = reinterpret_cast<const ReduceItem*>(c.meta.data() + c.off_reduce);
+                    all.insert(all.end(), it, it + c.n_reduce);
+                }
+            if (all.empty()) continue;
+            void* p = nullptr;
+            const size_t bytes = all.size() * sizeof(ReduceItem);
+            if (hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes for the split rows failed", bytes); return NTP_ENOMEM; }
+            F.d_all_reduce = (ReduceItem*)p;
+            F.n_all_reduce = (int)all.size();
+            G->device_bytes += (int64_t)bytes;
+            if (hipMemcpy(p, all.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) { (void)hipGetLastError(); set_error("upload of the split rows failed"); return NTP_EHIP; }
         }
         if (pinned_meta_bytes) {
             void* p = nullptr;
@@ -501,9 +531,10 @@ static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y,
     else rc = ensure_partial(g, F, f);
     if (rc != NTP_OK) return rc;
     for (auto& c : F.plan.chunks) {
-        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights, columns);
+        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights, columns, F.one_reduce());
         if (rc != NTP_OK) return rc;
     }
+    if (!scatter && F.one_reduce()) return reduce_all(F, g->partial, Y, f, ldy, dtype, (hipStream_t)stream);
     return NTP_OK;
 }
 
@@ -548,7 +579,8 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
     // every chunk is brought in once and applied to all right-hand sides before the next one
     auto run_all = [&](const Chunk& c, const char* img) -> int {
         for (int r = 0; r < n_rhs; ++r) {
-            const int e = run_chunk(c, img, X[r], Y[r], scatter ? nullptr : g->partial + (size_t)r * pstride, f, ldx, ldy, dtype, cs, scatter);
+            const int e = run_chunk(c, img, X[r], Y[r], scatter ? nullptr : g->partial + (size_t)r * pstride, f, ldx, ldy, dtype, cs, scatter,
+                                    nullptr, nullptr, F.one_reduce());
             if (e != NTP_OK) return e;
         }
         return NTP_OK;
@@ -582,6 +614,11 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
         HIP_TRY(hipEventRecord(g->ev_free[b], cs));
         g->stage_used[b] = true;
     }
+    if (!scatter && F.one_reduce())
+        for (int r = 0; r < n_rhs; ++r) {
+            rc = reduce_all(F, g->partial + (size_t)r * pstride, Y[r], f, ldy, dtype, cs);
+            if (rc != NTP_OK) return rc;
+        }
     return NTP_OK;
 }
 

@@ -114,6 +114,7 @@ struct Chunk {
     int32_t n_segs = 0;
     int32_t n_reduce = 0;
     int32_t max_split_len = 0;                 // entries of the longest split row that ends in this chunk
+    bool block_rows = false;                   // split rows are summed by one block each (no segments, no partial sums)
     // device image layout: [meta | colidx | val], each part 256-byte aligned
     size_t img_off_colidx = 0, img_off_val = 0, img_bytes = 0;
     // residency
