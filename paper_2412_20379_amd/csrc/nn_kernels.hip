@@ -737,7 +737,15 @@ int launch_gemm(const GemmArgs& g, int n_splits, hipStream_t st) {
     if (g.Ndim > 64) {
         launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 128, 128, 2, 2>(g, n_splits, st);
     } else if (g.Ndim > 32) {
-        launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 256, 64, 4, 1>(g, n_splits, st);
+        // two blocks per compute unit run at a time (512 on 256 CUs): take the tile height whose
+        // last round of blocks is fuller (169,343 rows: 662 blocks of 256 rows fill 65 % of two
+        // rounds, 1,323 blocks of 128 rows 86 % of three)
+        auto fill = [&](int64_t bm) {
+            const int64_t b = (g.Mdim + bm - 1) / bm * n_splits;
+            return (double)b / (double)((b + 511) / 512 * 512);
+        };
+        if (fill(128) > fill(256) + 0.1) launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 128, 64, 4, 1>(g, n_splits, st);
+        else launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 256, 64, 4, 1>(g, n_splits, st);
     } else if ((g.Mdim + 255) / 256 * n_splits >= 256) {
         launch_tiles<TA, TB, TC, AK, BKC, MA, MB, 256, 32, 4, 1>(g, n_splits, st);
     } else {     // few rows: smaller tiles so that more compute units get a block
