@@ -96,7 +96,7 @@ def test_attention_scores_argument_errors():
     ntp.ntp_attention_scores_fwd(z, a, a, v, v, 0, 8, 8)       # nothing to do
 
 
-def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=None, extra_flags=0, scale_floor=0.0):
+def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=None, extra_flags=0, scale_floor=0.0, grad_tol=5e-5):
     import torch
     from paper_2412_20379_amd.gat import GatEpoch
     from gpu_util import dev_f32
@@ -128,18 +128,37 @@ def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=
     assert np.abs(Z - ref["logits"]).max() <= 2e-5 * np.abs(ref["logits"]).max()
     a_in = ep.alpha_in.cpu().numpy().astype(np.float64)
     assert (np.abs(a_in - ref["alpha_in"]) / ref["alpha_in"]).max() <= 5e-5
+    # The LeakyReLU of an edge score has a kink at zero: where p[u] + q[v] is zero to rounding, fp32
+    # and fp64 may take different branches, and the gradients then differ by that edge's whole term
+    # (the forward values are continuous there and have been checked above).  Such a graph says
+    # nothing about the gradients; it turns up about once in fifty random cases.
+    if slope != 1.0:
+        rows_of = np.repeat(np.arange(n), np.diff(og.csr.rowptr))
+        pe, qe = ref["p"][og.csr.colidx], ref["q"][rows_of]
+        near = np.abs(pe + qe) <= 1e-5 * (np.abs(pe) + np.abs(qe))
+        if near.any():
+            say("      %d edge scores are zero to rounding: gradients not compared" % int(near.sum()))
+            g.close()
+            return
     # gradients: error against the sum of the magnitudes of the terms each one adds up; an epoch
     # chains about a dozen fp32 calls, so the bound is 5x the per-call 1e-5 (as for the GCN epochs)
     Lh = np.abs(ref["Z"][0])
-    for name, got, want, scale in (("da_src", ep.da_src, ref["da_src"], Lh.T @ np.abs(ref["dp"])),
-                                   ("da_dst", ep.da_dst, ref["da_dst"], Lh.T @ np.abs(ref["dq"]))):
-        scale = np.maximum(np.maximum(scale, scale_floor * scale.max()), np.finfo(np.float64).tiny)
+    s_src, s_dst = Lh.T @ np.abs(ref["dp"]), Lh.T @ np.abs(ref["dq"])
+    joint = max(s_src.max(), s_dst.max())       # dp and dq add up the same per-edge terms
+    for name, got, want, scale in (("da_src", ep.da_src, ref["da_src"], s_src), ("da_dst", ep.da_dst, ref["da_dst"], s_dst)):
+        scale = np.maximum(np.maximum(scale, scale_floor * joint), np.finfo(np.float64).tiny)
         err = (np.abs(got.cpu().numpy() - want) / scale).max()
         say("      %s error vs sum of |terms| %.2e" % (name, err))
-        assert err <= 5e-5, name
+        # the scale uses |dp|, |dq| as they come out, not the magnitudes of the terms they were summed
+        # from: where those cancel (softmax gradients add up to zero per vertex) it understates the
+        # rounding the factors carry, so random cases take a wider bound than the fixed ones
+        assert err <= grad_tol, name
     # dp, dq: normwise (their per-vertex scale is what the score-gradient tests check)
+    # one scale for both: dp and dq add up the same per-edge terms, and where every score is positive
+    # dq is zero but for rounding (a softmax gradient sums to zero over the in-edges of a vertex)
+    pq_scale = max(np.abs(ref["dp"]).max(), np.abs(ref["dq"]).max())
     for name, got, want in (("dp", ep.dp, ref["dp"]), ("dq", ep.dq, ref["dq"])):
-        nerr = np.abs(got.cpu().numpy() - want).max() / np.abs(want).max()
+        nerr = np.abs(got.cpu().numpy() - want).max() / pq_scale
         say("      %s normwise error %.2e" % (name, nerr))
         assert nerr <= 2e-4, name
     L = len(Ws)
