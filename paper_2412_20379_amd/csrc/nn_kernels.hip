@@ -644,6 +644,13 @@ __global__ void __launch_bounds__(256) sum_splits_kernel(const float* __restrict
     if (i < count) {
         const float* p = part + i;
         int k = w;
+        for (; k + 28 < n_splits; k += 32) {       // eight loads in flight, added in ascending order
+            float t[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[j] = p[(int64_t)(k + 4 * j) * stride];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += t[j];
+        }
         for (; k + 12 < n_splits; k += 16) {
             const float t0 = p[(int64_t)k * stride], t1 = p[(int64_t)(k + 4) * stride];
             const float t2 = p[(int64_t)(k + 8) * stride], t3 = p[(int64_t)(k + 12) * stride];
