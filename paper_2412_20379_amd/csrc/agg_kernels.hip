@@ -361,7 +361,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
 }
 
 // ---- second pass for split rows: Y[row,:] = sum of its partial-sum slots ---------------
-// One block per split row.  Wavefront w adds the slots w, w+4, w+8, ... in ascending
+// One block per split row and 64 columns.  Wavefront w adds the slots w, w+4, w+8, ... in ascending
 // order (independent loads, four in flight), the four sums are combined through LDS as
 // (s0 + s1) + (s2 + s3): a fixed order, so the result is deterministic.
 template <class T>
@@ -370,8 +370,8 @@ __global__ void __launch_bounds__(256) reduce_kernel(const ReduceArgs a) {
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const ReduceItem it = a.items[blockIdx.x];
-    for (int col0 = 0; col0 < a.f; col0 += 64) {
-        const int col = col0 + lane;
+    {
+        const int col = (int)blockIdx.y * 64 + lane;        // one block per split row and 64 columns
         float s = 0.f;
         if (col < a.f) {
             const float* p = a.partial + (int64_t)it.first_slot * a.fp + col;
@@ -391,7 +391,6 @@ __global__ void __launch_bounds__(256) reduce_kernel(const ReduceArgs a) {
             if constexpr (sizeof(T) == 4) *y = r;
             else *y = (T)f32_to_bf16_rne(r);
         }
-        __syncthreads();
     }
 }
 
@@ -505,7 +504,7 @@ int launch_aggregate(const AggArgs& a, int dtype, void* stream) {
 int launch_reduce(const ReduceArgs& a, int dtype, void* stream) {
     if (a.n_items <= 0) return NTP_OK;
     hipStream_t st = (hipStream_t)stream;
-    dim3 grid((unsigned)a.n_items);
+    dim3 grid((unsigned)a.n_items, (unsigned)((a.f + 63) / 64));
     if (dtype == NTP_F32) hipLaunchKernelGGL(reduce_kernel<float>, grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL(reduce_kernel<unsigned short>, grid, dim3(256), 0, st, a);
     const hipError_t e = hipGetLastError();
