@@ -196,7 +196,10 @@ def main():
     log("config %d: n=%d nnz=%d max_degree=%d (generated in %.1fs, graph build %.2fs)"
         % (args.config, n, nnz, info["max_degree"], t_gen, t_build))
 
-    if args.copy_probe:
+    copy_gbs = None
+    if args.copy_probe or args.mode == "step":
+        # a plain 1 GiB device copy: what the memory system delivers to a streaming kernel (read +
+        # write), the practical ceiling beside the 8 TB/s nominal one
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         b = torch.empty_like(a)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -206,7 +209,8 @@ def main():
             b.copy_(a)
         e1.record()
         torch.cuda.synchronize()
-        log("copy probe: 1 GiB read + 1 GiB written per copy, %.1f GB/s" % (5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9))
+        copy_gbs = 5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        log("copy probe: 1 GiB read + 1 GiB written per copy, %.1f GB/s" % copy_gbs)
         del a, b
 
     if args.mode == "chunk":
@@ -666,6 +670,9 @@ def main():
                     traffic_gbs=(traffic / (dur_ms * 1e-3) / 1e9) if traffic else None,
                     traffic_frac_of_peak=(traffic / (dur_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic else None,
                     overfetch=(traffic / balg) if traffic else None,
+                    # the same two rates against a plain device copy measured in this run
+                    copy_gbs=copy_gbs, frac_of_copy=(achieved / copy_gbs) if copy_gbs else None,
+                    traffic_frac_of_copy=(traffic / (dur_ms * 1e-3) / 1e9 / copy_gbs) if (traffic and copy_gbs) else None,
                     geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
     nn_tflops = flops_nn / (nn_ms * 1e-3) / 1e12 if nn_ms > 0 else None
     split_core = not os.environ.get("NTP_NN_CORE", "").startswith("f")
