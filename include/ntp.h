@@ -166,7 +166,10 @@ int ntp_aggregate_bwd(ntp_graph_t* g, const void* Gout, void* Gin,
 
 /*
  * Chunk-scheduled aggregation (Section 4.2.1, inner chunk loop of Alg. 1): same result as
- * ntp_aggregate_fwd / _bwd (direction NTP_FWD / NTP_BWD), produced chunk by chunk.
+ * ntp_aggregate_fwd / _bwd (direction NTP_FWD / NTP_BWD), produced chunk by chunk.  Against a
+ * graph built with another chunking the result agrees to rounding, not in every bit: rows too
+ * long for one wavefront are summed in pieces whose length follows the chunk size.  For one
+ * graph the result is the same whether a chunk is resident or streamed, and from call to call.
  * Resident chunks are aggregated in place; every other chunk is copied from pinned host
  * memory into one of two device staging buffers on copy_stream while the previous chunk
  * is aggregated on compute_stream (events order the two).  X and Y stay on the device for
