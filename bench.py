@@ -619,10 +619,10 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # Every fourth step of the timed region records a pair of HIP events around each library call
+    # Every eighth step of the timed region records a pair of HIP events around each library call
     # (the per-call durations below); the pairs cost about 6 us per call, which over all steps
     # would be 5-6 % of a config-2 epoch.
-    every = 4
+    every = 8
     n_instrumented = 0
     t0 = time.perf_counter()
     for i in range(args.steps):
