@@ -171,7 +171,7 @@ def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=
         # that fraction of it (their inputs carry the rounding of the calls before)
         scale_l = np.maximum(np.maximum(scale_l, scale_floor * scale_l.max()), np.finfo(np.float64).tiny)
         err = (np.abs(got - ref["dW"][l]) / scale_l).max()
-        nerr = np.abs(got - ref["dW"][l]).max() / np.abs(ref["dW"][l]).max()
+        nerr = np.abs(got - ref["dW"][l]).max() / max(np.abs(ref["dW"][l]).max(), np.finfo(np.float64).tiny)
         say("      dW[%d] error vs sum of |terms| %.2e, vs max|dW| %.2e" % (l, err, nerr))
         assert err <= 5e-5, "dW[%d]" % l
         assert nerr <= 2e-3, "dW[%d] normwise" % l
