@@ -156,6 +156,23 @@ int ntp_aggregate_fwd(ntp_graph_t* g, const void* X, void* Y,
                       int64_t f_slice, int64_t ldx, int64_t ldy, int dtype, void* stream);
 
 /*
+ * ntp_aggregate_fwd for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and the same bits as ntp_aggregate_fwd, but the partial sums of split rows (rows too long for
+ * one wavefront) go to a scratch array that is part of the library image instead of a buffer
+ * the handle allocates on first use: the call makes no hipMalloc / hipFree and no
+ * synchronisation.  The array holds NTP_NOALLOC_SCRATCH_BYTES on every GPU the library runs on,
+ * for the life of the process.  A graph whose split rows need more at this width
+ * (pieces of split rows x f_slice rounded up to 8 x 4 bytes) is refused with NTP_EUNSUPPORTED.
+ * All calls on one GPU share the array, whatever the handle or stream: calls that overlap in
+ * time on one GPU race; nothing in it has to be zero between calls (every slot is written
+ * before it is read).
+ */
+#define NTP_NOALLOC_SCRATCH_BYTES (8ll << 20)
+int ntp_aggregate_fwd_noalloc(ntp_graph_t* g, const void* X, void* Y,
+                              int64_t f_slice, int64_t ldx, int64_t ldy, int dtype, void* stream);
+
+/*
  * Backward aggregation (Section 4.2.1; AGG of the reverse loop in Alg. 1): the gradient of
  * a source vertex is the weighted sum of the gradients of the vertices it points to,
  *     Gin[u, 0:f] = sum over stored entries (v,u) of val(v,u) * Gout[v, 0:f] = A_hat^T Gout,

@@ -21,7 +21,7 @@ NTP_ACT_NONE, NTP_ACT_RELU = 0, 1
 
 EXPORTED_SYMBOLS = [
     "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_export_perm", "ntp_graph_chunks", "ntp_graph_stream_bytes",
-    "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
+    "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_fwd_noalloc", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
     "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_edge_softmax_bwd", "ntp_aggregate_weighted",
     "ntp_attention_scores_fwd", "ntp_attention_scores_bwd", "ntp_attention_scores_bwd_scratch_bytes",
     "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent", "ntp_softmax_xent_scratch_bytes", "ntp_relu_fwd", "ntp_relu_bwd",
@@ -62,6 +62,7 @@ def lib():
     L.ntp_graph_device_bytes.argtypes = [vp, vp]
     L.ntp_aggregate_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_aggregate_bwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
+    L.ntp_aggregate_fwd_noalloc.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_chunked_aggregate.argtypes = [vp, ctypes.c_int, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_chunked_aggregate_multi.argtypes = [vp, ctypes.c_int, i32, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_edge_softmax.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp]
@@ -210,6 +211,13 @@ def ntp_graph_free(g: Graph):
 
 def ntp_aggregate_fwd(g: Graph, X, Y, f_slice, ldx, ldy, dtype=NTP_F32, stream=None):
     _check(lib().ntp_aggregate_fwd(g.handle, _ptr(X), _ptr(Y), int(f_slice), int(ldx), int(ldy), int(dtype), _stream(stream)))
+
+
+NTP_NOALLOC_SCRATCH_BYTES = 8 << 20
+
+
+def ntp_aggregate_fwd_noalloc(g: Graph, X, Y, f_slice, ldx, ldy, dtype=NTP_F32, stream=None):
+    _check(lib().ntp_aggregate_fwd_noalloc(g.handle, _ptr(X), _ptr(Y), int(f_slice), int(ldx), int(ldy), int(dtype), _stream(stream)))
 
 
 def ntp_aggregate_bwd(g: Graph, Gout, Gin, f_slice, ldg_out, ldg_in, dtype=NTP_F32, stream=None):

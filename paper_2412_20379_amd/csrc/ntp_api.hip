@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 
 #include "ntp_internal.h"
@@ -66,7 +67,33 @@ struct ntp_graph {
     const Form& f(int which) const { return form[(which == NTP_CSC && !g.symmetric && g.has_csc) ? 1 : 0]; }
 };
 
+// Scratch of ntp_aggregate_fwd_noalloc: partial sums of split rows, in the library's own image
+// (every GPU the library is loaded on holds its own copy until the process ends).  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+// (No `used` attribute: with it the symbol stays local to the code object and the look-up aborts;
+// the host-side reference alone makes the compiler export it.)
+static __device__ __align__(256) float scratch[NTP_NOALLOC_SCRATCH_BYTES / sizeof(float)];
+
 namespace {
+
+// device address of `scratch` on the current device, resolved once per device
+int static_scratch(float** out) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static float* ptr[MAX_DEVICES] = {nullptr};
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) { set_error("device ordinal %d outside 0..%d", dev, MAX_DEVICES - 1); return NTP_EUNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { set_error("hipGetSymbolAddress returned no address for the static scratch"); return NTP_EHIP; }
+        ptr[dev] = static_cast<float*>(p);
+    }
+    *out = ptr[dev];
+    return NTP_OK;
+}
 
 void* alloc_plain(size_t bytes, void*) { return malloc(bytes); }
 void* alloc_pinned(size_t bytes, void*) {
@@ -431,6 +458,9 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
         }
         const hipError_t se = hipDeviceSynchronize();
         if (se != hipSuccess) { set_error("hipDeviceSynchronize failed: %s", hipGetErrorString(se)); return NTP_EHIP; }
+        float* unused = nullptr;            // resolve the static scratch of this device at set-up
+        rc = static_scratch(&unused);
+        if (rc != NTP_OK) return rc;
     }
     *out = guard.release();
     return NTP_OK;
@@ -517,9 +547,10 @@ int ntp_graph_device_bytes(const ntp_graph_t* g, int64_t* bytes) {
     return NTP_OK;
 }
 
+// static_partial: run on the library's static scratch instead of the handle's (no allocation)
 static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y, int64_t f,
                               int64_t ldx, int64_t ldy, int dtype, void* stream, const float* weights = nullptr,
-                              const int32_t* columns = nullptr) {
+                              const int32_t* columns = nullptr, bool static_partial = false) {
     int rc = check_agg_args(g, X, Y, f, ldx, ldy, dtype);
     if (rc != NTP_OK) return rc;
     Form& F = g->f(which);
@@ -527,20 +558,38 @@ static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y,
     if (scatter && dtype != NTP_F32) { set_error("the scatter backward (NTP_SCATTER_BWD) takes fp32 buffers only"); return NTP_EUNSUPPORTED; }
     if (!F.all_resident) { set_error("topology is not fully device-resident: use ntp_chunked_aggregate"); return NTP_EBUDGET; }
     if (g->g.n == 0) return NTP_OK;
-    if (scatter) rc = launch_zero_rows(Y, g->g.n, f, ldy, dtype, stream);
-    else rc = ensure_partial(g, F, f);
+    float* partial = nullptr;
+    if (static_partial) {
+        const size_t need = partial_floats(F, f) * sizeof(float);
+        if (need > (size_t)NTP_NOALLOC_SCRATCH_BYTES) {
+            set_error("the split rows of this graph need %zu bytes of partial sums at width %lld: more than the %lld-byte static scratch "
+                      "(use ntp_aggregate_fwd)", need, (long long)f, (long long)NTP_NOALLOC_SCRATCH_BYTES);
+            return NTP_EUNSUPPORTED;
+        }
+        rc = static_scratch(&partial);
+    } else if (scatter) {
+        rc = launch_zero_rows(Y, g->g.n, f, ldy, dtype, stream);
+    } else {
+        rc = ensure_partial(g, F, f);
+        partial = g->partial;
+    }
     if (rc != NTP_OK) return rc;
     for (auto& c : F.plan.chunks) {
-        rc = run_chunk(c, c.d_image, X, Y, g->partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights, columns, F.one_reduce());
+        rc = run_chunk(c, c.d_image, X, Y, partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights, columns, F.one_reduce());
         if (rc != NTP_OK) return rc;
     }
-    if (!scatter && F.one_reduce()) return reduce_all(F, g->partial, Y, f, ldy, dtype, (hipStream_t)stream);
+    if (!scatter && F.one_reduce()) return reduce_all(F, partial, Y, f, ldy, dtype, (hipStream_t)stream);
     return NTP_OK;
 }
 
 int ntp_aggregate_fwd(ntp_graph_t* g, const void* X, void* Y, int64_t f, int64_t ldx, int64_t ldy,
                       int dtype, void* stream) {
     return aggregate_resident(g, NTP_CSR, X, Y, f, ldx, ldy, dtype, stream);
+}
+
+int ntp_aggregate_fwd_noalloc(ntp_graph_t* g, const void* X, void* Y, int64_t f, int64_t ldx, int64_t ldy,
+                              int dtype, void* stream) {
+    return aggregate_resident(g, NTP_CSR, X, Y, f, ldx, ldy, dtype, stream, nullptr, nullptr, true);
 }
 
 int ntp_aggregate_bwd(ntp_graph_t* g, const void* Gout, void* Gin, int64_t f, int64_t ldo, int64_t ldi,
