@@ -7,9 +7,17 @@ A step is one pass of the whole hot path over one synthetic workload:
   configs 3, 4 : one worker's share of an epoch: the slice aggregations (forward and
                  backward) at F_slice = width / 8 on the full graph, and the transforms on
                  ceil(N / 8) vertices at full width.
+  config 5     : the same share with the topology cut into chunks under the config's device
+                 budget (ntp_chunked_aggregate).
 Prints ONE JSON line.  `value` is aggregation GEPS over the whole step: stored entries of
 A_hat (self loops included) x slice width, summed over the step's aggregation calls,
 divided by the step time (transforms included in the time).
+
+Without --config the line is that of config 3 (the power-law graph the bandwidth target is
+stated on) and carries a `configs` object with the same measurements of config 4 (fp32 and
+bf16 slices), config 2, config 5's shape at one eighth of its size, and config 5 itself when
+the host has the memory for it (75 GB) and its projected time fits --time-budget - else a
+`skipped` note with the reason.
 """
 from __future__ import annotations
 
@@ -48,12 +56,437 @@ def line_padded_ld(f, elem=4):
     return -(-f // per_line) * per_line if f >= per_line else -(-f // per_vec) * per_vec
 
 
+def copy_probe(torch, dev):
+    """a plain 1 GiB device copy: what the memory system delivers to a streaming kernel (read +
+    write), the practical ceiling beside the 8 TB/s nominal one"""
+    a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    b = torch.empty_like(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    b.copy_(a)
+    e0.record()
+    for _ in range(5):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    gbs = 5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    log("copy probe: 1 GiB read + 1 GiB written per copy, %.1f GB/s" % gbs)
+    return gbs
+
+
+def profile_traffic(key):
+    """L2-boundary bytes per launch of the aggregation kernel as counted in an earlier rocprofv3
+    run (profiles/traffic.json): not measured by this process, so it comes with the commit and
+    the kernel it was counted at"""
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        t = json.load(open(tfile))
+    except Exception:
+        return None, None
+    e = t.get(key)
+    if isinstance(e, dict):
+        return e.get("bytes"), {"from_profile": e.get("profile"), "counted_at_commit": e.get("commit"), "kernel": e.get("kernel")}
+    return None, None
+
+
+def step_bench(args, cfg, scale_down=1, agg_dtype="f32", copy_gbs=None, graph=None, cpu_seconds=20.0, context=True):
+    """One config's step, timed: returns (the JSON object of that config, (n, src, dst) for reuse)."""
+    import numpy as np
+    import torch
+    import ntp_inputs as gen
+    import paper_2412_20379_amd as ntp
+    from paper_2412_20379_amd.gcn import GcnEpoch
+    from paper_2412_20379_amd.tp import TensorParallelEpoch
+
+    dev = "cuda:0"
+    spec = gen.CONFIGS[cfg]
+    t0 = time.time()
+    if graph is None:
+        graph = gen.make_graph(cfg, args.seed, scale_down, permute=not args.unpermuted)
+    n, src, dst = graph
+    t_gen = time.time() - t0
+    log("config %d%s: %d undirected edges on %d vertices (generated in %.1fs)"
+        % (cfg, "" if scale_down == 1 else " / %d" % scale_down, src.size, n, t_gen))
+    t0 = time.time()
+    use_chunked = cfg == 5       # the config's device budget and chunk size apply
+    if use_chunked:
+        g = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=spec.device_budget_bytes // scale_down,
+                                chunk_edges=max(1024, spec.chunk_edges // scale_down))
+    else:
+        g = ntp.ntp_graph_build(n, src, dst)
+    t_build = time.time() - t0
+    info = ntp.ntp_graph_info(g)
+    nnz = info["nnz"]
+    log("config %d: n=%d nnz=%d max_degree=%d chunks=%d (graph build %.2fs)" % (cfg, n, nnz, info["max_degree"], info["n_chunks"], t_build))
+
+    dims = spec.layers
+    L = len(dims) - 1
+    f32 = dict(dtype=torch.float32, device=dev)
+    events = []
+    full_model = cfg in (1, 2) or args.full_width
+    share_bf16 = agg_dtype == "bf16" and not full_model
+    X = Ws = labels = None
+
+    if full_model:
+        X = torch.from_numpy(gen.make_features(cfg, dims[0], args.seed, scale_down)).to(dev)
+        Ws = [torch.from_numpy(gen.glorot_weight(dims[i], dims[i + 1], args.seed, i)).to(dev) for i in range(L)]
+        labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)).to(dev)
+        ep = GcnEpoch(g, n, dims, order=args.order)
+
+        def step():
+            ep.run(X, Ws, labels)
+
+        def set_events(lst):
+            ep.events = lst
+        if args.order == "decoupled":
+            edge_feats = nnz * dims[-1] * 2 * L
+        else:       # per layer: aggregation at the input width, or at the output width when transform-first
+            tf = ep.transform_first
+            fwd_w = sum(dims[l + 1] if tf[l] else dims[l] for l in range(L))
+            bwd_w = sum(dims[l + 1] if tf[l] else (dims[l] if l > 0 else 0) for l in range(L))
+            edge_feats = nnz * (fwd_w + bwd_w)
+        flops_nn = sum(2 * n * dims[i] * dims[i + 1] * (3 if i > 0 else 2) for i in range(L))
+        workload = "%s: %s GCN epoch fwd+bwd, %s, full width" % (spec.name, args.order, "->".join(map(str, dims)))
+    else:
+        # one worker's share (1 of 8): slice aggregations on the full graph, transforms on N/8 rows
+        W8 = spec.n_workers
+        slices = [-(-dims[l] // W8) for l in range(L)]          # ceil(width / 8) per layer input
+        n_share = -(-n // W8)
+        edge_feats = nnz * (sum(slices) + sum(slices[1:]))
+        flops_nn = sum(2 * n_share * dims[i] * dims[i + 1] * (3 if i > 0 else 2) for i in range(L))
+        workload = ("%s%s: one worker's share (1/%d) of a %s epoch: slice aggregations F=%s fwd+bwd on the full graph, "
+                    "transforms on %d rows" % (spec.name, "" if scale_down == 1 else " at 1/%d size" % scale_down, W8,
+                                               "->".join(map(str, dims)), slices, n_share))
+        if not share_bf16 and not use_chunked:
+            # fp32 on a resident graph: all eight workers run once on seeded inputs (the full model's
+            # epoch: the buffers then hold real activations and gradients), and the timed step is
+            # worker 0's calls on them
+            X = torch.empty(n, dims[0], **f32)
+            tg = torch.Generator(device=dev)
+            tg.manual_seed(args.seed)
+            X.normal_(generator=tg)
+            Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev) for l in range(L)]
+            labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)).to(dev)
+            tp = TensorParallelEpoch(g, n, dims, workers=W8)
+            tp.run(X, Ws, labels)
+            torch.cuda.synchronize()
+            log("config %d: all %d workers ran once, loss %.5f; timing worker 0's calls" % (cfg, W8, float(tp.loss)))
+
+            def step():
+                tp.run_worker(0)
+
+            def set_events(lst):
+                tp.events = lst
+            workload += "; operands: the activations and gradients of a full 8-worker epoch"
+        else:
+            # bf16 slices, and config 5 (whose full-width matrices do not fit beside the topology):
+            # timing only, on seeded random operands of the share's shapes
+            tg = torch.Generator(device=dev)
+            tg.manual_seed(args.seed)
+            code_s = ntp.NTP_BF16 if share_bf16 else ntp.NTP_F32
+            tdt = torch.bfloat16 if share_bf16 else torch.float32
+            lds = [line_padded_ld(s_, 2 if share_bf16 else 4) for s_ in slices]
+            xs = [torch.randn(n, ld, generator=tg, **f32).to(tdt) for ld in lds]
+            ys = [torch.empty_like(x) for x in xs]
+            A = [torch.randn(n_share, dims[l], generator=tg, **f32).to(tdt) for l in range(L)]
+            Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev).to(tdt) for l in range(L)]
+            H = [torch.empty(n_share, dims[l + 1], dtype=tdt, device=dev) for l in range(L)]
+            dH = [torch.randn(n_share, dims[l + 1], generator=tg, **f32).to(tdt) for l in range(L)]
+            dA = [torch.empty(n_share, dims[l], dtype=tdt, device=dev) for l in range(L)]
+            dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
+            wsb = max(ntp.ntp_nn_bwd_workspace_bytes(n_share, dims[l], dims[l + 1]) for l in range(L))
+            ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device=dev)
+            holder = {"ev": None}
+            copy_stream = torch.cuda.Stream() if use_chunked else None
+
+            def agg_fwd(gr, xi, yo, s_, ldx, ldy, code, st):
+                if use_chunked:
+                    ntp.ntp_chunked_aggregate(gr, ntp.NTP_FWD, xi, yo, s_, ldx, ldy, code, st, copy_stream)
+                else:
+                    ntp.ntp_aggregate_fwd(gr, xi, yo, s_, ldx, ldy, code, st)
+
+            def agg_bwd(gr, xi, yo, s_, ldx, ldy, code, st):
+                if use_chunked:
+                    ntp.ntp_chunked_aggregate(gr, ntp.NTP_BWD, xi, yo, s_, ldx, ldy, code, st, copy_stream)
+                else:
+                    ntp.ntp_aggregate_bwd(gr, xi, yo, s_, ldx, ldy, code, st)
+
+            def timed(tag, fn, *a):
+                if holder["ev"] is None:
+                    return fn(*a)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn(*a)
+                e1.record()
+                holder["ev"].append((tag, e0, e1))
+
+            def step():
+                st = torch.cuda.current_stream()
+                for l in range(L):
+                    s_ = slices[l]
+                    timed("agg_fwd f=%d" % s_, agg_fwd, g, xs[l], ys[l], s_, lds[l], lds[l], code_s, st)
+                    act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+                    timed("nn_fwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_fwd, A[l], Ws[l], H[l], n_share, dims[l], dims[l + 1], act, code_s, st)
+                for l in range(L - 1, -1, -1):
+                    act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
+                    timed("nn_bwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_bwd, A[l], Ws[l], H[l], dH[l], dA[l] if l > 0 else None, dW[l],
+                          n_share, dims[l], dims[l + 1], act, code_s, ws, wsb, st)
+                    if l > 0:
+                        s_ = slices[l]
+                        timed("agg_bwd f=%d" % s_, agg_bwd, g, ys[l], xs[l], s_, lds[l], lds[l], code_s, st)
+
+            def set_events(lst):
+                holder["ev"] = lst
+            workload += "; operands: seeded random matrices of the share's shapes"
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # Every eighth step of the timed region records a pair of HIP events around each library call
+    # (the per-call durations below); the pairs cost about 6 us per call, which over all steps
+    # would be 5-6 % of a config-2 epoch.
+    every = 8
+    n_instrumented = 0
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        instrument = i % every == 0
+        set_events(events if instrument else None)
+        n_instrumented += instrument
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    set_events(None)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    geps = edge_feats / (ms_per_step * 1e-3) / 1e9
+
+    # per-call durations from the HIP events recorded inside the timed region
+    per = {}
+    for tag, e0, e1 in events:
+        per.setdefault(tag, []).append(e0.elapsed_time(e1))
+    calls = {k: dict(n=len(v), avg_ms=float(np.mean(v)), min_ms=float(np.min(v))) for k, v in per.items()}
+    agg_ms = sum(np.sum(v) for k, v in per.items() if k.startswith("agg")) / n_instrumented
+    nn_ms = sum(np.sum(v) for k, v in per.items() if k.startswith("nn")) / n_instrumented
+
+    # roofline of the dominant aggregation kernel: the width with the largest share of step time
+    agg_tags = [k for k in per if k.startswith("agg")]
+    by_width = {}
+    for k in agg_tags:
+        f = int(k.split("f=")[1])
+        by_width.setdefault(f, []).extend(per[k])
+    fdom = max(by_width, key=lambda f: np.sum(by_width[f]))
+    dur_ms = float(np.mean(by_width[fdom]))
+    dtype_label = "bf16" if share_bf16 else "f32"
+    balg = agg_bytes(n, nnz, fdom, 2 if share_bf16 else 4)
+    achieved = balg / (dur_ms * 1e-3) / 1e9
+    traffic, traffic_source = (profile_traffic("cfg%d_f%d%s" % (cfg, fdom, "_bf16" if share_bf16 else ""))
+                               if scale_down == 1 and not args.unpermuted else (None, None))
+    roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, %s)" % (fdom, "bf16" if share_bf16 else "fp32"), achieved=achieved, peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=traffic,
+                    # `traffic` is not counted by this run: it is the L2-boundary byte count (reads that
+                    # miss the L2, Infinity-Cache hits included, plus writes) of an earlier rocprofv3 run
+                    traffic_source=traffic_source,
+                    algorithmic_bytes_per_launch=balg, avg_launch_ms=dur_ms,
+                    traffic_gbs=(traffic / (dur_ms * 1e-3) / 1e9) if traffic else None,
+                    overfetch=(traffic / balg) if traffic else None,
+                    # the algorithmic rate against a plain device copy measured in this run
+                    copy_gbs=copy_gbs, frac_of_copy=(achieved / copy_gbs) if copy_gbs else None,
+                    geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
+    nn_tflops = flops_nn / (nn_ms * 1e-3) / 1e12 if nn_ms > 0 else None
+    split_core = not os.environ.get("NTP_NN_CORE", "").startswith("f")
+    nn_peak = SPLIT_PEAK_TFLOPS if split_core else FP32_MFMA_PEAK_TFLOPS
+    if share_bf16:
+        nn_peak = BF16_MFMA_PEAK_TFLOPS       # bf16 operands: one bf16 matrix instruction per product
+    roofline_nn = dict(bound="mfma",
+                       kernel=("gemm_split_kernel (fp32 products from bf16 pieces, 6 bf16 MFMA per product; "
+                               "peak = 2500/6) + gemm_kernel (fp32 MFMA) for narrow products, all transform calls of a step"
+                               if split_core else "gemm_kernel (fp32 MFMA, all transform calls of a step)"),
+                       achieved=nn_tflops, peak=nn_peak, unit="TFLOP/s (useful fp32 flops)",
+                       frac=(nn_tflops / nn_peak) if nn_tflops else None,
+                       frac_of_fp32_mfma_peak=(nn_tflops / FP32_MFMA_PEAK_TFLOPS) if nn_tflops else None, traffic=None)
+
+    # context, outside the timed region: the same model in the paper's decoupled order
+    # (all transforms first, then L aggregations at the output width, Section 4.1)
+    other_order_ms = None
+    reordered_ms = None
+    overlap_ms = None
+    if context and cfg in (1, 2) and args.order == "layerwise" and not args.full_width and not args.no_context:
+        def epoch_ms(**kw):
+            e = GcnEpoch(g, n, dims, **kw)
+            for _ in range(3):
+                e.run(X, Ws, labels)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            for _ in range(args.steps):
+                e.run(X, Ws, labels)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t2) * 1e3 / args.steps
+        other_order_ms = epoch_ms(order="decoupled")
+        # the layer-wise epoch with its last layer evaluated as A_hat (H W)
+        reordered_ms = epoch_ms(order="reordered")
+        # and with every dW issued on a second stream beside dA and the backward aggregation that follows it
+        overlap_ms = epoch_ms(order="layerwise", overlap_dw=True)
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.time()
+        fo = fdom
+        # the oracle's rate on this graph is some 10 G edge-features/s on 16 cores: bound the sample
+        # to about cpu_seconds / 3 per repetition (three repetitions, the best one counts)
+        budget_ef = 3e9 * cpu_seconds / 20.0
+        xo = gen.normal_features(n, fo, args.seed)
+        if nnz * fo <= budget_ef and nnz <= 2e8:
+            og = oracle.build_graph(n, src, dst)
+            m = og.csr
+            done = og.nnz * fo
+            sample = "one forward aggregation of the whole graph at F_slice=%d" % fo
+        else:
+            # a uniform sample of rows, built one by one from the edge list
+            og = None
+            k = max(1000, int(n * budget_ef / (nnz * fo)))
+            rows = np.sort(gen.stream_rng(args.seed, 99).choice(n, size=min(k, n), replace=False)).astype(np.int64)
+            m = oracle.rows_from_undirected_edges(n, src, dst, rows)
+            done = m.nnz * fo
+            sample = "forward aggregation of %d uniformly sampled rows (%d entries) at F_slice=%d" % (rows.size, m.nnz, fo)
+        best = None
+        for _ in range(3):
+            t1 = time.perf_counter()
+            oracle.aggregate(m, xo)
+            dt = time.perf_counter() - t1
+            best = dt if best is None else min(best, dt)
+        cpu_baseline = dict(value=done / best / 1e9, unit="GEPS", cores=oracle.num_threads(), kind="oracle",
+                            sample=sample + ", fp64, best of 3 (%.3fs)" % best)
+        if cfg <= 2 and og is not None:        # small enough to time on one core as well
+            all_cores = oracle.num_threads()
+            oracle.set_num_threads(1)
+            t1 = time.perf_counter()
+            oracle.aggregate(m, xo)
+            cpu_baseline["single_core_value"] = done / (time.perf_counter() - t1) / 1e9
+            oracle.set_num_threads(all_cores)
+            if args.order == "layerwise" and not args.full_width and context:
+                # the same step as `value` (one whole layer-wise epoch: every aggregation and every
+                # transform, fp64) through the oracle, and its rate by the same definition
+                Xo = gen.make_features(cfg, dims[0], args.seed, scale_down)
+                Wo = [gen.glorot_weight(dims[i], dims[i + 1], args.seed, i) for i in range(L)]
+                lo = gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)
+                t1 = time.perf_counter()
+                oracle.epoch_layerwise(og, Xo, Wo, lo)
+                dt = time.perf_counter() - t1
+                cpu_baseline["epoch_s"] = dt
+                cpu_baseline["epoch_value"] = edge_feats / dt / 1e9
+                cpu_baseline["sample"] += "; epoch_value: one whole layer-wise epoch of the same model (%.2fs)" % dt
+        log("oracle baseline: %.2f GEPS on %d threads (%.1fs incl. building the rows)" % (cpu_baseline["value"], cpu_baseline["cores"], time.time() - t0))
+
+    # arithmetic type of the step: fp32 storage and accumulation; the transforms form every fp32
+    # product from three bf16 pieces per operand on the bf16 matrix instructions (as accurate as fp32
+    # arithmetic; narrow products use the fp32 matrix instructions)
+    dtype_full = "bf16 (fp32 accumulate)" if share_bf16 else ("f32 (transform: 3x bf16-split MFMA)" if split_core else "f32")
+    out = {
+        "metric": "aggregation GEPS (stored entries x F_slice / s) over the step; epoch ms in ms_per_step",
+        "value": geps, "unit": "GEPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype_full, "data": "synthetic",
+        "config": {"workload": workload, "n_vertices": n, "nnz": nnz, "max_degree": info["max_degree"],
+                   "seed": args.seed, "scale_down": scale_down,
+                   "vertex_ids": "generator order" if args.unpermuted else "random relabelling"},
+        "roofline": roofline, "roofline_nn": roofline_nn, "cpu_baseline": cpu_baseline,
+        "agg_ms_per_step": float(agg_ms), "nn_ms_per_step": float(nn_ms),
+        "agg_geps_calls_only": edge_feats / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else None,
+        "calls": calls, "instrumented_steps": n_instrumented, "graph_build_s": t_build, "graph_generate_s": t_gen,
+    }
+    if other_order_ms is not None:
+        out.update(epoch_ms_decoupled_order=other_order_ms, epoch_ms_dw_on_second_stream=overlap_ms, epoch_ms_last_layer_reordered=reordered_ms)
+    if use_chunked:
+        res = ntp.ntp_graph_chunks(g)["resident"]
+        out["chunks"] = {"n": int(res.size), "resident": int(res.sum()), "device_budget_bytes": spec.device_budget_bytes // scale_down,
+                         "chunk_edges": max(1024, spec.chunk_edges // scale_down), "streamed_bytes_per_pass": ntp.ntp_graph_stream_bytes(g)}
+    log("config %d%s %s: %.3f ms per step, %.0f GEPS; dominant aggregation F=%d %.3f ms = %.0f GB/s algorithmic = %.3f of 8 TB/s"
+        % (cfg, "" if scale_down == 1 else " / %d" % scale_down, dtype_label, ms_per_step, geps, fdom, dur_ms, achieved, achieved / HBM_PEAK_GBS))
+    g.close()
+    return out, graph
+
+
+def host_mem_available_gb():
+    try:
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemAvailable:"):
+                return int(line.split()[1]) / 1e6
+    except Exception:
+        pass
+    return None
+
+
+def run_step_mode(args):
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(3)
+    t_start = time.time()
+    copy_gbs = copy_probe(torch, "cuda:0")
+    if args.config is not None:
+        out, _ = step_bench(args, args.config, args.scale_down, args.agg_dtype, copy_gbs)
+        print(json.dumps(out), flush=True)
+        return
+    # default: config 3 is the line; the other configs ride along as sub-entries, each with its own
+    # roofline and oracle baseline.  A sub-entry that fails is reported, not fatal.
+    head, _ = step_bench(args, 3, 1, "f32", copy_gbs, cpu_seconds=20.0)
+    subs = {}
+
+    def sub(key, fn):
+        try:
+            t0 = time.time()
+            torch.cuda.empty_cache()
+            subs[key] = fn()
+            subs[key]["wall_s"] = time.time() - t0
+        except Exception as e:          # never lose the headline to a sub-entry
+            log("bench.py: %s failed: %r" % (key, e))
+            subs[key] = {"failed": repr(e)[:300]}
+
+    keep = {}
+
+    def cfg4_f32():
+        o, keep["g4"] = step_bench(args, 4, 1, "f32", copy_gbs, cpu_seconds=6.0)
+        return o
+    sub("cfg4_f32", cfg4_f32)
+    sub("cfg4_bf16", lambda: step_bench(args, 4, 1, "bf16", copy_gbs, graph=keep.get("g4"), cpu_seconds=6.0)[0])
+    keep.clear()
+    sub("cfg2", lambda: step_bench(args, 2, 1, "f32", copy_gbs, cpu_seconds=6.0, context=False)[0])
+    if not args.no_scaled_config5:
+        sub("cfg5_at_one_eighth", lambda: step_bench(args, 5, 8, "f32", copy_gbs, cpu_seconds=6.0)[0])
+    # config 5 at full size: 75 GB of host memory, and host work (generation, graph build) that is
+    # eight times that of the 1/8 instance: only if memory and the time budget allow
+    mem = host_mem_available_gb()
+    eighth = subs.get("cfg5_at_one_eighth", {})
+    projected = 8 * (eighth.get("graph_generate_s", 30.0) + eighth.get("graph_build_s", 30.0)) + 60.0
+    elapsed = time.time() - t_start
+    if args.no_config5:
+        subs["cfg5"] = {"skipped": "--no-config5"}
+    elif mem is not None and mem < 100:
+        subs["cfg5"] = {"skipped": "%.0f GB of host memory available, config 5 needs 100" % mem}
+    elif not args.with_config5 and elapsed + projected > args.time_budget:
+        subs["cfg5"] = {"skipped": "projected %.0f s on top of %.0f s already spent exceeds the time budget of %.0f s (--with-config5 runs it anyway)"
+                                   % (projected, elapsed, args.time_budget)}
+    else:
+        log("config 5 at full size: projected %.0f s, %.0f s spent so far" % (projected, elapsed))
+        sub("cfg5", lambda: step_bench(args, 5, 1, "f32", copy_gbs, cpu_seconds=6.0)[0])
+    head["configs"] = subs
+    head["bench_wall_s"] = time.time() - t_start
+    print(json.dumps(head), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=None, choices=[1, 2, 3, 4, 5],
+                    help="one config only (default: config 3 as the headline plus the other configs as sub-entries)")
+    ap.add_argument("--with-config5", action="store_true",
+                    help="default run: time config 5 at full size whatever the time budget says")
+    ap.add_argument("--no-config5", action="store_true", help="default run: leave out config 5 at full size")
+    ap.add_argument("--time-budget", type=float, default=480.0,
+                    help="default run: seconds the whole run may take; config 5 at full size (75 GB of host memory) runs only if "
+                         "its projected time fits")
+    ap.add_argument("--no-scaled-config5", action="store_true", help="default run: leave out config 5's shape at 1/8 size")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--scale-down", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -82,18 +515,22 @@ def main():
             "use --gpus 1.  value is the one GPU's throughput.")
         sys.exit(2)
 
+    if args.mode == "step":
+        return run_step_mode(args)
+    if args.config is None:
+        args.config = 2
+
     import numpy as np
     import torch
     import ntp_inputs as gen
     import paper_2412_20379_amd as ntp
-    from paper_2412_20379_amd.gcn import GcnEpoch
 
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible; the HIP path has no CPU fallback")
         sys.exit(3)
     dev = "cuda:0"
     spec = gen.CONFIGS[args.config]
-    if args.config == 5 and args.mode not in ("budget", "step"):
+    if args.config == 5 and args.mode != "budget":
         log("bench.py: config 5 runs under its device budget: use --mode budget or --mode step")
         sys.exit(2)
     t0 = time.time()
@@ -184,34 +621,14 @@ def main():
         return
 
     t0 = time.time()
-    use_chunked = args.config == 5       # the config's device budget and chunk size apply
-    if use_chunked:
-        g = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=spec.device_budget_bytes // args.scale_down,
-                                chunk_edges=max(1024, spec.chunk_edges // args.scale_down))
-    else:
-        g = ntp.ntp_graph_build(n, src, dst)
+    g = ntp.ntp_graph_build(n, src, dst)
     t_build = time.time() - t0
     info = ntp.ntp_graph_info(g)
     nnz = info["nnz"]
     log("config %d: n=%d nnz=%d max_degree=%d (generated in %.1fs, graph build %.2fs)"
         % (args.config, n, nnz, info["max_degree"], t_gen, t_build))
-
-    copy_gbs = None
-    if args.copy_probe or args.mode == "step":
-        # a plain 1 GiB device copy: what the memory system delivers to a streaming kernel (read +
-        # write), the practical ceiling beside the 8 TB/s nominal one
-        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        b = torch.empty_like(a)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        b.copy_(a)
-        e0.record()
-        for _ in range(5):
-            b.copy_(a)
-        e1.record()
-        torch.cuda.synchronize()
-        copy_gbs = 5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        log("copy probe: 1 GiB read + 1 GiB written per copy, %.1f GB/s" % copy_gbs)
-        del a, b
+    if args.copy_probe:
+        copy_probe(torch, dev)
 
     if args.mode == "chunk":
         # Section 4.2.1 schedule: in-memory call vs chunked call with every chunk resident, with
@@ -516,280 +933,6 @@ def main():
                           "results": res}), flush=True)
         g.close()
         return
-
-    dims = spec.layers
-    L = len(dims) - 1
-    f32 = dict(dtype=torch.float32, device=dev)
-    events = []
-    edge_feats = 0            # stored entries x width, summed over aggregation calls of a step
-    flops_nn = 0
-
-    if args.config in (1, 2) or args.full_width:
-        X = torch.from_numpy(gen.make_features(args.config, dims[0], args.seed, args.scale_down)).to(dev)
-        Ws = [torch.from_numpy(gen.glorot_weight(dims[i], dims[i + 1], args.seed, i)).to(dev) for i in range(L)]
-        labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)).to(dev)
-        ep = GcnEpoch(g, n, dims, order=args.order)
-
-        def step():
-            ep.run(X, Ws, labels)
-
-        def set_events(lst):
-            ep.events = lst
-        if args.order == "decoupled":
-            edge_feats = nnz * dims[-1] * 2 * L
-        else:       # per layer: aggregation at the input width, or at the output width when transform-first
-            tf = ep.transform_first
-            fwd_w = sum(dims[l + 1] if tf[l] else dims[l] for l in range(L))
-            bwd_w = sum(dims[l + 1] if tf[l] else (dims[l] if l > 0 else 0) for l in range(L))
-            edge_feats = nnz * (fwd_w + bwd_w)
-        flops_nn = sum(2 * n * dims[i] * dims[i + 1] * (3 if i > 0 else 2) for i in range(L))
-        workload = "%s: %s GCN epoch fwd+bwd, %s, full width" % (spec.name, args.order, "->".join(map(str, dims)))
-    else:
-        # one worker's share (1 of 8): slice aggregations on the full graph, transforms on N/8 rows
-        W8 = spec.n_workers
-        slices = [-(-dims[l] // W8) for l in range(L)]          # ceil(width / 8) per layer input
-        n_share = -(-n // W8)
-        # timing only: the big dense operands are drawn on the device (seeded)
-        tg = torch.Generator(device=dev)
-        tg.manual_seed(args.seed)
-        # slice rows start on 128-byte lines when they are at least one line wide (the aggregation
-        # then walks the columns line by line), else on 16-byte vectors
-        # --agg-dtype bf16: the bf16 feature variant (features, activations and their gradients in
-        # bf16; weights' gradients and all accumulation in fp32)
-        share_bf16 = args.agg_dtype == "bf16"
-        code_s = ntp.NTP_BF16 if share_bf16 else ntp.NTP_F32
-        tdt = torch.bfloat16 if share_bf16 else torch.float32
-        lds = [line_padded_ld(s, 2 if share_bf16 else 4) for s in slices]
-        xs = [torch.randn(n, ld, generator=tg, **f32).to(tdt) for ld in lds]
-        ys = [torch.empty_like(x) for x in xs]
-        A = [torch.randn(n_share, dims[l], generator=tg, **f32).to(tdt) for l in range(L)]
-        Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev).to(tdt) for l in range(L)]
-        H = [torch.empty(n_share, dims[l + 1], dtype=tdt, device=dev) for l in range(L)]
-        dH = [torch.randn(n_share, dims[l + 1], generator=tg, **f32).to(tdt) for l in range(L)]
-        dA = [torch.empty(n_share, dims[l], dtype=tdt, device=dev) for l in range(L)]
-        dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
-        wsb = max(ntp.ntp_nn_bwd_workspace_bytes(n_share, dims[l], dims[l + 1]) for l in range(L))
-        ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device=dev)
-        holder = {"ev": None}
-        copy_stream = torch.cuda.Stream() if use_chunked else None
-
-        def agg_fwd(gr, xi, yo, s, ldx, ldy, code, st):
-            if use_chunked:
-                ntp.ntp_chunked_aggregate(gr, ntp.NTP_FWD, xi, yo, s, ldx, ldy, code, st, copy_stream)
-            else:
-                ntp.ntp_aggregate_fwd(gr, xi, yo, s, ldx, ldy, code, st)
-
-        def agg_bwd(gr, xi, yo, s, ldx, ldy, code, st):
-            if use_chunked:
-                ntp.ntp_chunked_aggregate(gr, ntp.NTP_BWD, xi, yo, s, ldx, ldy, code, st, copy_stream)
-            else:
-                ntp.ntp_aggregate_bwd(gr, xi, yo, s, ldx, ldy, code, st)
-
-        def timed(tag, fn, *a):
-            if holder["ev"] is None:
-                return fn(*a)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            fn(*a)
-            e1.record()
-            holder["ev"].append((tag, e0, e1))
-
-        def step():
-            st = torch.cuda.current_stream()
-            for l in range(L):
-                s = slices[l]
-                timed("agg_fwd f=%d" % s, agg_fwd, g, xs[l], ys[l], s, lds[l], lds[l], code_s, st)
-                act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
-                timed("nn_fwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_fwd, A[l], Ws[l], H[l], n_share, dims[l], dims[l + 1], act, code_s, st)
-            for l in range(L - 1, -1, -1):
-                act = ntp.NTP_ACT_RELU if l < L - 1 else ntp.NTP_ACT_NONE
-                timed("nn_bwd %dx%d" % (dims[l], dims[l + 1]), ntp.ntp_nn_bwd, A[l], Ws[l], H[l], dH[l], dA[l] if l > 0 else None, dW[l],
-                      n_share, dims[l], dims[l + 1], act, code_s, ws, wsb, st)
-                if l > 0:
-                    s = slices[l]
-                    timed("agg_bwd f=%d" % s, agg_bwd, g, ys[l], xs[l], s, lds[l], lds[l], code_s, st)
-
-        def set_events(lst):
-            holder["ev"] = lst
-        edge_feats = nnz * (sum(slices) + sum(slices[1:]))
-        flops_nn = sum(2 * n_share * dims[i] * dims[i + 1] * (3 if i > 0 else 2) for i in range(L))
-        workload = ("%s: one worker's share (1/%d) of a %s epoch: slice aggregations F=%s fwd+bwd on the full graph, "
-                    "transforms on %d rows" % (spec.name, W8, "->".join(map(str, dims)), slices, n_share))
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # Every eighth step of the timed region records a pair of HIP events around each library call
-    # (the per-call durations below); the pairs cost about 6 us per call, which over all steps
-    # would be 5-6 % of a config-2 epoch.
-    every = 8
-    n_instrumented = 0
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        instrument = i % every == 0
-        set_events(events if instrument else None)
-        n_instrumented += instrument
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    set_events(None)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    geps = edge_feats / (ms_per_step * 1e-3) / 1e9
-
-    # per-call durations from the HIP events recorded inside the timed region
-    per = {}
-    for tag, e0, e1 in events:
-        per.setdefault(tag, []).append(e0.elapsed_time(e1))
-    calls = {k: dict(n=len(v), avg_ms=float(np.mean(v)), min_ms=float(np.min(v))) for k, v in per.items()}
-    agg_ms = sum(np.sum(v) for k, v in per.items() if k.startswith("agg")) / n_instrumented
-    nn_ms = sum(np.sum(v) for k, v in per.items() if k.startswith("nn")) / n_instrumented
-
-    # roofline of the dominant aggregation kernel: the width with the largest share of step time
-    agg_tags = [k for k in per if k.startswith("agg")]
-    by_width = {}
-    for k in agg_tags:
-        f = int(k.split("f=")[1])
-        by_width.setdefault(f, []).extend(per[k])
-    fdom = max(by_width, key=lambda f: np.sum(by_width[f]))
-    dur_ms = float(np.mean(by_width[fdom]))
-    step_bf16 = args.agg_dtype == "bf16" and not (args.config in (1, 2) or args.full_width)
-    dtype_label = "bf16" if step_bf16 else "f32"
-    balg = agg_bytes(n, nnz, fdom, 2 if step_bf16 else 4)
-    achieved = balg / (dur_ms * 1e-3) / 1e9
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tfile):
-        try:
-            traffic = json.load(open(tfile)).get("cfg%d_f%d%s" % (args.config, fdom, "_bf16" if step_bf16 else "")) if args.scale_down == 1 else None
-        except Exception:
-            traffic = None
-    roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, %s)" % (fdom, "bf16" if step_bf16 else "fp32"), achieved=achieved, peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=traffic,
-                    algorithmic_bytes_per_launch=balg, avg_launch_ms=dur_ms,
-                    # measured HBM-side bytes over the same duration, and how far they exceed the algorithmic ones
-                    traffic_gbs=(traffic / (dur_ms * 1e-3) / 1e9) if traffic else None,
-                    traffic_frac_of_peak=(traffic / (dur_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic else None,
-                    overfetch=(traffic / balg) if traffic else None,
-                    # the same two rates against a plain device copy measured in this run
-                    copy_gbs=copy_gbs, frac_of_copy=(achieved / copy_gbs) if copy_gbs else None,
-                    traffic_frac_of_copy=(traffic / (dur_ms * 1e-3) / 1e9 / copy_gbs) if (traffic and copy_gbs) else None,
-                    geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
-    nn_tflops = flops_nn / (nn_ms * 1e-3) / 1e12 if nn_ms > 0 else None
-    split_core = not os.environ.get("NTP_NN_CORE", "").startswith("f")
-    nn_peak = SPLIT_PEAK_TFLOPS if split_core else FP32_MFMA_PEAK_TFLOPS
-    if step_bf16:
-        nn_peak = BF16_MFMA_PEAK_TFLOPS       # bf16 operands: one bf16 matrix instruction per product
-    roofline_nn = dict(bound="mfma",
-                       kernel=("gemm_split_kernel (fp32 products from bf16 pieces, 6 bf16 MFMA per product; "
-                               "peak = 2500/6) + gemm_kernel (fp32 MFMA) for narrow products, all transform calls of a step"
-                               if split_core else "gemm_kernel (fp32 MFMA, all transform calls of a step)"),
-                       achieved=nn_tflops, peak=nn_peak, unit="TFLOP/s (useful fp32 flops)",
-                       frac=(nn_tflops / nn_peak) if nn_tflops else None,
-                       frac_of_fp32_mfma_peak=(nn_tflops / FP32_MFMA_PEAK_TFLOPS) if nn_tflops else None, traffic=None)
-
-    # context, outside the timed region: the same model in the paper's decoupled order
-    # (all transforms first, then L aggregations at the output width, Section 4.1)
-    other_order_ms = None
-    reordered_ms = None
-    overlap_ms = None
-    if args.config in (1, 2) and args.order == "layerwise" and not args.full_width and not args.no_context:
-        ep2 = GcnEpoch(g, n, dims, order="decoupled")
-        for _ in range(3):
-            ep2.run(X, Ws, labels)
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(args.steps):
-            ep2.run(X, Ws, labels)
-        torch.cuda.synchronize()
-        other_order_ms = (time.perf_counter() - t2) * 1e3 / args.steps
-        del ep2
-        # and the layer-wise epoch with its last layer evaluated as A_hat (H W)
-        ep3 = GcnEpoch(g, n, dims, order="reordered")
-        for _ in range(3):
-            ep3.run(X, Ws, labels)
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(args.steps):
-            ep3.run(X, Ws, labels)
-        torch.cuda.synchronize()
-        reordered_ms = (time.perf_counter() - t2) * 1e3 / args.steps
-        del ep3
-        # and the layer-wise epoch with every dW issued on a second stream beside dA and the
-        # backward aggregation that follows it
-        ep4 = GcnEpoch(g, n, dims, order="layerwise", overlap_dw=True)
-        for _ in range(3):
-            ep4.run(X, Ws, labels)
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(args.steps):
-            ep4.run(X, Ws, labels)
-        torch.cuda.synchronize()
-        overlap_ms = (time.perf_counter() - t2) * 1e3 / args.steps
-        del ep4
-
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
-        import oracle
-        t0 = time.time()
-        fo = fdom
-        xo = gen.normal_features(n, fo, args.seed)
-        if nnz * fo <= 3e9:
-            og = oracle.build_graph(n, src, dst)
-            m = og.csr
-            done = og.nnz * fo
-            sample = "one forward aggregation of the whole graph at F_slice=%d" % fo
-        else:
-            # bound the CPU work: a uniform sample of rows, built one by one from the edge list
-            k = max(1000, int(n * 3e9 / (nnz * fo)))
-            rows = np.sort(gen.stream_rng(args.seed, 99).choice(n, size=min(k, n), replace=False)).astype(np.int64)
-            m = oracle.rows_from_undirected_edges(n, src, dst, rows)
-            done = m.nnz * fo
-            sample = "forward aggregation of %d uniformly sampled rows (%d entries) at F_slice=%d" % (rows.size, m.nnz, fo)
-        best = None
-        for _ in range(3):
-            t1 = time.perf_counter()
-            oracle.aggregate(m, xo)
-            dt = time.perf_counter() - t1
-            best = dt if best is None else min(best, dt)
-        cpu_baseline = dict(value=done / best / 1e9, unit="GEPS", cores=oracle.num_threads(), kind="oracle",
-                            sample=sample + ", fp64, best of 3 (%.3fs)" % best)
-        if args.config <= 2:        # small enough to time on one core as well
-            all_cores = oracle.num_threads()
-            oracle.set_num_threads(1)
-            t1 = time.perf_counter()
-            oracle.aggregate(m, xo)
-            cpu_baseline["single_core_value"] = done / (time.perf_counter() - t1) / 1e9
-            oracle.set_num_threads(all_cores)
-            if args.order == "layerwise" and not args.full_width:
-                # the same step as `value` (one whole layer-wise epoch: every aggregation and every
-                # transform, fp64) through the oracle, and its rate by the same definition
-                Xo = gen.make_features(args.config, dims[0], args.seed, args.scale_down)
-                Wo = [gen.glorot_weight(dims[i], dims[i + 1], args.seed, i) for i in range(L)]
-                lo = gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)
-                t1 = time.perf_counter()
-                oracle.epoch_layerwise(og, Xo, Wo, lo)
-                dt = time.perf_counter() - t1
-                cpu_baseline["epoch_s"] = dt
-                cpu_baseline["epoch_value"] = edge_feats / dt / 1e9
-                cpu_baseline["sample"] += "; epoch_value: one whole layer-wise epoch of the same model (%.2fs)" % dt
-        log("oracle baseline: %.2f GEPS on %d threads (%.1fs incl. graph build)" % (cpu_baseline["value"], cpu_baseline["cores"], time.time() - t0))
-
-    out = {
-        "metric": "aggregation GEPS (stored entries x F_slice / s) over the step; epoch ms in ms_per_step",
-        "value": geps, "unit": "GEPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": dtype_label, "data": "synthetic",
-        "config": {"workload": workload, "n_vertices": n, "nnz": nnz, "max_degree": info["max_degree"],
-                   "seed": args.seed, "scale_down": args.scale_down,
-                   "vertex_ids": "generator order" if args.unpermuted else "random relabelling"},
-        "roofline": roofline, "roofline_nn": roofline_nn, "cpu_baseline": cpu_baseline,
-        "agg_ms_per_step": float(agg_ms), "nn_ms_per_step": float(nn_ms),
-        "agg_geps_calls_only": edge_feats / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else None,
-        "calls": calls, "instrumented_steps": n_instrumented, "graph_build_s": t_build, "epoch_ms_decoupled_order": other_order_ms, "epoch_ms_dw_on_second_stream": overlap_ms,
-        "epoch_ms_last_layer_reordered": reordered_ms,
-    }
-    print(json.dumps(out), flush=True)
-    g.close()
 
 
 if __name__ == "__main__":

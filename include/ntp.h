@@ -300,8 +300,16 @@ int ntp_aggregate_weighted(ntp_graph_t* g, int direction, const float* weights, 
 
 /*
  * Dense transform, UPDATE of eq. (4):  H = act(A W),  A [n x k] (ld k), W [k x m] (ld m),
- * H [n x m] (ld m), all device, row-major, dtype NTP_F32 (fp32 MFMA) or NTP_BF16 (bf16
- * MFMA, fp32 accumulate, bf16 output).  act = NTP_ACT_NONE or NTP_ACT_RELU.
+ * H [n x m] (ld m), all device, row-major, dtype NTP_F32 or NTP_BF16 (bf16 operands on the
+ * bf16 matrix instructions, fp32 accumulate, bf16 output).  act = NTP_ACT_NONE or NTP_ACT_RELU.
+ * Arithmetic of NTP_F32: products with a contraction of at least 64 and an output of at least
+ * 64 columns run on the bf16 matrix instructions with every fp32 operand cut exactly into three
+ * bf16 pieces (hi + mid + lo) and the six piece products of weight >= 2^-16 accumulated in
+ * fp32: each product a*b is formed to within 2^-23 |a b|, the accuracy of an fp32 multiply-add
+ * chain, at several times the fp32 matrix rate.  One difference from fp32 arithmetic: an input
+ * that is +-inf gives NaN (inf - inf in the cut) where an fp32 product would give inf.
+ * Narrower or shorter products run on the fp32 matrix instructions.  The same holds for
+ * ntp_nn_bwd.  (NTP_NN_CORE=fp32 in the environment selects the fp32 instructions throughout.)
  */
 int ntp_nn_fwd(const void* A, const void* W, void* H, int64_t n, int64_t k, int64_t m,
                int act, int dtype, void* stream);

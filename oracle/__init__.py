@@ -26,7 +26,7 @@ from .aggregate import (  # noqa: F401
 )
 from .sampled import rows_from_undirected_edges  # noqa: F401
 from .attention import edge_softmax, edge_softmax_bwd, edge_softmax_bwd_rows, leaky_relu, weighted  # noqa: F401
-from .gat import attention_scores, attention_scores_bwd, epoch_gat_decoupled  # noqa: F401
+from .gat import attention_scores, attention_scores_bwd, epoch_gat_decoupled, resolve_gate  # noqa: F401
 from .gcn import (  # noqa: F401
-    nn_fwd, nn_bwd, softmax_cross_entropy, epoch_layerwise, epoch_decoupled,
+    nn_fwd, nn_bwd, softmax_cross_entropy, epoch_layerwise, epoch_decoupled, resolve_relu,
 )

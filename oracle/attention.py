@@ -72,7 +72,7 @@ def weighted(g: Graph, alpha_in, alpha_out) -> Graph:
                    csc=Sparse(g.csc.rowptr, g.csc.colidx, np.asarray(alpha_out, dtype=np.float32)))
 
 
-def edge_softmax_bwd(g: Graph, p, q, Z, dY, negative_slope: float = 0.2):
+def edge_softmax_bwd(g: Graph, p, q, Z, dY, negative_slope: float = 0.2, gate=None):
     """Gradient of a scalar loss with respect to the scores p and q through the attention
     weights, when the loss depends on them only through Y = sum_u alpha(u -> v) Z[u]
     (AGG of GAT, Section 2.1) and dY = dLoss/dY is given.  Chain rule, step by step:
@@ -82,6 +82,10 @@ def edge_softmax_bwd(g: Graph, p, q, Z, dY, negative_slope: float = 0.2):
         de(u -> v)     = alpha(u -> v) (dalpha(u -> v) - t[v])                (softmax over the in-edges of v)
         ds(u -> v)     = de(u -> v) * (1 if p[u] + q[v] > 0 else negative_slope)   (LeakyReLU)
         dq[v]          = sum over the in-edges of v of ds,   dp[u] = sum over the out-edges of u of ds
+
+    gate (optional, boolean per entry of g.csr): the LeakyReLU branch of every edge (True: slope 1),
+    given instead of taken from the sign of p[u] + q[v] (an epoch comparison resolves the edges whose
+    sign is not determined in finite precision, see oracle.gat.resolve_gate).
 
     Returns (dp, dq, scale_p, scale_q) in float64; the scales are the sums of |alpha| (|dalpha| + |t|)
     over the same edges (what bounds the rounding error of any evaluation order).
@@ -106,7 +110,8 @@ def edge_softmax_bwd(g: Graph, p, q, Z, dY, negative_slope: float = 0.2):
         dalpha = Z[us] @ dY[v]
         t = float(np.dot(a, dalpha))
         de = a * (dalpha - t)
-        ds = de * np.where(p[us] + q[v] > 0, 1.0, negative_slope)
+        branch = (p[us] + q[v] > 0) if gate is None else np.asarray(gate[b:e], dtype=bool)
+        ds = de * np.where(branch, 1.0, negative_slope)
         mag = a * (np.abs(dalpha) + abs(t))
         dq[v] = ds.sum()
         sq[v] = mag.sum()

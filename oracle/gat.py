@@ -25,7 +25,7 @@ import numpy as np
 import scipy.sparse as sp
 
 from .attention import edge_softmax, edge_softmax_bwd
-from .gcn import ACT_NONE, ACT_RELU, nn_bwd, nn_fwd, softmax_cross_entropy
+from .gcn import ACT_NONE, ACT_RELU, _transform, nn_bwd, softmax_cross_entropy, threshold
 from .graph import Graph
 
 
@@ -46,22 +46,47 @@ def attention_scores_bwd(Z, a_src, a_dst, dp, dq, dZ):
     return out, Z.T @ dp, Z.T @ dq
 
 
+def resolve_gate(g: Graph, p, q, mag_p, mag_q, tol: float, device_gate=None):
+    """LeakyReLU branch of every stored edge, in by-destination entry order: (gate, ambiguous).
+    The branch is the sign of s = p[u] + q[v]; an evaluation in finite precision knows the two scores
+    only up to rounding, which scales with the magnitude sums of their terms (mag_p = |Lhat| |a_src|,
+    mag_q = |Lhat| |a_dst|), so where |s| <= tol * (mag_p[u] + mag_q[v]) the supplied decisions
+    (`device_gate`: what the device decided) are taken, and only there (as oracle.gcn.resolve_relu)."""
+    rows_of = np.repeat(np.arange(g.n), np.diff(g.csr.rowptr))
+    cols = g.csr.colidx
+    s = p[cols] + q[rows_of]
+    own = s > 0
+    amb = np.abs(s) <= threshold(tol, mag_p[cols] + mag_q[rows_of])
+    if device_gate is None:
+        return own, amb
+    return np.where(amb, np.asarray(device_gate, dtype=bool), own), amb
+
+
 def epoch_gat_decoupled(g: Graph, X, weights, a_src, a_dst, labels, rounds: int = 2,
-                        negative_slope: float = 0.2, relu_masks=None):
+                        negative_slope: float = 0.2, device_relu=None, device_gate=None, tol: float = 1e-5):
     """One forward + backward pass.  Returns dict(loss, logits, dW=[...], da_src, da_dst, p, q,
-    alpha_in, alpha_out, Z=[Z^0..Z^rounds], G=[G^0..G^rounds] (G^k = dloss/dZ^k), dp, dq, dLhat)."""
+    alpha_in, alpha_out, Z=[Z^0..Z^rounds], G=[G^0..G^rounds] (G^k = dloss/dZ^k), dp, dq, dLhat),
+    plus what a comparison in finite precision needs: relu_keep / relu_ambiguous per hidden layer,
+    gate / gate_ambiguous per edge (by-destination order), dp_mag / dq_mag (sums of the magnitudes
+    of the per-edge terms of dp, dq over all rounds).  device_relu / device_gate: the device's ReLU
+    and LeakyReLU decisions, used only where the sign is ambiguous at `tol`."""
     L = len(weights)
-    mk = (lambda l: relu_masks[l] if relu_masks is not None and l < L - 1 else None)
     a_src = np.asarray(a_src, dtype=np.float64)
     a_dst = np.asarray(a_dst, dtype=np.float64)
     H = np.asarray(X, dtype=np.float64)
-    ins, outs = [], []
+    ins, outs, keeps, ambs, mags, pre = [], [], [], [], [], []
     for l, W in enumerate(weights):
         ins.append(H)
-        H = nn_fwd(H, W, ACT_RELU if l < L - 1 else ACT_NONE, mk(l))
+        H, Zl, mag, keep, amb = _transform(H, W, l == L - 1, tol, None if device_relu is None or l == L - 1 else device_relu[l])
         outs.append(H)
+        pre.append(Zl)
+        mags.append(mag)
+        if l < L - 1:
+            keeps.append(keep)
+            ambs.append(amb)
     Lhat = H
     p, q = attention_scores(Lhat, a_src, a_dst)
+    gate, gate_amb = resolve_gate(g, p, q, np.abs(Lhat) @ np.abs(a_src), np.abs(Lhat) @ np.abs(a_dst), tol, device_gate)
     alpha_in, alpha_out = edge_softmax(g, p, q, negative_slope)
     n = g.n
     A = sp.csr_matrix((alpha_in, g.csr.colidx, g.csr.rowptr), shape=(n, n))      # rows = destinations
@@ -74,19 +99,24 @@ def epoch_gat_decoupled(g: Graph, X, weights, a_src, a_dst, labels, rounds: int 
     G[rounds] = dZ
     dp = np.zeros(n)
     dq = np.zeros(n)
+    dp_mag = np.zeros(n)
+    dq_mag = np.zeros(n)
     for k in range(rounds, 0, -1):
-        dpk, dqk, _, _ = edge_softmax_bwd(g, p, q, Z[k - 1], G[k], negative_slope)
+        dpk, dqk, spk, sqk = edge_softmax_bwd(g, p, q, Z[k - 1], G[k], negative_slope, gate=gate)
         dp += dpk
         dq += dqk
+        dp_mag += spk
+        dq_mag += sqk
         G[k - 1] = At @ G[k]
     dLhat, da_src, da_dst = attention_scores_bwd(Lhat, a_src, a_dst, dp, dq, G[0])
     dH = dLhat
     dWs = [None] * L
     for l in range(L - 1, -1, -1):
         act = ACT_RELU if l < L - 1 else ACT_NONE
-        dA, dW = nn_bwd(ins[l], weights[l], outs[l], dH, act, need_dA=(l > 0), relu_mask=mk(l))
+        dA, dW = nn_bwd(ins[l], weights[l], outs[l], dH, act, need_dA=(l > 0), relu_mask=keeps[l] if l < L - 1 else None)
         dWs[l] = dW
         dH = dA
     return dict(loss=loss, logits=Z[-1], dW=dWs, da_src=da_src, da_dst=da_dst, p=p, q=q,
                 alpha_in=alpha_in, alpha_out=alpha_out, Z=Z, G=G, dp=dp, dq=dq, dLhat=dLhat,
-                nn_in=ins, hidden=outs)
+                nn_in=ins, hidden=outs, preact=pre, preact_mag=mags, relu_keep=keeps, relu_ambiguous=ambs,
+                gate=gate, gate_ambiguous=gate_amb, dp_mag=dp_mag, dq_mag=dq_mag)

@@ -246,20 +246,33 @@ int ensure_partial(ntp_graph* G, const Form& F, int64_t f, int n_rhs = 1) {
     return NTP_OK;
 }
 
-int check_agg_args(const ntp_graph* g, const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype) {
+// Do two row-major views of n rows x f elements (row strides lda, ldb in elements of es bytes)
+// share a byte?  Each view is n intervals of f * es bytes.  Disjoint spans: no.  Equal strides: the
+// intervals of both repeat with the same period, so they meet iff the two windows meet modulo the
+// stride.  Different strides inside one span: not decided here, reported as overlapping.
+bool views_overlap(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n, int64_t f, int64_t es) {
+    if (n <= 0 || f <= 0) return false;
+    const uintptr_t a = (uintptr_t)A, b = (uintptr_t)B;
+    const uintptr_t wa = (uintptr_t)(f * es);
+    const uintptr_t span_a = (uintptr_t)((n - 1) * lda * es) + wa, span_b = (uintptr_t)((n - 1) * ldb * es) + wa;
+    if (a + span_a <= b || b + span_b <= a) return false;
+    if (lda != ldb) return true;
+    const uintptr_t period = (uintptr_t)(lda * es);
+    const uintptr_t d = (b >= a ? b - a : a - b) % period;       // offset of one window inside the other's period
+    return d < wa || period - d < wa;
+}
+
+int check_agg_args(const ntp_graph* g, const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype, bool need_device = true) {
     if (!g) { set_error("graph handle is NULL"); return NTP_EINVAL; }
-    if (g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
     if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
     if (f < 1 || f > (1 << 20)) { set_error("slice width %lld out of range (1..2^20)", (long long)f); return NTP_EINVAL; }
     if (ldx < f || ldy < f) { set_error("row stride smaller than the slice width"); return NTP_EINVAL; }
     if (g->g.n > 0 && (!X || !Y)) { set_error("X or Y is NULL"); return NTP_EINVAL; }
-    if (X == Y && g->g.n > 0) { set_error("input and output must not overlap"); return NTP_EINVAL; }
-    if (ldx == f && ldy == f && g->g.n > 0) {
-        const size_t es = dtype == NTP_BF16 ? 2 : 4;
-        const char* x0 = (const char*)X; const char* y0 = (const char*)Y;
-        const size_t bytes = (size_t)g->g.n * (size_t)f * es;
-        if (x0 < y0 + bytes && y0 < x0 + bytes) { set_error("input and output must not overlap"); return NTP_EINVAL; }
+    if (g->g.n > 0 && views_overlap(X, ldx, Y, ldy, g->g.n, f, dtype == NTP_BF16 ? 2 : 4)) {
+        set_error("input and output must not overlap");
+        return NTP_EINVAL;
     }
+    if (need_device && g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
     return NTP_OK;
 }
 
@@ -604,14 +617,16 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
     if (!X || !Y) { set_error("X or Y is NULL"); return NTP_EINVAL; }
     int rc;
     for (int r = 0; r < n_rhs; ++r) {
-        rc = check_agg_args(g, X[r], Y[r], f, ldx, ldy, dtype);
+        rc = check_agg_args(g, X[r], Y[r], f, ldx, ldy, dtype, false);
         if (rc != NTP_OK) return rc;
+        const int64_t es = dtype == NTP_BF16 ? 2 : 4;
         for (int q = 0; q < n_rhs; ++q)
-            if (g->g.n > 0 && Y[r] == X[q]) { set_error("an output aliases an input"); return NTP_EINVAL; }
+            if (q != r && views_overlap(X[q], ldx, Y[r], ldy, g->g.n, f, es)) { set_error("an output overlaps an input"); return NTP_EINVAL; }
         for (int q = 0; q < r; ++q)
-            if (g->g.n > 0 && Y[r] == Y[q]) { set_error("two outputs alias"); return NTP_EINVAL; }
+            if (views_overlap(Y[q], ldy, Y[r], ldy, g->g.n, f, es)) { set_error("two outputs overlap"); return NTP_EINVAL; }
     }
     if (direction != NTP_FWD && direction != NTP_BWD) { set_error("direction must be NTP_FWD or NTP_BWD"); return NTP_EINVAL; }
+    if (g->host_only) { set_error("graph was built with NTP_HOST_ONLY: nothing is on the device"); return NTP_EBUDGET; }
     Form& F = g->f(direction == NTP_FWD ? NTP_CSR : NTP_CSC);
     const bool scatter = direction == NTP_BWD && g->scatter_bwd();
     if (scatter && dtype != NTP_F32) { set_error("the scatter backward (NTP_SCATTER_BWD) takes fp32 buffers only"); return NTP_EUNSUPPORTED; }

@@ -224,6 +224,59 @@ def test_argument_errors():
     L.ntp_graph_free(None)                       # NULL is allowed
 
 
+def test_overlapping_strided_views_are_refused():
+    """Input and output of an aggregation call must not share a byte, also when both are column
+    windows of one wider matrix (a worker's slices of a full-width buffer).  The check runs before
+    anything touches the device, so a host-only handle shows it: overlapping windows give
+    NTP_EINVAL, disjoint ones pass the check and end at the host-only handle's NTP_EBUDGET."""
+    n = 1000
+    g = ntp.ntp_graph_build(n, [0, 1], [1, 2], flags=ntp.NTP_GCN_FLAGS | HOST)
+    base = 1 << 30                     # addresses only: nothing is dereferenced on a host-only handle
+
+    def code(x, y, f, ldx, ldy, dtype=ntp.NTP_F32):
+        with pytest.raises(ntp.NtpError) as e:
+            ntp.ntp_aggregate_fwd(g, x, y, f, ldx, ldy, dtype)
+        return e.value.code
+
+    ld = 256
+    # Y = X + 16 columns inside rows of 256: the 32-column windows share 16 columns of every row
+    assert code(base, base + 16 * 4, 32, ld, ld) == ntp.NTP_EINVAL
+    assert code(base + 16 * 4, base, 32, ld, ld) == ntp.NTP_EINVAL
+    # neighbouring windows of the same rows do not overlap
+    assert code(base, base + 32 * 4, 32, ld, ld) == ntp.NTP_EBUDGET
+    assert code(base + 32 * 4, base, 32, ld, ld) == ntp.NTP_EBUDGET
+    # the last window of a row against the first window: disjoint although the address distance wraps
+    assert code(base, base + 224 * 4, 32, ld, ld) == ntp.NTP_EBUDGET
+    assert code(base, base + 225 * 4, 32, ld, ld) == ntp.NTP_EINVAL        # 225 + 32 > 256: runs into the next row's first window
+    # a window that starts some rows further down still overlaps if its columns do
+    assert code(base, base + (5 * ld + 8) * 4, 32, ld, ld) == ntp.NTP_EINVAL
+    assert code(base, base + (5 * ld + 40) * 4, 32, ld, ld) == ntp.NTP_EBUDGET
+    # compact matrices: equal, shifted by half a matrix, back to back
+    assert code(base, base, 32, 32, 32) == ntp.NTP_EINVAL
+    assert code(base, base + n * 16 * 4, 32, 32, 32) == ntp.NTP_EINVAL
+    assert code(base, base + n * 32 * 4, 32, 32, 32) == ntp.NTP_EBUDGET
+    # bf16 elements are two bytes wide
+    assert code(base, base + 32 * 2, 32, ld, ld, ntp.NTP_BF16) == ntp.NTP_EBUDGET
+    assert code(base, base + 31 * 2, 32, ld, ld, ntp.NTP_BF16) == ntp.NTP_EINVAL
+    # different strides inside one span cannot be told apart cheaply: refused
+    assert code(base, base + 64, 32, 256, 128) == ntp.NTP_EINVAL
+    assert code(base, base + n * 256 * 4, 32, 256, 128) == ntp.NTP_EBUDGET
+    # several right-hand sides: every output against every input and every other output
+    L = ntp.lib()
+    import ctypes
+
+    def multi(xs, ys):
+        xa = (ctypes.c_void_p * len(xs))(*xs)
+        ya = (ctypes.c_void_p * len(ys))(*ys)
+        return L.ntp_chunked_aggregate_multi(g.handle, ntp.NTP_FWD, len(xs), xa, ya, 32, ld, ld, ntp.NTP_F32, None, None)
+
+    far = base + n * ld * 4
+    assert multi([base, base + 128], [far, far + 128]) == ntp.NTP_EBUDGET
+    assert multi([base, base + 512], [far, base + 64]) == ntp.NTP_EINVAL and "overlaps an input" in ntp.ntp_last_error()
+    assert multi([base, base + 128], [far, far + 64]) == ntp.NTP_EINVAL and "two outputs" in ntp.ntp_last_error()
+    g.close()
+
+
 def test_inputs_are_reproducible():
     a = gen.make_graph(2, seed=0, scale_down=16)
     b = gen.make_graph(2, seed=0, scale_down=16)

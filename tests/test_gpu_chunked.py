@@ -168,3 +168,68 @@ def test_streamed_weights_rebuilt_on_the_device_are_the_stored_ones(inputs, case
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), "%s %s" % (case, direction)
     resident.close()
     streamed.close()
+
+
+def test_config5_shape_streams_under_a_budget():
+    """Config 5's shape at one eighth of its size (13.9 M vertices, 0.42 B stored entries, one
+    worker's 16-column slice, chunks of 32 Mi entries = the config's 256 Mi scaled) under a device
+    budget that leaves more than half of the chunks streamed from pinned host memory on every
+    call: forward and backward through ntp_chunked_aggregate give, bit for bit, what the same
+    chunking gives with every chunk resident, and 21,000 sampled rows (20,000 uniform + the 1,000
+    with most entries) match oracle rows built one by one from the edge list."""
+    import time
+    import torch
+    from gpu_util import dev_f32
+    from helpers import assert_close, TOL_F32
+    scale, f = 8, 16
+    t0 = time.time()
+    n, src, dst = gen.make_graph(5, seed=0, scale_down=scale)
+    ce = gen.CONFIGS[5].chunk_edges // scale
+    say("config 5 / %d: n %d, undirected edges %d, chunk_edges %d (generated in %.0fs)" % (scale, n, src.size, ce, time.time() - t0))
+    x_np = gen.normal_features(n, f, 0)
+    x = dev_f32(x_np)
+    cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def both_directions(g):
+        out = []
+        for direction in (ntp.NTP_FWD, ntp.NTP_BWD):
+            y = torch.full((n, f), float("nan"), device="cuda:0")
+            torch.cuda.synchronize()
+            ntp.ntp_chunked_aggregate(g, direction, x, y, f, f, f, ntp.NTP_F32, cs, xs)
+            torch.cuda.synchronize()
+            out.append(y)
+        return out
+
+    t0 = time.time()
+    g = ntp.ntp_graph_build(n, src, dst, chunk_edges=ce)
+    info = ntp.ntp_graph_info(g)
+    nnz = info["nnz"]
+    say("  all-resident graph built in %.0fs: nnz %d, %d chunks, longest row %d" % (time.time() - t0, nnz, info["n_chunks"], info["max_degree"]))
+    assert ntp.ntp_graph_chunks(g)["resident"].all() and info["n_chunks"] >= 12
+    want_fwd, want_bwd = both_directions(g)
+    rowptr = np.empty(n + 1, dtype=np.int64)
+    ntp.binding._check(ntp.lib().ntp_graph_export(g.handle, ntp.NTP_CSR, ntp.binding._ptr(rowptr), None, None))
+    g.close()
+    t0 = time.time()
+    g = ntp.ntp_graph_build(n, src, dst, device_budget_bytes=int(0.45 * (8 * nnz + 12 * n)), chunk_edges=ce)
+    res = ntp.ntp_graph_chunks(g)["resident"]
+    say("  budgeted graph built in %.0fs: %d of %d chunks resident, %d bytes streamed per pass"
+        % (time.time() - t0, int(res.sum()), res.size, ntp.ntp_graph_stream_bytes(g)))
+    assert 2 * int(res.sum()) <= res.size and res.sum() >= 1
+    for rep in range(2):                    # the second call finds the staging buffers in use
+        got_fwd, got_bwd = both_directions(g)
+        assert torch.equal(got_fwd, want_fwd) and torch.equal(got_bwd, want_bwd), "streamed and resident results differ"
+    assert torch.equal(got_fwd, got_bwd)    # the adjacency is symmetric
+    g.close()
+    deg = np.diff(rowptr)
+    assert int(rowptr[-1]) == nnz == 2 * src.size + n
+    top = np.argsort(deg)[-1000:]
+    uni = gen.stream_rng(0, 98).choice(np.setdiff1d(np.arange(n), top), size=20000, replace=False)
+    rows = np.concatenate([top, uni]).astype(np.int64)
+    t0 = time.time()
+    m = oracle.rows_from_undirected_edges(n, src, dst, rows)
+    assert np.array_equal(np.diff(m.rowptr), deg[rows])
+    ref, ref_abs = oracle.aggregate(m, x_np, with_abs=True)
+    say("  oracle rows in %.0fs (%d entries)" % (time.time() - t0, m.nnz))
+    got = got_fwd[torch.from_numpy(rows).to("cuda:0")].cpu().numpy()
+    assert_close(got, ref, ref_abs, TOL_F32, "config 5 / 8 sampled rows")

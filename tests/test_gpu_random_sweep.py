@@ -178,4 +178,4 @@ def test_random_gat_epoch_case(seed):
     chunk_edges = int(rng.integers(500, 20000)) if rng.integers(0, 3) == 0 else None
     extra = ntp.NTP_EDGE_PERM if rng.integers(0, 2) else 0
     _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, "random seed %d, chunk_edges %s, extra flags %d" % (seed, chunk_edges, extra),
-               chunk_edges=chunk_edges, extra_flags=extra, scale_floor=1e-2, grad_tol=2e-4)
+               chunk_edges=chunk_edges, extra_flags=extra, scale_floor=1e-2)

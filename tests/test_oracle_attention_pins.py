@@ -331,3 +331,67 @@ def test_a13_row_restricted_score_gradient_matches_the_whole_graph_oracle():
         cols = mu.colidx[mu.rowptr[i]:mu.rowptr[i + 1]]
         total += ou["ds"][mu.rowptr[i]:mu.rowptr[i + 1]][cols == u].sum()
     assert abs(total - dp[u]) <= 1e-12 * max(1.0, abs(dp[u]))
+
+
+def test_a14_leaky_relu_branch_argument_and_ambiguous_edges():
+    """edge_softmax_bwd with the branches given: the oracle's own branches change nothing; flipping one
+    edge's branch changes dq of its destination and dp of its source by (1 - slope) x that edge's
+    softmax term.  resolve_gate hands over exactly the edges whose score sum is zero at the tolerance."""
+    n = 120
+    src, dst = gen.directed_random_edges(n, 700, 5)
+    g = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    rng = np.random.default_rng(4)
+    p, q = rng.normal(size=n), rng.normal(size=n)
+    Z, dY = rng.normal(size=(n, 5)), rng.normal(size=(n, 5))
+    slope = 0.2
+    rows_of = np.repeat(np.arange(n), np.diff(g.csr.rowptr))
+    own = p[g.csr.colidx] + q[rows_of] > 0
+    base = oracle.edge_softmax_bwd(g, p, q, Z, dY, slope)
+    same = oracle.edge_softmax_bwd(g, p, q, Z, dY, slope, gate=own)
+    for a, b in zip(base, same):
+        np.testing.assert_array_equal(a, b)
+    k = int(np.flatnonzero(own)[17])              # an edge on the slope-1 branch
+    v, u = int(rows_of[k]), int(g.csr.colidx[k])
+    flipped = own.copy()
+    flipped[k] = False
+    dp2, dq2, _, _ = oracle.edge_softmax_bwd(g, p, q, Z, dY, slope, gate=flipped)
+    a_in, _ = oracle.edge_softmax(g, p, q, slope)
+    b, e = g.csr.rowptr[v], g.csr.rowptr[v + 1]
+    dalpha = Z[g.csr.colidx[b:e]] @ dY[v]
+    de_k = a_in[k] * (dalpha[k - b] - a_in[b:e] @ dalpha)
+    assert abs((base[1][v] - dq2[v]) - (1 - slope) * de_k) <= 1e-14
+    assert abs((base[0][u] - dp2[u]) - (1 - slope) * de_k) <= 1e-14
+    changed_q = np.flatnonzero(base[1] != dq2)
+    changed_p = np.flatnonzero(base[0] != dp2)
+    assert list(changed_q) == [v] and list(changed_p) == [u]
+    # resolve_gate: plant one score sum of relative size 1e-9
+    q2 = q.copy()
+    mag_p, mag_q = np.abs(p) + 0.5, np.abs(q) + 0.5
+    kk = int(g.csr.rowptr[40])                    # first in-edge of vertex 40
+    q2[40] = -p[g.csr.colidx[kk]] + 1e-9
+    gate, amb = oracle.resolve_gate(g, p, q2, mag_p, mag_q, 1e-5)
+    assert amb[kk] and gate[kk]                   # tiny but positive: the oracle's own branch
+    others = np.flatnonzero(amb)
+    assert others.size >= 1 and np.all(np.abs(p[g.csr.colidx[others]] + q2[rows_of[others]]) <= 1e-5 * 20)
+    dev = np.zeros(g.csr.nnz, dtype=bool)         # a device that puts every edge on the negative branch
+    gate2, _ = oracle.resolve_gate(g, p, q2, mag_p, mag_q, 1e-5, device_gate=dev)
+    assert not gate2[kk] and np.array_equal(gate2[~amb], gate[~amb])
+    gate3, amb3 = oracle.resolve_gate(g, p, q2, mag_p, mag_q, 0.0, device_gate=dev)
+    assert not amb3.any() and np.array_equal(gate3, p[g.csr.colidx] + q2[rows_of] > 0)
+
+
+def test_a15_gat_epoch_device_decisions_count_only_where_ambiguous():
+    """with tol = 0 arbitrary ReLU and LeakyReLU decisions handed to the epoch change nothing"""
+    g, X, Ws, a_s, a_d, labels = _tiny_gat(9, True)
+    a = oracle.epoch_gat_decoupled(g, X, Ws, a_s, a_d, labels, 2, 0.2)
+    wrong_relu = [np.zeros_like(h, dtype=bool) for h in a["hidden"][:-1]]
+    wrong_gate = np.ones(g.csr.nnz, dtype=bool)
+    b = oracle.epoch_gat_decoupled(g, X, Ws, a_s, a_d, labels, 2, 0.2, device_relu=wrong_relu, device_gate=wrong_gate, tol=0.0)
+    assert a["loss"] == b["loss"]
+    for x, y in zip(a["dW"] + [a["da_src"], a["da_dst"]], b["dW"] + [b["da_src"], b["da_dst"]]):
+        np.testing.assert_array_equal(x, y)
+    c = oracle.epoch_gat_decoupled(g, X, Ws, a_s, a_d, labels, 2, 0.2, device_gate=wrong_gate, tol=np.inf)
+    d = oracle.epoch_gat_decoupled(g, X, Ws, a_s, a_d, labels, 2, 1.0)      # every edge on the slope-1 branch = slope 1 ...
+    # ... in the backward pass only: the forward still uses slope 0.2, so only check that the gradient moved
+    assert c["loss"] == a["loss"] and not np.array_equal(c["da_src"], a["da_src"])
+    assert d["loss"] != a["loss"]

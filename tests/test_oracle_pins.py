@@ -282,22 +282,68 @@ def test_p7_identity_adjacency_reduces_to_mlp():
 
 
 @pytest.mark.parametrize("epoch", ["layerwise", "decoupled"])
-def test_p7_relu_masks_argument(epoch):
-    """passing the epoch its own ReLU decisions changes nothing; a flipped decision on one
-    entry changes exactly what zeroing / keeping that entry implies"""
+def test_p7_device_relu_decisions_count_only_where_the_sign_is_ambiguous(epoch):
+    """Decisions handed to the epoch are used only on pre-activations that are zero at the given
+    tolerance: with tol = 0 nothing but exact zeros is ambiguous and arbitrary decisions change
+    nothing; with an infinite tolerance every entry is ambiguous and the decisions are the activation;
+    a planted near-zero pre-activation is the one entry a small tolerance hands over"""
     fn = gcn.epoch_layerwise if epoch == "layerwise" else gcn.epoch_decoupled
     g, X, Ws, labels = _tiny_model(16)
     a = fn(g, X, Ws, labels)
-    masks = [h > 0 for h in a["hidden"][:-1]]
-    b = fn(g, X, Ws, labels, relu_masks=masks)
+    assert all(not amb.any() for amb in fn(g, X, Ws, labels, tol=0.0)["relu_ambiguous"])
+    for k, keep in enumerate(a["relu_keep"]):
+        np.testing.assert_array_equal(keep, a["preact"][k] > 0)
+    wrong = [np.ones_like(h, dtype=bool) for h in a["hidden"][:-1]]
+    b = fn(g, X, Ws, labels, device_relu=wrong, tol=0.0)
     assert a["loss"] == b["loss"]
     for x, y in zip(a["dW"], b["dW"]):
         np.testing.assert_array_equal(x, y)
-    masks[0][:] = True                          # identity activation on layer 0
-    c = fn(g, X, Ws, labels, relu_masks=masks)
-    pre0 = (c["nn_in"][0] @ Ws[0])
-    np.testing.assert_allclose(c["hidden"][0], pre0, rtol=1e-14)
-    assert c["loss"] != a["loss"]
+    c = fn(g, X, Ws, labels, device_relu=wrong, tol=np.inf)          # identity activation everywhere
+    np.testing.assert_allclose(c["hidden"][0], c["nn_in"][0] @ Ws[0], rtol=1e-14)
+    assert all(amb.all() for amb in c["relu_ambiguous"]) and c["loss"] != a["loss"]
+    # plant a pre-activation of relative size 1e-9 in layer 0: shift one weight column so that
+    # entry (v, j) of the first pre-activation becomes 1e-9 of its magnitude sum
+    v, j = 7, 3
+    A0 = a["nn_in"][0]
+    W0 = Ws[0].copy()
+    k = int(np.argmax(np.abs(A0[v])))
+    target = 1e-9 * (np.abs(A0[v]) @ np.abs(W0[:, j]))
+    W0[k, j] -= (a["preact"][0][v, j] - target) / A0[v, k]
+    Wp = [W0] + Ws[1:]
+    base = fn(g, X, Wp, labels)
+    amb0 = base["relu_ambiguous"][0]
+    assert amb0[v, j] and amb0.sum() == 1 and base["relu_keep"][0][v, j]            # tiny but positive: kept
+    flip = [np.ones_like(h, dtype=bool) for h in base["hidden"][:-1]]
+    flip[0][v, j] = False
+    d = fn(g, X, Wp, labels, device_relu=flip)
+    assert not d["relu_keep"][0][v, j] and (d["relu_keep"][0] != base["relu_keep"][0]).sum() == 1
+    assert d["hidden"][0][v, j] == 0.0
+    # the gradient of W0[:, j] loses exactly that entry's term A0[v, :] * dZ[v, j] (first layer: nothing upstream changes;
+    # downstream the forward value moved by 1e-9 of its scale only)
+    dZ_vj = base["dH"][0][v, j]
+    np.testing.assert_allclose(base["dW"][0][:, j] - d["dW"][0][:, j], base["nn_in"][0][v] * dZ_vj, rtol=1e-5, atol=1e-12)
+
+
+def test_p7_transform_first_changes_only_the_magnitude_sums():
+    """naming the other evaluation order of a layer changes no value; its magnitude sums
+    |A_hat| (|H| |W|) are never below those of the aggregate-first order, |A_hat H| |W|"""
+    g, X, Ws, labels = _tiny_model(19, directed=True)
+    a = gcn.epoch_layerwise(g, X, Ws, labels)
+    b = gcn.epoch_layerwise(g, X, Ws, labels, transform_first=[True, False, True])
+    assert a["loss"] == b["loss"]
+    for x, y in zip(a["dW"], b["dW"]):
+        np.testing.assert_array_equal(x, y)
+    np.testing.assert_array_equal(a["preact_mag"][1], b["preact_mag"][1])
+    for l in (0, 2):
+        assert np.all(b["preact_mag"][l] >= a["preact_mag"][l] * (1 - 1e-14))
+    assert (b["preact_mag"][0] > a["preact_mag"][0] * 1.01).any()       # signed inputs cancel in A_hat H
+    # dense check of the other order's magnitude sums on layer 0
+    n = g.n
+    D = np.zeros((n, n))
+    for v in range(n):
+        for k in range(g.csr.rowptr[v], g.csr.rowptr[v + 1]):
+            D[v, g.csr.colidx[k]] += abs(float(g.csr.val[k]))
+    np.testing.assert_allclose(b["preact_mag"][0], D @ (np.abs(X) @ np.abs(Ws[0])), rtol=1e-12)
 
 
 def test_p7_decoupled_is_power_of_ahat():
