@@ -267,19 +267,21 @@ def step_bench(args, cfg, scale_down=1, agg_dtype="f32", copy_gbs=None, graph=No
     nn_ms = sum(np.sum(v) for k, v in per.items() if k.startswith("nn")) / n_instrumented
 
     # roofline of the dominant aggregation kernel: the width with the largest share of step time
+    # (timed on its forward launches: a backward launch may carry the ReLU mask of the layer below on
+    # its way out, which reads one more matrix than the algorithmic bytes of a plain aggregation count)
     agg_tags = [k for k in per if k.startswith("agg")]
     by_width = {}
     for k in agg_tags:
         f = int(k.split("f=")[1])
         by_width.setdefault(f, []).extend(per[k])
     fdom = max(by_width, key=lambda f: np.sum(by_width[f]))
-    dur_ms = float(np.mean(by_width[fdom]))
+    dur_ms = float(np.mean(per.get("agg_fwd f=%d" % fdom, by_width[fdom])))
     dtype_label = "bf16" if share_bf16 else "f32"
     balg = agg_bytes(n, nnz, fdom, 2 if share_bf16 else 4)
     achieved = balg / (dur_ms * 1e-3) / 1e9
     traffic, traffic_source = (profile_traffic("cfg%d_f%d%s" % (cfg, fdom, "_bf16" if share_bf16 else ""))
                                if scale_down == 1 and not args.unpermuted else (None, None))
-    roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, %s)" % (fdom, "bf16" if share_bf16 else "fp32"), achieved=achieved, peak=HBM_PEAK_GBS,
+    roofline = dict(bound="hbm", kernel="agg_kernel (F_slice=%d, %s, forward launches)" % (fdom, "bf16" if share_bf16 else "fp32"), achieved=achieved, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=traffic,
                     # `traffic` is not counted by this run: it is the L2-boundary byte count (reads that
                     # miss the L2, Infinity-Cache hits included, plus writes) of an earlier rocprofv3 run

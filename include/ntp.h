@@ -215,6 +215,26 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
                                 void* compute_stream, void* copy_stream);
 
 /*
+ * Aggregation with the activation sigma of eq. (4) applied on the way out, for the two places where
+ * an epoch applies it right after an aggregation (no separate pass over the matrix):
+ *   - a layer evaluated as sigma(A_hat (H W)) (transform first, aggregate at the narrower output
+ *     width): direction NTP_FWD, act NTP_ACT_RELU, M NULL:   Y = max(A_hat X, 0);
+ *   - the gradient that flows back into a ReLU layer through the aggregation above it:
+ *     direction NTP_BWD, act NTP_ACT_RELU, M = that layer's output H [n x f_slice], row stride ldm:
+ *         Y = (A_hat^T X) * 1[M > 0]
+ *     i.e. Y is dZ of the layer below, and its ntp_nn_bwd runs with NTP_ACT_NONE.
+ * In general: an output element is kept where its mask element (the same position of M, or the
+ * output itself when M is NULL) is > 0 and stored as zero elsewhere (a NaN mask element stores 0).
+ * act NTP_ACT_NONE is ntp_chunked_aggregate.  M: device, same dtype as Y, must not overlap Y.
+ * Chunk schedule, streams and every other rule as for ntp_chunked_aggregate (copy_stream may be
+ * NULL when every chunk is resident).  Not available for the backward of a graph built with
+ * NTP_SCATTER_BWD (NTP_EUNSUPPORTED).
+ */
+int ntp_aggregate_act(ntp_graph_t* g, int direction, const void* X, void* Y,
+                      int64_t f_slice, int64_t ldx, int64_t ldy, int dtype,
+                      int act, const void* M, int64_t ldm, void* compute_stream, void* copy_stream);
+
+/*
  * Edge attention weights of GAT-style aggregation (AGG of GAT, Section 2.1; Section 4.1 computes
  * the coefficients of all edges before the aggregation starts and then aggregates with them as
  * edge weights).  For every stored entry u -> v of g (self loops included; g's own weights are

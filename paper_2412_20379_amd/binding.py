@@ -22,7 +22,7 @@ NTP_ACT_NONE, NTP_ACT_RELU = 0, 1
 EXPORTED_SYMBOLS = [
     "ntp_graph_build", "ntp_graph_info", "ntp_graph_export", "ntp_graph_export_perm", "ntp_graph_chunks", "ntp_graph_stream_bytes",
     "ntp_graph_device_bytes", "ntp_aggregate_fwd", "ntp_aggregate_fwd_noalloc", "ntp_aggregate_bwd", "ntp_chunked_aggregate",
-    "ntp_chunked_aggregate_multi", "ntp_edge_softmax", "ntp_edge_softmax_bwd", "ntp_aggregate_weighted",
+    "ntp_chunked_aggregate_multi", "ntp_aggregate_act", "ntp_edge_softmax", "ntp_edge_softmax_bwd", "ntp_aggregate_weighted",
     "ntp_attention_scores_fwd", "ntp_attention_scores_bwd", "ntp_attention_scores_bwd_scratch_bytes",
     "ntp_nn_fwd", "ntp_nn_bwd", "ntp_nn_bwd_workspace_bytes", "ntp_softmax_xent", "ntp_softmax_xent_scratch_bytes", "ntp_relu_fwd", "ntp_relu_bwd",
     "ntp_graph_free", "ntp_last_error",
@@ -65,6 +65,7 @@ def lib():
     L.ntp_aggregate_fwd_noalloc.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, vp]
     L.ntp_chunked_aggregate.argtypes = [vp, ctypes.c_int, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
     L.ntp_chunked_aggregate_multi.argtypes = [vp, ctypes.c_int, i32, vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
+    L.ntp_aggregate_act.argtypes = [vp, ctypes.c_int, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, i64, vp, vp]
     L.ntp_edge_softmax.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp]
     L.ntp_edge_softmax_bwd.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i64, i64, i64, vp, vp, ctypes.c_int, vp]
     L.ntp_attention_scores_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
@@ -260,6 +261,12 @@ def ntp_chunked_aggregate(g: Graph, direction, X, Y, f_slice, ldx, ldy, dtype=NT
                           compute_stream=None, copy_stream=None):
     _check(lib().ntp_chunked_aggregate(g.handle, int(direction), _ptr(X), _ptr(Y), int(f_slice), int(ldx), int(ldy),
                                        int(dtype), _stream(compute_stream), _stream(copy_stream)))
+
+
+def ntp_aggregate_act(g: Graph, direction, X, Y, f_slice, ldx, ldy, dtype=NTP_F32, act=NTP_ACT_RELU, M=None, ldm=0,
+                      compute_stream=None, copy_stream=None):
+    _check(lib().ntp_aggregate_act(g.handle, int(direction), _ptr(X), _ptr(Y), int(f_slice), int(ldx), int(ldy), int(dtype),
+                                   int(act), _ptr(M), int(ldm), _stream(compute_stream), _stream(copy_stream)))
 
 
 def ntp_chunked_aggregate_multi(g: Graph, direction, Xs, Ys, f_slice, ldx, ldy, dtype=NTP_F32,

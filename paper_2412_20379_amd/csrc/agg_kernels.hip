@@ -13,8 +13,24 @@
 //   - rows beyond the split threshold: cut into segments, one wavefront per segment, fp32
 //     partial sums to a scratch slot; reduce_kernel adds the slots of a row in order.
 // No atomics anywhere: the result is deterministic.
+//
+// Hub table (agg_hub_kernel).  What bounds the gather loop is the rate at which a compute unit's
+// L1 can miss: every gathered row is a miss.  On a power-law graph a few columns take a large
+// share of the gathers, so the graph build marks the most gathered columns ("hubs") in a second
+// column-id array: a hub entry carries 0x80000000 | slot instead of its vertex id.  The hub
+// kernel runs one persistent block of 16 wavefronts per compute unit, which first copies the hub
+// rows of its column pass into an LDS table (one line of L x 16 bytes per slot) and then works
+// through the launch's rows exactly as agg_kernel does, except that a hub entry's row comes from
+// LDS.  No look-up and no branch: the sign of the id selects the source, the global load of a
+// hub entry is pointed at the first hub's row (a line every wavefront keeps touching, so it
+// stays in the L1), and the summation order is that of agg_kernel: same bits.
+// Measured on MI355X it does not pay and is therefore opt-in (graphs built with NTP_AGG_HUB=1 in
+// the environment): the L1-to-L2 requests fall by the hubs' share of the gathers (a third on a
+// 2.5 M-entry R-MAT graph), but the persistent blocks run 20-35 % behind the plain kernel with
+// one slot as with 1024, i.e. what the table saves never becomes the bottleneck.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 
 #include "lane_util.h"
@@ -54,6 +70,11 @@ template <int VEC> struct IoF32 {
         else { *p = v[0]; }
     }
     static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
+    // exact copy of loaded elements (for staging in LDS)
+    static __device__ __forceinline__ void store_plain(float* p, const float (&v)[VEC]) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) p[i] = v[i];
+    }
 };
 
 // VEC fp32 partial sums to scratch (VEC may be 8 for bf16 features)
@@ -91,6 +112,11 @@ template <int VEC> struct IoBf16 {
         else { *p = (unsigned short)f32_to_bf16_rne(v[0]); }
     }
     static __device__ __forceinline__ void store1(unsigned short* p, float v) { *p = (unsigned short)f32_to_bf16_rne(v); }
+    // exact copy of loaded elements (for staging in LDS): the floats hold bf16 values, truncation is exact
+    static __device__ __forceinline__ void store_plain(unsigned short* p, const float (&v)[VEC]) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) p[i] = (unsigned short)(__float_as_uint(v[i]) >> 16);
+    }
 };
 
 // Wavefronts per SIMD the register allocation must allow.  The gather loop lives on loads in
@@ -105,18 +131,15 @@ constexpr int agg_min_waves() {
     return 1;
 }
 
-// ---- the aggregation kernel -----------------------------------------------------------
-// L lanes per feature row, NACC vectors per lane (columns l*VEC + j*L*VEC), 4 wavefronts
-// per block, every wavefront an independent unit of work.  blockIdx.y walks column passes
-// when the slice is wider than L*VEC*NACC.
-//
-// Gathers are issued U at a time with no branch between them, so that U neighbour rows
-// are in flight per lane before the first multiply-add waits.  To keep the loads free of
-// branches every lane always loads from a valid address: a lane whose columns lie beyond
-// the slice reads the first column of its pass, an entry that does not exist reads the row's own vertex, and
-// what such a load returns is replaced by zero before it is used.
-template <class IO, int L, int NACC>
-__global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kernel(const AggArgs a) {
+// ---- the aggregation kernels ----------------------------------------------------------
+constexpr int HUB_SLOTS = 1024;       // lines of the LDS hub table (128 KB at 128 bytes per line)
+
+// One wavefront's unit of work (item `wave` of the launch: a row, R short rows, a segment, or a
+// quarter of a block-per-row row) in column pass `pass`.  HUB: entries whose column id is negative
+// take their row from `table`; MODE_BLOCK_PER_ROW is not available then.
+template <class IO, int L, int NACC, bool HUB>
+__device__ __forceinline__ void agg_item(const AggArgs& a, const int wave, const int pass,
+                                         const typename IO::elem* table, float (*quarter)[L * IO::kVec * NACC]) {
     using T = typename IO::elem;
     constexpr int VEC = IO::kVec;
     constexpr int R = 64 / L;
@@ -127,24 +150,21 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
     constexpr int UMAX = NACC == 4 ? 2 : 4;
     constexpr int U = L < UMAX ? L : UMAX;
 
-    __shared__ float quarter[3][PASS_W];     // block-per-row mode: sums of wavefronts 1..3
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
-    if (wave >= a.wave_start[a.n_groups]) return;
     int grp = 0;
     while (grp + 1 < a.n_groups && wave >= a.wave_start[grp + 1]) ++grp;
     const int item0 = wave - a.wave_start[grp];
     const int mode = a.mode[grp];
     const int g = lane / L;
     const int l = lane % L;
-    const int colbase = (int)blockIdx.y * PASS_W + l * VEC;
+    const int colbase = pass * PASS_W + l * VEC;
 
     int nval[NACC];            // elements of vector j that lie inside the slice (0..VEC)
     int coff[NACC];            // column offset read by this lane
     // A lane whose vector lies outside the slice re-reads the first vector of its group's
     // 16*L-byte piece (or of the pass, if the whole piece is outside): an address the
     // active lanes fetch anyway, so it adds no cache line to the gather.
-    const int passbase = (int)blockIdx.y * PASS_W;
+    const int passbase = pass * PASS_W;
 #pragma unroll
     for (int j = 0; j < NACC; ++j) {
         const int c = colbase + j * L * VEC;
@@ -163,9 +183,17 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
     for (int j = 0; j < NACC; ++j)
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[j][i] = 0.f;
-    auto store_row = [&](T* y) {
+    // epilogue (a.epilogue): an element is kept where its mask element is > 0, else stored as zero;
+    // the mask element is the same position of row `row` of M, or the output itself (ReLU)
+    auto store_row = [&](T* y, const int row) {
 #pragma unroll
         for (int j = 0; j < NACC; ++j) {
+            if (a.epilogue && nval[j] > 0) {
+                float m[VEC];
+                if (a.M) IO::load(static_cast<const T*>(a.M) + (int64_t)row * a.ldm + colbase + j * L * VEC, m);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[j][i] = (a.M ? m[i] : acc[j][i]) > 0.f ? acc[j][i] : 0.f;
+            }
             if (nval[j] == VEC) IO::store(y + j * L * VEC, acc[j]);
             else {
 #pragma unroll
@@ -175,15 +203,30 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
         }
     };
 
+    // the feature-row vectors of entry c: from memory, or for a hub entry (HUB, c < 0) from the LDS
+    // table; the global load of a hub entry goes to the first hub's row, which stays in the L1
+    const int64_t hub0 = HUB ? (int64_t)a.hub_cols[0] * ldx : 0;
+    auto load_row = [&](const int c, float (&x)[NACC][VEC]) {
+        if constexpr (HUB) {
+            const bool hub = c < 0;
+            const T* xr = X + (hub ? hub0 : (int64_t)c * ldx);
+            const T* xt = table + (hub ? (c & 0x7fffffff) : 0) * (L * VEC) + l * VEC;
+            float t[VEC];
+            IO::load(xr + coff[0], x[0]);
+            IO::load(xt, t);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) x[0][i] = hub ? t[i] : x[0][i];
+        } else {
+            const T* xr = X + (int64_t)c * ldx;
+#pragma unroll
+            for (int j = 0; j < NACC; ++j) IO::load(xr + coff[j], x[j]);
+        }
+    };
     // acc += sum over u < U of w[u] * X[c[u], columns of this lane]; all loads first
     auto gather_u = [&](const int (&c)[U], const float (&w)[U]) {
         float x[U][NACC][VEC];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const T* xr = X + (int64_t)c[u] * ldx;
-#pragma unroll
-            for (int j = 0; j < NACC; ++j) IO::load(xr + coff[j], x[u][j]);
-        }
+        for (int u = 0; u < U; ++u) load_row(c[u], x[u]);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -195,11 +238,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
     auto gather_u_if = [&](const bool (&on)[U], const int (&c)[U], const float (&w)[U]) {
         float x[U][NACC][VEC];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const T* xr = X + (int64_t)c[u] * ldx;
-#pragma unroll
-            for (int j = 0; j < NACC; ++j) IO::load(xr + coff[j], x[u][j]);
-        }
+        for (int u = 0; u < U; ++u) load_row(c[u], x[u]);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -207,6 +246,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[j][i] = fmaf(on[u] ? w[u] : 0.f, on[u] ? x[u][j][i] : 0.f, acc[j][i]);
     };
+    const int32_t* const colidx = HUB ? a.colidx_hub : a.colidx;
 
     if (mode == MODE_GROUP_PER_ROW) {
         // ---- one group of L lanes per row ------------------------------------------
@@ -220,7 +260,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
             beg = a.rowptr[row - a.row_base];
             d = (int)(a.rowptr[row - a.row_base + 1] - beg);
         }
-        const int32_t* ci = a.colidx + (beg - a.e_base);
+        const int32_t* ci = colidx + (beg - a.e_base);
         const float* vv = a.val + (beg - a.e_base);
         for (int k0 = 0; __ballot(k0 < d) != 0; k0 += L) {
             int c = row;
@@ -241,7 +281,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
                 gather_u_if(on, cj, wj);
             }
         }
-        if (valid) store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase);
+        if (valid) store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase, row);
         return;
     }
 
@@ -249,7 +289,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
     int row;
     int64_t beg, end;
     float* pout = nullptr;
-    if (mode == MODE_BLOCK_PER_ROW) {
+    if (!HUB && mode == MODE_BLOCK_PER_ROW) {
         // the block's four wavefronts take a quarter of the row each; the group is the first of
         // the launch, so item0 / 4 is the block and item0 % 4 the wavefront inside it
         row = __builtin_amdgcn_readfirstlane(a.split_rows[a.item_off[grp] + (item0 >> 2)].row);
@@ -269,7 +309,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
         beg = uniform64(a.rowptr[row - a.row_base]);
         end = uniform64(a.rowptr[row - a.row_base + 1]);
     }
-    const int32_t* ci = a.colidx + (beg - a.e_base);
+    const int32_t* ci = colidx + (beg - a.e_base);
     const float* vv = a.val + (beg - a.e_base);
     const int64_t cnt = end - beg;
 
@@ -327,7 +367,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[j][i] += bperm_f(lane ^ off, acc[j][i]);
 
-    if (mode == MODE_BLOCK_PER_ROW) {
+    if (!HUB && mode == MODE_BLOCK_PER_ROW) {
         // wavefronts 1..3 hand their sums to wavefront 0, which adds them in a fixed order
         const int q = item0 & 3;
         if (q > 0 && g == 0) {
@@ -345,7 +385,7 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
                     const int s = (j * VEC + i) * L + l;
                     acc[j][i] = (acc[j][i] + quarter[0][s]) + (quarter[1][s] + quarter[2][s]);
                 }
-            store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase);
+            store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase, row);
         }
         return;
     }
@@ -355,9 +395,53 @@ __global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kerne
             for (int j = 0; j < NACC; ++j)
                 if (nval[j] > 0) store_partial<VEC>(pout + j * L * VEC, acc[j]);
         } else {
-            store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase);
+            store_row(static_cast<T*>(a.Y) + (int64_t)row * a.ldy + colbase, row);
         }
     }
+}
+
+// L lanes per feature row, NACC vectors per lane (columns l*VEC + j*L*VEC), 4 wavefronts
+// per block, every wavefront an independent unit of work.  blockIdx.y walks column passes
+// when the slice is wider than L*VEC*NACC.
+//
+// Gathers are issued U at a time with no branch between them, so that U neighbour rows
+// are in flight per lane before the first multiply-add waits.  To keep the loads free of
+// branches every lane always loads from a valid address: a lane whose columns lie beyond
+// the slice reads the first column of its pass, an entry that does not exist reads the row's own vertex, and
+// what such a load returns is replaced by zero before it is used.
+template <class IO, int L, int NACC>
+__global__ void __launch_bounds__(256, (agg_min_waves<IO, L, NACC>())) agg_kernel(const AggArgs a) {
+    __shared__ float quarter[3][L * IO::kVec * NACC];     // block-per-row mode: sums of wavefronts 1..3
+    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (wave >= a.wave_start[a.n_groups]) return;
+    agg_item<IO, L, NACC, false>(a, wave, (int)blockIdx.y, nullptr, quarter);
+}
+
+// The same work with the hub rows of the column pass in LDS: one block of 16 wavefronts per
+// compute unit; wavefront w of block b takes the items b*16 + w, + 16*gridDim.x, ... (the items are
+// sorted heaviest first, so the shares come out even).
+template <class IO, int L>
+__global__ void __launch_bounds__(1024, 4) agg_hub_kernel(const AggArgs a) {
+    using T = typename IO::elem;
+    constexpr int VEC = IO::kVec;
+    constexpr int LINE = L * VEC;
+    __shared__ __align__(16) T table[HUB_SLOTS * LINE];
+    {
+        const int l = threadIdx.x % L;
+        const int c = (int)blockIdx.y * LINE + l * VEC;
+        const int coff = c < a.f ? c : (int)blockIdx.y * LINE;     // lanes beyond the slice re-read the pass's first vector
+        const T* X = static_cast<const T*>(a.X);
+        for (int s = threadIdx.x / L; s < a.n_hub; s += 1024 / L) {
+            float v[VEC];
+            IO::load(X + (int64_t)a.hub_cols[s] * a.ldx + coff, v);
+            IO::store_plain(table + s * LINE + l * VEC, v);
+        }
+    }
+    __syncthreads();
+    const int total = a.wave_start[a.n_groups];
+    const int w0 = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 16 + (threadIdx.x >> 6)));
+    for (int wave = w0; wave < total; wave += 16 * (int)gridDim.x)
+        agg_item<IO, L, 1, true>(a, wave, (int)blockIdx.y, table, nullptr);
 }
 
 // ---- second pass for split rows: Y[row,:] = sum of its partial-sum slots ---------------
@@ -386,7 +470,16 @@ __global__ void __launch_bounds__(256) reduce_kernel(const ReduceArgs a) {
         part[w][lane] = s;
         __syncthreads();
         if (w == 0 && col < a.f) {
-            const float r = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+            float r = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+            if (a.epilogue) {        // the aggregation's epilogue for rows summed here
+                float m = r;
+                if (a.M) {
+                    const T mv = static_cast<const T*>(a.M)[(int64_t)it.row * a.ldm + col];
+                    if constexpr (sizeof(T) == 4) m = mv;
+                    else m = __uint_as_float((unsigned)mv << 16);
+                }
+                r = m > 0.f ? r : 0.f;
+            }
             T* y = static_cast<T*>(a.Y) + (int64_t)it.row * a.ldy + col;
             if constexpr (sizeof(T) == 4) *y = r;
             else *y = (T)f32_to_bf16_rne(r);
@@ -402,6 +495,26 @@ int launch_one(const AggArgs& a, int n_passes, hipStream_t st) {
     hipLaunchKernelGGL((agg_kernel<IO, L, NACC>), grid, dim3(256), 0, st, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("aggregation kernel launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
+    return NTP_OK;
+}
+
+int compute_units() {
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        return n;
+    }();
+    return cus;
+}
+
+template <class IO, int L>
+int launch_hub(const AggArgs& a, int n_passes, hipStream_t st) {
+    const int total = a.wave_start[a.n_groups];
+    if (total <= 0) return NTP_OK;
+    const int blocks = std::min(compute_units(), (total + 15) / 16);
+    hipLaunchKernelGGL((agg_hub_kernel<IO, L>), dim3((unsigned)blocks, (unsigned)n_passes), dim3(1024), 0, st, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("aggregation kernel (hub table) launch failed: %s", hipGetErrorString(e)); return NTP_EHIP; }
     return NTP_OK;
 }
 
@@ -469,20 +582,38 @@ int agg_pick_pass_lanes(const void* X, int64_t ldx, int dtype, int vec, double e
     return 8;
 }
 
-int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype) {
+int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype, const void* M, int64_t ldm) {
     const int es = dtype == NTP_BF16 ? 2 : 4;
     int vec = 16 / es;
-    const uintptr_t px = (uintptr_t)X, py = (uintptr_t)Y;
+    const uintptr_t px = (uintptr_t)X, py = (uintptr_t)Y, pm = (uintptr_t)M;
     (void)f;   // the slice width need not be a multiple: a straddling vector is read whole, stored by element
-    while (vec > 1 && (ldx % vec || ldy % vec || px % (uintptr_t)(vec * es) || py % (uintptr_t)(vec * es))) vec >>= 1;
+    while (vec > 1 && (ldx % vec || ldy % vec || px % (uintptr_t)(vec * es) || py % (uintptr_t)(vec * es) ||
+                       (M && (ldm % vec || pm % (uintptr_t)(vec * es))))) vec >>= 1;
     return vec;
+}
+
+int agg_hub_slots() { return HUB_SLOTS; }
+
+// The hub kernel exists for rows walked in 16-byte vectors by 4 or 8 lanes (64- and 128-byte
+// lines per pass), on graphs that were built with a hub table (NTP_AGG_HUB=1 at build time).
+bool agg_uses_hub(const AggArgs& a, int dtype) {
+    if (!a.colidx_hub || a.n_hub <= 0 || !a.hub_cols) return false;
+    const int vec = agg_pick_vec(a.X, a.Y, a.f, a.ldx, a.ldy, dtype, a.M, a.ldm);
+    if (vec * (dtype == NTP_BF16 ? 2 : 4) != 16) return false;
+    int L, nacc, passes;
+    agg_shape(a.f, vec, a.pass_lanes, &L, &nacc, &passes);
+    return nacc == 1 && (L == 8 || L == 4);
 }
 
 int launch_aggregate(const AggArgs& a, int dtype, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    const int vec = agg_pick_vec(a.X, a.Y, a.f, a.ldx, a.ldy, dtype);
+    const int vec = agg_pick_vec(a.X, a.Y, a.f, a.ldx, a.ldy, dtype, a.M, a.ldm);
     int L, nacc, passes;
     agg_shape(a.f, vec, a.pass_lanes, &L, &nacc, &passes);
+    if (agg_uses_hub(a, dtype)) {
+        if (dtype == NTP_F32) return L == 8 ? launch_hub<IoF32<4>, 8>(a, passes, st) : launch_hub<IoF32<4>, 4>(a, passes, st);
+        return L == 8 ? launch_hub<IoBf16<8>, 8>(a, passes, st) : launch_hub<IoBf16<8>, 4>(a, passes, st);
+    }
     if (dtype == NTP_F32) {
         switch (vec) {
             case 4: return launch_by_shape<IoF32<4>>(a, L, nacc, passes, st);

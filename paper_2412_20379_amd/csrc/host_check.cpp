@@ -114,6 +114,42 @@ void check_plan(const HostSparse& m, const Plan& P, int64_t chunk_edges, const c
         CHECK(covered[v] == m.rowptr[v + 1] - m.rowptr[v], "%s: row %" PRId64 " covered %" PRId64 " of %" PRId64, what, v, covered[v], m.rowptr[v + 1] - m.rowptr[v]);
 }
 
+// hub columns: the most gathered ones, most first, none below the bound; the encoded ids decode back
+void check_hubs(const HostSparse& m, const HostSparse* transposed, const char* what) {
+    std::vector<int64_t> count((size_t)m.n, 0);
+    for (int64_t k = 0; k < m.nnz; ++k) ++count[(size_t)m.colidx[k]];
+    for (int slots : {1, 5, 1024})
+        for (int64_t min_count : {(int64_t)1, (int64_t)3, (int64_t)1000000}) {
+            std::vector<int32_t> hubs, counted;
+            pick_hub_columns(m, transposed, slots, min_count, &hubs);
+            pick_hub_columns(m, nullptr, slots, min_count, &counted);
+            CHECK(hubs == counted, "%s: hub columns differ between the two ways of counting", what);
+            CHECK((int)hubs.size() <= slots, "%s: %zu hubs for %d slots", what, hubs.size(), slots);
+            std::vector<char> is_hub((size_t)m.n, 0);
+            int64_t least = INT64_MAX;
+            for (size_t i = 0; i < hubs.size(); ++i) {
+                const int32_t c = hubs[i];
+                CHECK(c >= 0 && c < m.n && !is_hub[(size_t)c], "%s: bad hub column", what);
+                is_hub[(size_t)c] = 1;
+                CHECK(count[(size_t)c] >= min_count, "%s: hub below the bound", what);
+                if (i > 0) CHECK(count[(size_t)hubs[i - 1]] > count[(size_t)c] || (count[(size_t)hubs[i - 1]] == count[(size_t)c] && hubs[i - 1] < c), "%s: hub order", what);
+                least = count[(size_t)c] < least ? count[(size_t)c] : least;
+            }
+            for (int64_t c = 0; c < m.n; ++c)
+                if (!is_hub[(size_t)c] && count[(size_t)c] >= min_count)
+                    CHECK((int)hubs.size() == slots && count[(size_t)c] <= least, "%s: column %" PRId64 " with %" PRId64 " entries left out", what, c, count[(size_t)c]);
+            if (m.nnz == 0) continue;
+            const int64_t e0 = m.nnz / 3, e1 = m.nnz - m.nnz / 5;
+            std::vector<int32_t> enc((size_t)(e1 - e0));
+            encode_hub_columns(m, hubs, e0, e1, enc.data());
+            for (int64_t k = e0; k < e1; ++k) {
+                const int32_t e = enc[(size_t)(k - e0)], c = m.colidx[k];
+                if (is_hub[(size_t)c]) CHECK(e < 0 && (size_t)(e & 0x7fffffff) < hubs.size() && hubs[(size_t)(e & 0x7fffffff)] == c, "%s: hub entry encoded wrongly", what);
+                else CHECK(e == c, "%s: plain entry changed", what);
+            }
+        }
+}
+
 void build_and_plan(int64_t n, const std::vector<int32_t>& src, const std::vector<int32_t>& dst, const float* w, uint32_t flags, const char* what) {
     BuiltGraph G;
     EntryAllocator alloc{alloc_plain, nullptr, alloc_plain};
@@ -133,6 +169,8 @@ void build_and_plan(int64_t n, const std::vector<int32_t>& src, const std::vecto
                 CHECK(p >= 0 && p < G.csr.nnz && G.csr.colidx[p] == u && G.csr.val[p] == G.csc.val[k], "%s: edge permutation", what);
             }
     }
+    check_hubs(G.csr, G.symmetric ? &G.csr : (G.has_csc ? &G.csc : nullptr), what);
+    if (G.has_csc && !G.symmetric) check_hubs(G.csc, &G.csr, what);
     for (int64_t ce : {(int64_t)0, (int64_t)1, (int64_t)7, (int64_t)100, (int64_t)5000}) {
         Plan P;
         make_plan(G.csr, ce, &P);

@@ -31,6 +31,7 @@ struct Form {
     // segments, in chunk order, on the device (one reduce_kernel launch per pass)
     ReduceItem* d_all_reduce = nullptr;
     int n_all_reduce = 0;
+    int32_t* d_hub_cols = nullptr;      // the form's hub columns on the device (plan.hub_cols), when it has a hub table
     bool one_reduce() const { return d_all_reduce != nullptr; }
 };
 
@@ -129,6 +130,13 @@ int upload_chunk(const HostSparse& m, Chunk& c, char* dst, hipStream_t st, bool 
     return NTP_OK;
 }
 
+// what the aggregation does to an output element on its way out (AggArgs::epilogue)
+struct Epilogue {
+    bool on = false;
+    const void* M = nullptr;       // mask source (nullptr: the output itself, i.e. ReLU)
+    int64_t ldm = 0;
+};
+
 inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX : (1 << b)); }
 
 // Enqueue the kernels of one chunk whose image lives at `img` on the device.
@@ -136,7 +144,8 @@ inline int bin_max_degree(int b) { return b == 0 ? 1 : (b == NBINS - 1 ? INT_MAX
 // weights: caller's edge weights in the entry order of the form (nullptr: the stored ones)
 int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* partial,
               int64_t f, int64_t ldx, int64_t ldy, int dtype, hipStream_t st, bool scatter = false,
-              const float* weights = nullptr, const int32_t* columns = nullptr, bool defer_reduce = false) {
+              const float* weights = nullptr, const int32_t* columns = nullptr, bool defer_reduce = false,
+              const int32_t* hub_cols = nullptr, int n_hub = 0, const Epilogue& epi = Epilogue()) {
     AggArgs a;
     memset(&a, 0, sizeof a);
     a.rowptr = reinterpret_cast<const int64_t*>(img + c.off_rowptr);
@@ -146,6 +155,9 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
     a.val = weights ? weights + c.e_begin : reinterpret_cast<const float*>(img + c.img_off_val);
     a.X = X;
     a.Y = Y;
+    a.M = epi.M;
+    a.ldm = epi.ldm;
+    a.epilogue = epi.on ? 1 : 0;
     a.partial = partial;
     a.row_base = c.row_begin;
     a.e_base = c.e_begin;
@@ -158,12 +170,19 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
     if (scatter) {
         L = scatter_lanes(f);
     } else {
-        const int vec = agg_pick_vec(X, Y, f, ldx, ldy, dtype);
+        const int vec = agg_pick_vec(X, Y, f, ldx, ldy, dtype, epi.M, epi.ldm);
         const int64_t rows = c.partial_row ? 1 : c.row_end - c.row_begin;
         a.pass_lanes = agg_pick_pass_lanes(X, ldx, dtype, vec, (double)(c.e_end - c.e_begin) / (double)std::max<int64_t>(1, rows));
         agg_shape(f, vec, a.pass_lanes, &L, &nacc, &passes);
     }
     const int R = 64 / L;
+    bool hub = false;
+    if (!scatter && !columns && c.d_colidx_hub && hub_cols) {
+        a.colidx_hub = c.d_colidx_hub;
+        a.hub_cols = hub_cols;
+        a.n_hub = n_hub;
+        hub = agg_uses_hub(a, dtype);
+    }
 
     int ng = 0;
     int64_t waves = 0;
@@ -175,7 +194,7 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
         waves += nw;
         ++ng;
     };
-    const bool block_rows = !scatter && c.block_rows;      // split rows summed by one block each (see make_plan)
+    const bool block_rows = !scatter && !hub && c.block_rows;      // split rows summed by one block each (see make_plan)
     a.split_rows = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
     // heaviest work first: split rows, then bins from long rows to short rows
     if (block_rows) add_group(MODE_BLOCK_PER_ROW, 0, c.n_reduce, 4 * (int64_t)c.n_reduce);   // first: block-aligned
@@ -200,6 +219,9 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
         r.items = reinterpret_cast<const ReduceItem*>(img + c.off_reduce);
         r.partial = partial;
         r.Y = Y;
+        r.M = epi.M;
+        r.ldm = epi.ldm;
+        r.epilogue = epi.on ? 1 : 0;
         r.ldy = ldy;
         r.f = (int32_t)f;
         r.fp = (int32_t)((f + 7) / 8 * 8);
@@ -212,12 +234,15 @@ int run_chunk(const Chunk& c, const char* img, const void* X, void* Y, float* pa
 
 // One reduce_kernel launch for the split rows of every chunk of a form (their items were
 // gathered on the device at build time): replaces one launch per chunk when a form has several.
-int reduce_all(const Form& F, float* partial, void* Y, int64_t f, int64_t ldy, int dtype, hipStream_t st) {
+int reduce_all(const Form& F, float* partial, void* Y, int64_t f, int64_t ldy, int dtype, hipStream_t st, const Epilogue& epi = Epilogue()) {
     if (F.n_all_reduce == 0) return NTP_OK;
     ReduceArgs r;
     r.items = F.d_all_reduce;
     r.partial = partial;
     r.Y = Y;
+    r.M = epi.M;
+    r.ldm = epi.ldm;
+    r.epilogue = epi.on ? 1 : 0;
     r.ldy = ldy;
     r.f = (int32_t)f;
     r.fp = (int32_t)((f + 7) / 8 * 8);
@@ -282,6 +307,9 @@ void destroy(ntp_graph* G) {
     for (int k = 0; k < 2; ++k) {
         for (auto& c : G->form[k].plan.chunks)
             if (c.d_image) (void)hipFree(c.d_image);
+        for (auto& c : G->form[k].plan.chunks)
+            if (c.d_colidx_hub) (void)hipFree(c.d_colidx_hub);
+        if (G->form[k].d_hub_cols) (void)hipFree(G->form[k].d_hub_cols);
         if (G->form[k].d_all_reduce) (void)hipFree(G->form[k].d_all_reduce);
         if (G->stage[k]) (void)hipFree(G->stage[k]);
         if (G->ev_ready[k]) (void)hipEventDestroy(G->ev_ready[k]);
@@ -445,6 +473,46 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
                         off += c.meta.size();
                     }
         }
+        // Hub tables (opt-in: NTP_AGG_HUB=1 in the environment of the build call; measured slower than
+        // the plain kernel, see agg_kernels.hip): for a fully resident topology with room for 4 more
+        // bytes per entry, the most gathered columns of each form get LDS slots and a second column-id
+        // array names them.  A column is worth a slot when it is gathered more often than the table is
+        // filled (once per compute unit and column pass): NTP_AGG_HUB_MIN_COUNT overrides the bound,
+        // NTP_AGG_HUB_SLOTS the number of slots.
+        const char* hub_env = getenv("NTP_AGG_HUB");
+        if (fits && n > 0 && hub_env && hub_env[0] == '1') {
+            int64_t min_count = 256;
+            if (const char* e = getenv("NTP_AGG_HUB_MIN_COUNT")) min_count = std::max<int64_t>(1, atoll(e));
+            int64_t extra = 0;
+            for (int k = 0; k < n_forms; ++k) extra += G->form[k].m->nnz * 4;
+            if (budget == 0 || (int64_t)all + extra <= budget) {
+                for (int k = 0; k < n_forms; ++k) {
+                    Form& F = G->form[k];
+                    const HostSparse* transposed = k == 1 ? &G->g.csr : (G->g.symmetric ? &G->g.csr : (G->g.has_csc ? &G->g.csc : nullptr));
+                    int slots = agg_hub_slots();
+                    if (const char* e = getenv("NTP_AGG_HUB_SLOTS")) slots = std::max(1, std::min(slots, atoi(e)));
+                    pick_hub_columns(*F.m, transposed, slots, min_count, &F.plan.hub_cols);
+                    if (F.plan.hub_cols.empty()) continue;
+                    void* p = nullptr;
+                    const size_t hb = F.plan.hub_cols.size() * 4;
+                    if (hipMalloc(&p, hb) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes for the hub columns failed", hb); return NTP_ENOMEM; }
+                    F.d_hub_cols = (int32_t*)p;
+                    G->device_bytes += (int64_t)hb;
+                    if (hipMemcpy(p, F.plan.hub_cols.data(), hb, hipMemcpyHostToDevice) != hipSuccess) { (void)hipGetLastError(); set_error("upload of the hub columns failed"); return NTP_EHIP; }
+                    std::vector<int32_t> enc;
+                    for (auto& c : F.plan.chunks) {
+                        const size_t ne = (size_t)(c.e_end - c.e_begin);
+                        if (ne == 0) continue;
+                        enc.resize(ne);
+                        encode_hub_columns(*F.m, F.plan.hub_cols, c.e_begin, c.e_end, enc.data());
+                        if (hipMalloc(&p, ne * 4) != hipSuccess) { (void)hipGetLastError(); set_error("device allocation of %zu bytes for the hub column ids failed", ne * 4); return NTP_ENOMEM; }
+                        c.d_colidx_hub = (int32_t*)p;
+                        G->device_bytes += (int64_t)(ne * 4);
+                        if (hipMemcpy(p, enc.data(), ne * 4, hipMemcpyHostToDevice) != hipSuccess) { (void)hipGetLastError(); set_error("upload of the hub column ids failed"); return NTP_EHIP; }
+                    }
+                }
+            }
+        }
         bool any_streamed = false;
         for (int k = 0; k < n_forms; ++k) any_streamed = any_streamed || !G->form[k].all_resident;
         if (any_streamed && G->g.val_mode == VAL_GCN && n > 0) {
@@ -588,7 +656,8 @@ static int aggregate_resident(ntp_graph_t* g, int which, const void* X, void* Y,
     }
     if (rc != NTP_OK) return rc;
     for (auto& c : F.plan.chunks) {
-        rc = run_chunk(c, c.d_image, X, Y, partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights, columns, F.one_reduce());
+        rc = run_chunk(c, c.d_image, X, Y, partial, f, ldx, ldy, dtype, (hipStream_t)stream, scatter, weights, columns, F.one_reduce(),
+                       F.d_hub_cols, (int)F.plan.hub_cols.size());
         if (rc != NTP_OK) return rc;
     }
     if (!scatter && F.one_reduce()) return reduce_all(F, partial, Y, f, ldy, dtype, (hipStream_t)stream);
@@ -610,9 +679,9 @@ int ntp_aggregate_bwd(ntp_graph_t* g, const void* Gout, void* Gin, int64_t f, in
     return aggregate_resident(g, NTP_CSC, Gout, Gin, f, ldo, ldi, dtype, stream);
 }
 
-int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
-                                const void* const* X, void* const* Y, int64_t f,
-                                int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream) {
+static int chunked_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
+                         const void* const* X, void* const* Y, int64_t f,
+                         int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream, const Epilogue& epi) {
     if (n_rhs < 1 || n_rhs > 64) { set_error("n_rhs must be in 1..64"); return NTP_EINVAL; }
     if (!X || !Y) { set_error("X or Y is NULL"); return NTP_EINVAL; }
     int rc;
@@ -644,7 +713,7 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
     auto run_all = [&](const Chunk& c, const char* img) -> int {
         for (int r = 0; r < n_rhs; ++r) {
             const int e = run_chunk(c, img, X[r], Y[r], scatter ? nullptr : g->partial + (size_t)r * pstride, f, ldx, ldy, dtype, cs, scatter,
-                                    nullptr, nullptr, F.one_reduce());
+                                    nullptr, nullptr, F.one_reduce(), F.d_hub_cols, (int)F.plan.hub_cols.size(), epi);
             if (e != NTP_OK) return e;
         }
         return NTP_OK;
@@ -680,10 +749,37 @@ int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
     }
     if (!scatter && F.one_reduce())
         for (int r = 0; r < n_rhs; ++r) {
-            rc = reduce_all(F, g->partial + (size_t)r * pstride, Y[r], f, ldy, dtype, cs);
+            rc = reduce_all(F, g->partial + (size_t)r * pstride, Y[r], f, ldy, dtype, cs, epi);
             if (rc != NTP_OK) return rc;
         }
     return NTP_OK;
+}
+
+int ntp_chunked_aggregate_multi(ntp_graph_t* g, int direction, int32_t n_rhs,
+                                const void* const* X, void* const* Y, int64_t f,
+                                int64_t ldx, int64_t ldy, int dtype, void* compute_stream, void* copy_stream) {
+    return chunked_multi(g, direction, n_rhs, X, Y, f, ldx, ldy, dtype, compute_stream, copy_stream, Epilogue());
+}
+
+int ntp_aggregate_act(ntp_graph_t* g, int direction, const void* X, void* Y, int64_t f, int64_t ldx, int64_t ldy,
+                      int dtype, int act, const void* M, int64_t ldm, void* compute_stream, void* copy_stream) {
+    if (act != NTP_ACT_NONE && act != NTP_ACT_RELU) { set_error("unknown activation %d", act); return NTP_EINVAL; }
+    Epilogue epi;
+    if (act == NTP_ACT_RELU) {
+        epi.on = true;
+        epi.M = M;
+        epi.ldm = M ? ldm : 0;
+        if (M && ldm < f) { set_error("row stride of the mask smaller than the slice width"); return NTP_EINVAL; }
+        if (M && g && g->g.n > 0 && views_overlap(M, ldm, Y, ldy, g->g.n, f, dtype == NTP_BF16 ? 2 : 4)) {
+            set_error("the mask and the output must not overlap");
+            return NTP_EINVAL;
+        }
+        if (g && direction == NTP_BWD && g->scatter_bwd()) {
+            set_error("graph was built with NTP_SCATTER_BWD: the scatter-add backward has no epilogue (use ntp_relu_bwd)");
+            return NTP_EUNSUPPORTED;
+        }
+    }
+    return chunked_multi(g, direction, 1, &X, &Y, f, ldx, ldy, dtype, compute_stream, copy_stream, epi);
 }
 
 int ntp_chunked_aggregate(ntp_graph_t* g, int direction, const void* X, void* Y, int64_t f,

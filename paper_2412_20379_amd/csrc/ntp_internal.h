@@ -118,11 +118,15 @@ struct Chunk {
     // device image layout: [meta | colidx | val], each part 256-byte aligned
     size_t img_off_colidx = 0, img_off_val = 0, img_bytes = 0;
     // residency
+    int32_t* d_colidx_hub = nullptr;           // resident chunks of a form with a hub table: hub-encoded column ids
     char* d_image = nullptr;                   // device image if resident
     char* h_meta_pinned = nullptr;             // pinned copy of meta for streaming
 };
 
 struct Plan {
+    // the most gathered columns of the form, most gathered first (at most agg_hub_slots(); empty: no
+    // hub table): the aggregation keeps their feature rows in LDS (agg_kernels.hip)
+    std::vector<int32_t> hub_cols;
     int64_t seg_len = 0;
     int64_t split_threshold = 0;
     int64_t chunk_edges = 0;
@@ -134,6 +138,14 @@ struct Plan {
 // Build the plan of one compressed form.  chunk_edges <= 0: a single chunk.
 void make_plan(const HostSparse& m, int64_t chunk_edges, Plan* plan);
 
+// The hub columns of a form: the up to max_slots columns with most entries, most first (ties by
+// id), among those with at least min_count entries.  transposed (nullable): the other compressed
+// form of the same matrix (this form itself if symmetric), whose row lengths are the column counts.
+void pick_hub_columns(const HostSparse& m, const HostSparse* transposed, int max_slots, int64_t min_count,
+                      std::vector<int32_t>* hub_cols);
+// out[k] = 0x80000000 | slot for entries e_begin + k whose column is a hub, else the column id
+void encode_hub_columns(const HostSparse& m, const std::vector<int32_t>& hub_cols, int64_t e_begin, int64_t e_end, int32_t* out);
+
 // ---------------------------------------------------------------------------------------
 // Argument block of the aggregation kernel (passed by value).
 struct AggArgs {
@@ -143,15 +155,21 @@ struct AggArgs {
     const int32_t* rows;       // bin row lists (global row ids)
     const Segment* segs;
     const ReduceItem* split_rows;   // the chunk's split rows (block-per-row mode)
+    const int32_t* colidx_hub; // chunk slice of the column ids with the hub columns replaced by 0x80000000 | slot
+                               // (nullptr: the chunk has no hub table)
+    const int32_t* hub_cols;   // [n_hub] vertex ids of the hub columns in slot order
     const void* X;
     void* Y;
+    const void* M;             // epilogue mask source, rows indexed like Y (nullptr: the output itself)
     float* partial;            // [n_slots x fp] partial sums of split rows
     int64_t row_base;
     int64_t e_base;
-    int64_t ldx, ldy;
+    int64_t ldx, ldy, ldm;
+    int32_t epilogue;          // 1: an output element is kept where its mask element (M, or itself) is > 0, else stored as 0
     int32_t f;                 // slice width
     int32_t fp;                // row stride of `partial` in floats: f rounded up to 8
     int32_t pass_lanes;        // vectors per feature row and column pass (0: widest shape)
+    int32_t n_hub;             // hub columns (at most agg_hub_slots())
     int32_t n_groups;          // entries used in the tables below
     int32_t wave_start[NGROUPS + 1];   // first wavefront of each group; last = total
     int32_t item_off[NGROUPS];         // offset into rows[] (bins) or segs[] (segment group)
@@ -164,7 +182,9 @@ struct ReduceArgs {
     const ReduceItem* items;
     const float* partial;
     void* Y;
-    int64_t ldy;
+    const void* M;             // epilogue mask source (see AggArgs)
+    int64_t ldy, ldm;
+    int32_t epilogue;
     int32_t f;
     int32_t fp;                // row stride of `partial` in floats
     int32_t n_items;
@@ -173,6 +193,9 @@ struct ReduceArgs {
 // kernels (agg_kernels.hip / nn_kernels.hip); stream is a hipStream_t
 int launch_aggregate(const AggArgs& a, int dtype, void* stream);
 int launch_reduce(const ReduceArgs& a, int dtype, void* stream);
+int agg_hub_slots();               // lines of the LDS hub table
+// does the launch of `a` (already holding X, Y, f, strides, pass_lanes) take the hub kernel?
+bool agg_uses_hub(const AggArgs& a, int dtype);
 // transposed product by scatter-add over the same rows: Y[colidx[k], :] += val[k] * X[row, :] (fp32 only)
 int launch_scatter(const AggArgs& a, void* stream);
 int scatter_lanes(int64_t f);      // lanes per feature row the scatter kernel uses for width f
@@ -181,7 +204,7 @@ int launch_zero_rows(void* Y, int64_t n, int64_t f, int64_t ld, int dtype, void*
 // lanes per row chosen for (f, vec): exposed for tests of the host logic
 void agg_shape(int64_t f, int vec, int pass_lanes, int* lanes_per_row, int* n_acc, int* n_passes);
 int agg_pick_pass_lanes(const void* X, int64_t ldx, int dtype, int vec, double entries_per_row);
-int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype);
+int agg_pick_vec(const void* X, const void* Y, int64_t f, int64_t ldx, int64_t ldy, int dtype, const void* M = nullptr, int64_t ldm = 0);
 
 // edge attention weights (attention_kernels.hip)
 struct AttArgs {

@@ -75,6 +75,41 @@ struct ChunkBuilder {
 
 }  // namespace
 
+void pick_hub_columns(const HostSparse& m, const HostSparse* transposed, int max_slots, int64_t min_count,
+                      std::vector<int32_t>* hub_cols) {
+    hub_cols->clear();
+    if (m.n <= 0 || m.nnz <= 0 || max_slots <= 0) return;
+    // entries per column: the row lengths of the transposed form when there is one, else counted
+    std::vector<int32_t> counted;
+    if (!transposed) {
+        counted.assign((size_t)m.n, 0);
+        for (int64_t k = 0; k < m.nnz; ++k) ++counted[(size_t)m.colidx[k]];
+    }
+    std::vector<std::pair<int64_t, int32_t>> cand;        // (-count, id): ascending = most gathered first, ties by id
+    for (int64_t c = 0; c < m.n; ++c) {
+        const int64_t total = transposed ? transposed->rowptr[(size_t)c + 1] - transposed->rowptr[(size_t)c] : counted[(size_t)c];
+        if (total >= min_count) cand.emplace_back(-total, (int32_t)c);
+    }
+    const size_t k = std::min<size_t>((size_t)max_slots, cand.size());
+    std::partial_sort(cand.begin(), cand.begin() + (std::ptrdiff_t)k, cand.end());
+    for (size_t i = 0; i < k; ++i) hub_cols->push_back(cand[i].second);
+}
+
+void encode_hub_columns(const HostSparse& m, const std::vector<int32_t>& hub_cols, int64_t e_begin, int64_t e_end, int32_t* out) {
+    std::vector<int32_t> slot_of((size_t)m.n, -1);
+    for (size_t s = 0; s < hub_cols.size(); ++s) slot_of[(size_t)hub_cols[s]] = (int32_t)s;
+    const int64_t ne = e_end - e_begin;
+    const int T = std::max(1, std::min(host_threads(), (int)std::min<int64_t>(16, ne / (1 << 20) + 1)));
+    parallel_for_threads(T, [&](int t, int nt) {
+        const int64_t lo = e_begin + ne * t / nt, hi = e_begin + ne * (t + 1) / nt;
+        for (int64_t k = lo; k < hi; ++k) {
+            const int32_t c = m.colidx[k];
+            const int32_t s = slot_of[(size_t)c];
+            out[k - e_begin] = s >= 0 ? (int32_t)(0x80000000u | (uint32_t)s) : c;
+        }
+    });
+}
+
 void make_plan(const HostSparse& m, int64_t chunk_edges, Plan* plan) {
     Plan& P = *plan;
     P = Plan();

@@ -31,7 +31,10 @@ class GcnEpoch:
     """
 
     def __init__(self, graph: ntp.Graph, n: int, dims, device="cuda:0", order="layerwise", chunked=False,
-                 overlap_dw=False, pad_classes=True):
+                 overlap_dw=False, pad_classes=True, fuse_activation=True):
+        # fuse_activation: activations that directly follow an aggregation ride on its way out
+        # (ntp_aggregate_act) instead of taking a pass of their own (ntp_relu_fwd / ntp_relu_bwd, or
+        # the mask reads of ntp_nn_bwd)
         # A class count that is not a multiple of four floats makes every row of the logits (and of
         # whatever is aggregated at that width) start off a 16-byte boundary.  The last transform
         # then gets zero columns appended up to whole 128-byte lines (16-byte vectors below 32
@@ -75,6 +78,7 @@ class GcnEpoch:
         self.ws2 = torch.empty(max(ws, 4), dtype=torch.uint8, device=device) if overlap_dw else None
         self.loss = None
         self.logits = None
+        self.fuse_activation = fuse_activation
         self.events = None      # set to a list to collect (tag, start, end) HIP events per library call
 
     def _timed(self, tag, fn, *a):
@@ -94,8 +98,23 @@ class GcnEpoch:
         tag = "nn_bwd %dx%d%s" % (a[7], a[8], "" if a[4] is None else (" +dA" if a[5] is not None else " dA only"))
         self._timed(tag, ntp.ntp_nn_bwd, *a)
 
-    def _agg(self, direction, src, dst, f):
-        self._timed("agg_%s f=%d" % ("fwd" if direction == ntp.NTP_FWD else "bwd", f), self._agg_call, direction, src, dst, f)
+    def _agg(self, direction, src, dst, f, relu=False, mask=None):
+        """aggregate; relu / mask: with the activation applied on the way out (ntp_aggregate_act):
+        forward ReLU of a transform-first layer, or the backward mask 1[mask > 0] of the ReLU layer
+        below.  Returns False when the activation could not ride along (scatter-add backward) and
+        the plain aggregation ran instead."""
+        tag = "agg_%s f=%d" % ("fwd" if direction == ntp.NTP_FWD else "bwd", f)
+        if (relu or mask is not None) and self.fuse_activation:
+            try:
+                self._timed(tag, ntp.ntp_aggregate_act, self.g, direction, src, dst, f, f, f, ntp.NTP_F32, ntp.NTP_ACT_RELU,
+                            mask, f, torch.cuda.current_stream(), self.copy_stream)
+                return True
+            except ntp.NtpError as e:
+                if e.code != ntp.NTP_EUNSUPPORTED:
+                    raise
+                self.fuse_activation = False
+        self._timed(tag, self._agg_call, direction, src, dst, f)
+        return False
 
     def _agg_call(self, direction, src, dst, f):
         st = torch.cuda.current_stream()
@@ -145,8 +164,7 @@ class GcnEpoch:
             if tf[l]:
                 # sigma(A_hat (H W)): transform first, aggregate at the output width, then activate
                 self._nn_fwd(H, Ws[l], self.tbuf[l], n, d[l], d[l + 1], ntp.NTP_ACT_NONE, ntp.NTP_F32, st)
-                self._agg(ntp.NTP_FWD, self.tbuf[l], self.hid[l], d[l + 1])
-                if not last:
+                if not self._agg(ntp.NTP_FWD, self.tbuf[l], self.hid[l], d[l + 1], relu=not last) and not last:
                     self._timed("relu_fwd %d" % d[l + 1], ntp.ntp_relu_fwd, self.hid[l], n, d[l + 1], d[l + 1], ntp.NTP_F32, st)
             else:
                 self._agg(ntp.NTP_FWD, H, self.aggs[l], d[l])
@@ -156,13 +174,15 @@ class GcnEpoch:
         self.logits = H
         dH = self._loss_grad(H, labels)
         pending = None      # event of the last dW issued on the side stream
+        masked = False      # dH already carries the mask of this layer's ReLU (applied by the aggregation that produced it)
         for l in range(L - 1, -1, -1):
             last = l == L - 1
+            was_masked, masked = masked, False
             if tf[l]:
                 if pending is not None:
                     st.wait_event(pending)
                     pending = None
-                if not last:       # dZ = dH * 1[H > 0], in place
+                if not last and not was_masked:       # dZ = dH * 1[H > 0], in place
                     self._timed("relu_bwd %d" % d[l + 1], ntp.ntp_relu_bwd, dH, self.hid[l], dH, n, d[l + 1], d[l + 1], ntp.NTP_F32, st)
                 dT = self.tbuf[l]  # dT = A_hat^T dZ at the output width; then dW = H_in^T dT, dH_in = dT W^T
                 self._agg(ntp.NTP_BWD, dH, dT, d[l + 1])
@@ -171,7 +191,7 @@ class GcnEpoch:
                              ntp.NTP_ACT_NONE, ntp.NTP_F32, self.ws, self.ws_bytes, st)
                 dH = dHin
             elif self.overlap_dw and l > 0:
-                act = ntp.NTP_ACT_NONE if last else ntp.NTP_ACT_RELU
+                act = ntp.NTP_ACT_NONE if (last or was_masked) else ntp.NTP_ACT_RELU
                 # dW beside dA + aggregation: the side stream reads dH, which therefore must not
                 # be overwritten before its event; three scratch buffers rotate
                 ready = torch.cuda.Event()
@@ -191,11 +211,11 @@ class GcnEpoch:
                 used.add(dA.data_ptr())
                 io = next(i for i in range(3) if self.tmp[i].data_ptr() not in used)
                 out = self._view(io, d[l])
-                self._agg(ntp.NTP_BWD, dA, out, d[l])
+                masked = self._agg(ntp.NTP_BWD, dA, out, d[l], mask=self.hid[l - 1])
                 dH = out
                 pending = done
             else:
-                act = ntp.NTP_ACT_NONE if last else ntp.NTP_ACT_RELU
+                act = ntp.NTP_ACT_NONE if (last or was_masked) else ntp.NTP_ACT_RELU
                 dA = self._other_view(dH, d[l]) if l > 0 else None
                 if pending is not None:
                     st.wait_event(pending)
@@ -204,7 +224,7 @@ class GcnEpoch:
                              ntp.NTP_F32, self.ws, self.ws_bytes, st)
                 if l > 0:
                     dH = self._other_view(dA, d[l])
-                    self._agg(ntp.NTP_BWD, dA, dH, d[l])
+                    masked = self._agg(ntp.NTP_BWD, dA, dH, d[l], mask=self.hid[l - 1])
         if pending is not None:
             st.wait_event(pending)
         return self.loss

@@ -78,10 +78,14 @@ class TensorParallelEpoch:
         e1.record()
         self.events.append((tag, e0, e1))
 
-    def _agg(self, direction, src, dst, f, ld):
+    def _agg(self, direction, src, dst, f, ld, mask=None):
         st = torch.cuda.current_stream()
         tag = "agg_%s f=%d" % ("fwd" if direction == ntp.NTP_FWD else "bwd", f)
-        if self.chunked:
+        if mask is not None:
+            # the gradient flows back into a ReLU layer: its mask rides on the aggregation's way out
+            self._timed(tag, ntp.ntp_aggregate_act, self.g, direction, src, dst, f, ld, ld, ntp.NTP_F32, ntp.NTP_ACT_RELU,
+                        mask, ld, st, self.copy_stream)
+        elif self.chunked:
             self._timed(tag, ntp.ntp_chunked_aggregate, self.g, direction, src, dst, f, ld, ld, ntp.NTP_F32, st, self.copy_stream)
         elif direction == ntp.NTP_FWD:
             self._timed(tag, ntp.ntp_aggregate_fwd, self.g, src, dst, f, ld, ld, ntp.NTP_F32, st)
@@ -96,7 +100,9 @@ class TensorParallelEpoch:
     def agg_bwd(self, l, w):
         c0, c1 = self.cols[l][w]
         if c1 > c0:
-            self._agg(ntp.NTP_BWD, self.dS[l][w], self.dT[l][w], c1 - c0, self.ld[l])
+            # the result is the gradient at H_{l-1}, whose slice this worker holds as the input of
+            # its forward aggregation: masked by its sign, it is dZ of layer l-1 already
+            self._agg(ntp.NTP_BWD, self.dS[l][w], self.dT[l][w], c1 - c0, self.ld[l], mask=self.S[l][w])
 
     def nn_fwd(self, l, w):
         r0, r1 = self.rows[w]
@@ -110,10 +116,10 @@ class TensorParallelEpoch:
         r0, r1 = self.rows[w]
         d = self.dims
         if r1 > r0:
-            act = ntp.NTP_ACT_RELU if l < self.L - 1 else ntp.NTP_ACT_NONE
+            # no activation here: the gradient of a hidden layer arrives masked (agg_bwd), the last layer has none
             self._timed("nn_bwd %dx%d%s" % (d[l], d[l + 1], " +dA" if l > 0 else ""), ntp.ntp_nn_bwd,
                         self.A[l][r0:r1], self.weights[l], self.H[l][r0:r1], self.dH[l][r0:r1],
-                        self.dA[l][r0:r1] if l > 0 else None, self.dW_part[l][w], r1 - r0, d[l], d[l + 1], act, ntp.NTP_F32,
+                        self.dA[l][r0:r1] if l > 0 else None, self.dW_part[l][w], r1 - r0, d[l], d[l + 1], ntp.NTP_ACT_NONE, ntp.NTP_F32,
                         self.ws, self.ws_bytes, torch.cuda.current_stream())
         else:
             self.dW_part[l][w].zero_()
