@@ -56,7 +56,8 @@ def resolve_gate(g: Graph, p, q, mag_p, mag_q, tol: float, device_gate=None):
     cols = g.csr.colidx
     s = p[cols] + q[rows_of]
     own = s > 0
-    amb = np.abs(s) <= threshold(tol, mag_p[cols] + mag_q[rows_of])
+    mag = mag_p[cols] + mag_q[rows_of]
+    amb = (np.abs(s) <= threshold(tol, mag)) & (mag > 0)
     if device_gate is None:
         return own, amb
     return np.where(amb, np.asarray(device_gate, dtype=bool), own), amb

@@ -65,7 +65,7 @@ def resolve_relu(z, mag, tol: float, device_relu=None):
     """(keep, ambiguous): keep = z > 0 outside the ambiguous set, the supplied decision inside it.
     mag: the magnitude sums |A| |W| of the pre-activations z = A W."""
     own = z > 0
-    amb = np.abs(z) <= threshold(tol, mag)
+    amb = (np.abs(z) <= threshold(tol, mag)) & (mag > 0)       # mag = 0: every term is zero, nothing to round
     if device_relu is None:
         return own, amb
     return np.where(amb, np.asarray(device_relu, dtype=bool), own), amb

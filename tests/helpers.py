@@ -29,7 +29,7 @@ def assert_close(got, ref, ref_abs, tol, what=""):
     assert zero_ok, what + ": nonzero output where every term is zero"
 
 
-def check_activation_decisions(dev_hidden, ref, what="", say=None, calls_per_layer=2):
+def check_activation_decisions(dev_hidden, ref, what="", say=None, calls_per_layer=2, scale_floor=0.0):
     """The device's ReLU decisions against the oracle's, per hidden layer.
 
     ref: an oracle epoch that was GIVEN the device's decisions (device_relu) and used them only
@@ -37,7 +37,9 @@ def check_activation_decisions(dev_hidden, ref, what="", say=None, calls_per_lay
     their terms).  Asserts that outside that set the device decided as the oracle does, that the
     set is a small fraction of the entries, and that the hidden activations themselves match:
     layer l is the output of a chain of calls_per_layer * (l + 1) calls, each within 1e-5 of the
-    magnitude sums of its terms."""
+    magnitude sums of its terms.  scale_floor (random sweeps only): an entry whose own magnitude
+    sum is below that fraction of the layer's largest is measured against that fraction (its
+    operands carry the rounding of the calls before, relative to THEIR magnitude sums)."""
     for l, amb in enumerate(ref["relu_ambiguous"]):
         dev = np.asarray(dev_hidden[l], dtype=np.float64)
         own = ref["preact"][l] > 0
@@ -48,7 +50,8 @@ def check_activation_decisions(dev_hidden, ref, what="", say=None, calls_per_lay
         assert not (differ & ~amb).any(), "%s layer %d: %d ReLU decisions differ outside the ambiguous set" % (what, l, int((differ & ~amb).sum()))
         assert amb.mean() <= 1e-3, "%s layer %d: ambiguous set too large (%.2e of the entries)" % (what, l, amb.mean())
         tol = calls_per_layer * (l + 1) * TOL_F32
-        err = np.abs(dev - ref["hidden"][l]) / np.maximum(ref["preact_mag"][l], np.finfo(np.float64).tiny)
+        mag = ref["preact_mag"][l]
+        err = np.abs(dev - ref["hidden"][l]) / np.maximum(np.maximum(mag, scale_floor * mag.max()), np.finfo(np.float64).tiny)
         if say:
             say("  %s layer %d: hidden activations within %.2e of their magnitude sums (bound %.0e)" % (what, l, err.max(), tol))
         assert err.max() <= tol, "%s layer %d: hidden activations off by %.2e of their magnitude sums" % (what, l, err.max())

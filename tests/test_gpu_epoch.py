@@ -8,7 +8,7 @@ import oracle
 from oracle import gcn as ogcn
 import ntp_inputs as gen
 import paper_2412_20379_amd as ntp
-from helpers import check_activation_decisions
+from helpers import check_activation_decisions, TOL_F32
 
 pytestmark = pytest.mark.gpu
 
@@ -31,7 +31,7 @@ def _run(cfg, order, scale=1, chunked=False, directed=False, scatter=False, over
 
 
 def run_epoch_case(n, src, dst, flags, X, dims, order, chunked=False, scatter=False, overlap_dw=False, build_kw=None, what="", seed=0,
-                   scale_floor=0.0, workers=0):
+                   scale_floor=0.0, workers=0, dw_tol=TOL_F32):
     """one epoch on the device against the oracle: loss, logits, every dW.  scale_floor: entries of dW whose
     sum of |terms| is below this fraction of the largest one are measured against that fraction (the inputs of
     the product carry the rounding of the calls before it, which is relative to THEIR sums of magnitudes and can
@@ -61,15 +61,16 @@ def run_epoch_case(n, src, dst, flags, X, dims, order, chunked=False, scatter=Fa
     hid_dev = [h.cpu().numpy() for h in ep.hid[:-1]]
     kw = {} if order == "decoupled" else dict(transform_first=ep.transform_first)
     ref = fn(og, X, Ws, labels, device_relu=[h > 0 for h in hid_dev], **kw)
-    check_activation_decisions(hid_dev, ref, what, say, calls_per_layer=1 if order == "decoupled" else 2)
+    check_activation_decisions(hid_dev, ref, what, say, calls_per_layer=1 if order == "decoupled" else 2, scale_floor=scale_floor)
     say(what, order, "loss", float(loss), "oracle", ref["loss"])
     assert abs(float(loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
     Z = ep.logits.cpu().numpy().astype(np.float64)
     zs = np.abs(ref["logits"]).max()
     assert np.abs(Z - ref["logits"]).max() <= 2e-5 * zs
     # dW_l sums n products of mixed sign: its rounding error scales with the sum of
-    # absolute products |A_l|^T |dZ_l|, not with the (much smaller) result.  An epoch
-    # chains about ten fp32 calls, so the bound is 5x the per-call 1e-5.
+    # absolute products |A_l|^T |dZ_l|, not with the (much smaller) result.  The fixed cases
+    # hold the per-call 1e-5 against that scale (measured: at most 2e-6); the random sweeps, whose
+    # graphs produce columns of dW that cancel almost completely, pass scale_floor and a wider dw_tol.
     L = len(Ws)
     for l, dW in enumerate(ep.dW):
         got = dW.cpu().numpy().astype(np.float64)
@@ -79,7 +80,7 @@ def run_epoch_case(n, src, dst, flags, X, dims, order, chunked=False, scatter=Fa
         err = (np.abs(got - ref["dW"][l]) / np.maximum(scale_l, np.finfo(np.float64).tiny)).max()
         nerr = np.abs(got - ref["dW"][l]).max() / max(np.abs(ref["dW"][l]).max(), np.finfo(np.float64).tiny)   # a dead layer has dW = 0
         say("  dW[%d] error vs sum of |terms| %.2e, vs max|dW| %.2e" % (l, err, nerr))
-        assert err <= 5e-5, "dW[%d]" % l
+        assert err <= dw_tol, "dW[%d]" % l
     g.close()
 
 
@@ -172,7 +173,7 @@ def test_epoch_auto_order_mixed_widths():
         got = ep.dW[l].cpu().numpy().astype(np.float64)
         dZ = ref["dH"][l] * ref["relu_keep"][l] if l < 2 else ref["dH"][l]
         scale = np.abs(ref["nn_in"][l]).T @ np.abs(dZ)
-        assert (np.abs(got - ref["dW"][l]) / scale).max() <= 5e-5, "dW[%d]" % l
+        assert (np.abs(got - ref["dW"][l]) / scale).max() <= TOL_F32, "dW[%d]" % l
     g.close()
 
 

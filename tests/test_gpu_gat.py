@@ -9,7 +9,7 @@ import pytest
 import oracle
 import ntp_inputs as gen
 import paper_2412_20379_amd as ntp
-from helpers import check_activation_decisions
+from helpers import check_activation_decisions, TOL_F32
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-5
@@ -97,7 +97,7 @@ def test_attention_scores_argument_errors():
     ntp.ntp_attention_scores_fwd(z, a, a, v, v, 0, 8, 8)       # nothing to do
 
 
-def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=None, extra_flags=0, scale_floor=0.0, grad_tol=5e-5):
+def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=None, extra_flags=0, scale_floor=0.0, grad_tol=1e-5):
     """one decoupled GAT epoch on the device against the oracle: decisions, loss, logits, weights, every gradient"""
     import torch
     from paper_2412_20379_amd.gat import GatEpoch
@@ -128,7 +128,7 @@ def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=
     gate_dev = (p_dev[og.csr.colidx] + q_dev[rows_of]) > np.float32(0)
     ref = oracle.epoch_gat_decoupled(og, X, Ws, a_s, a_d, labels, rounds, slope,
                                      device_relu=[h > 0 for h in hid_dev], device_gate=gate_dev)
-    check_activation_decisions(hid_dev, ref, what, say, calls_per_layer=1)
+    check_activation_decisions(hid_dev, ref, what, say, calls_per_layer=1, scale_floor=scale_floor)
     own_gate = (ref["p"][og.csr.colidx] + ref["q"][rows_of]) > 0
     amb = ref["gate_ambiguous"]
     say("      %d of %d edge scores ambiguous at 1e-5 of their magnitude sums, %d device branches differ"
@@ -143,7 +143,7 @@ def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=
     a_in = ep.alpha_in.cpu().numpy().astype(np.float64)
     assert (np.abs(a_in - ref["alpha_in"]) / ref["alpha_in"]).max() <= 5e-5
     # gradients: error against the sum of the magnitudes of the terms each one adds up; an epoch
-    # chains about a dozen fp32 calls, so the bound is 5x the per-call 1e-5 (as for the GCN epochs).
+    # chains about a dozen fp32 calls; measured errors stay below 5e-6, so the per-call 1e-5 is kept.
     # The terms of dp[u], dq[v] are the per-edge alpha (dalpha - t) of all rounds, whose magnitudes
     # the oracle sums up (dp_mag, dq_mag); da_src = Lhat^T dp inherits them through |Lhat|.
     Lh = np.abs(ref["Z"][0])
@@ -168,7 +168,7 @@ def _gat_epoch(n, src, dst, flags, dims, rounds, slope, seed, what, chunk_edges=
         err = (np.abs(got - ref["dW"][l]) / scale_l).max()
         nerr = np.abs(got - ref["dW"][l]).max() / max(np.abs(ref["dW"][l]).max(), np.finfo(np.float64).tiny)
         say("      dW[%d] error vs sum of |terms| %.2e, vs max|dW| %.2e" % (l, err, nerr))
-        assert err <= 5e-5, "dW[%d]" % l
+        assert err <= TOL_F32, "dW[%d]" % l
         dH = dZl @ Ws[l].astype(np.float64).T
     g.close()
 
