@@ -22,8 +22,10 @@
  *    up to 15 bytes past the slice but inside the row stride (never written), so padding
  *    the stride of an odd-width slice to a multiple of 4 elements buys the fast path.
  *  - stream arguments are hipStream_t passed as void* (NULL = the null stream).  The
- *    aggregate and nn calls only enqueue work; they do not synchronise with the host,
- *    except that the first call needing a larger scratch buffer allocates it.
+ *    aggregate and nn calls only enqueue work; they do not synchronise with the host.  One
+ *    exception: the scratch for the partial sums of split rows is allocated at graph build for
+ *    slices of up to 256 columns (and one right-hand side); the first call with a wider slice, or
+ *    with more right-hand sides, synchronises the device and allocates a larger one.
  *  - A graph handle may be used by one thread at a time; calls on one handle that overlap
  *    in time on different streams race on its scratch memory.
  */

@@ -539,6 +539,13 @@ static int graph_build_impl(int64_t n, int64_t n_edges, const int32_t* src, cons
         }
         const hipError_t se = hipDeviceSynchronize();
         if (se != hipSuccess) { set_error("hipDeviceSynchronize failed: %s", hipGetErrorString(se)); return NTP_EHIP; }
+        // partial sums of split rows: allocated here for slices of up to 256 columns, so that only a
+        // call with a wider slice ever allocates (and synchronises) inside an aggregation
+        for (int k = 0; k < n_forms; ++k)
+            if (G->form[k].plan.n_slots > 0) {
+                rc = ensure_partial(G, G->form[k], 256);
+                if (rc != NTP_OK) return rc;
+            }
         float* unused = nullptr;            // resolve the static scratch of this device at set-up
         rc = static_scratch(&unused);
         if (rc != NTP_OK) return rc;

@@ -106,16 +106,22 @@ def test_sizes_beyond_the_static_scratch_are_refused():
 
 
 def test_static_scratch_needs_no_device_memory_from_the_handle():
-    """the handle's device bytes do not grow over a no-alloc call (the allocating call grows them)"""
+    """the handle's device bytes do not grow over a no-alloc call, whatever the width (the allocating
+    call grows them once a slice is wider than the 256 columns its scratch was sized for at build)"""
     import torch
     src, dst = _hub_graph(5000, 30000, 14, hub_in=3000)
     g = ntp.ntp_graph_build(5000, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
-    x = torch.randn(5000, 32, device="cuda:0")
+    x = torch.randn(5000, 512, device="cuda:0")
     y = torch.empty_like(x)
     before = ntp.ntp_graph_device_bytes(g)
-    ntp.ntp_aggregate_fwd_noalloc(g, x, y, 32, 32, 32, ntp.NTP_F32)
+    ntp.ntp_aggregate_fwd_noalloc(g, x, y, 512, 512, 512, ntp.NTP_F32)
     assert ntp.ntp_graph_device_bytes(g) == before
-    ntp.ntp_aggregate_fwd(g, x, y, 32, 32, 32, ntp.NTP_F32)
+    ntp.ntp_aggregate_fwd(g, x, y, 256, 512, 512, ntp.NTP_F32)
+    assert ntp.ntp_graph_device_bytes(g) == before
+    y2 = torch.empty_like(x)
+    ntp.ntp_aggregate_fwd(g, x, y2, 512, 512, 512, ntp.NTP_F32)
     assert ntp.ntp_graph_device_bytes(g) > before
+    ntp.ntp_aggregate_fwd_noalloc(g, x, y, 512, 512, 512, ntp.NTP_F32)
     torch.cuda.synchronize()
+    assert torch.equal(y, y2)
     g.close()
