@@ -166,7 +166,7 @@ def step_bench(args, cfg, scale_down=1, agg_dtype="f32", copy_gbs=None, graph=No
             X.normal_(generator=tg)
             Ws = [torch.from_numpy(gen.glorot_weight(dims[l], dims[l + 1], args.seed, l)).to(dev) for l in range(L)]
             labels = torch.from_numpy(gen.uniform_labels(n, dims[-1], args.seed).astype(np.int64)).to(dev)
-            tp = TensorParallelEpoch(g, n, dims, workers=W8)
+            tp = TensorParallelEpoch(g, n, dims, workers=W8, overlap_dw=args.overlap_dw)
             tp.run(X, Ws, labels)
             torch.cuda.synchronize()
             log("config %d: all %d workers ran once, loss %.5f; timing worker 0's calls" % (cfg, W8, float(tp.loss)))
@@ -506,6 +506,9 @@ def main():
     ap.add_argument("--agg-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--parity-rows", type=int, default=2000,
                     help="--mode gat: uniformly sampled destinations checked against the oracle (0: no check)")
+    ap.add_argument("--overlap-dw", action="store_true",
+                    help="worker-share steps (configs 3, 4 in fp32): issue every weight gradient on a second stream beside dA and "
+                         "the backward aggregation that follows it")
     ap.add_argument("--unpermuted", action="store_true",
                     help="keep the generator's vertex numbering (hubs at the low ids) instead of the random relabelling "
                          "the configs ask for: the best case for locality, reported as context only")

@@ -30,9 +30,13 @@ def line_padded_ld(f: int, elem: int = 4) -> int:
 
 
 class TensorParallelEpoch:
-    def __init__(self, graph: ntp.Graph, n: int, dims, workers: int = 8, device="cuda:0", chunked=False):
+    def __init__(self, graph: ntp.Graph, n: int, dims, workers: int = 8, device="cuda:0", chunked=False, overlap_dw=False):
         self.g, self.n, self.dims, self.W = graph, n, tuple(dims), workers
         self.chunked = chunked
+        # overlap_dw: the weight gradient of a layer (matrix cores, needed by nobody downstream) runs on a
+        # second stream beside the layer's dA and the backward aggregation that follows it (memory system)
+        self.overlap_dw = overlap_dw
+        self.dw_stream = torch.cuda.Stream(device=device) if overlap_dw else None
         L = self.L = len(dims) - 1
         f32 = dict(dtype=torch.float32, device=device)
         W = workers
@@ -57,6 +61,7 @@ class TensorParallelEpoch:
         self.dW = [torch.empty(dims[l], dims[l + 1], **f32) for l in range(L)]
         self.ws_bytes = max(ntp.ntp_nn_bwd_workspace_bytes(self.n_share, dims[l], dims[l + 1]) for l in range(L))
         self.ws = torch.empty(max(self.ws_bytes, 4), dtype=torch.uint8, device=device)
+        self.ws2 = torch.empty(max(self.ws_bytes, 4), dtype=torch.uint8, device=device) if overlap_dw else None
         self.loss_buf = torch.zeros(1, **f32)
         self.loss_scratch = torch.empty(ntp.ntp_softmax_xent_scratch_bytes(n) // 4, **f32)
         self.copy_stream = torch.cuda.Stream(device=device) if chunked else None
@@ -115,14 +120,29 @@ class TensorParallelEpoch:
     def nn_bwd(self, l, w):
         r0, r1 = self.rows[w]
         d = self.dims
-        if r1 > r0:
-            # no activation here: the gradient of a hidden layer arrives masked (agg_bwd), the last layer has none
-            self._timed("nn_bwd %dx%d%s" % (d[l], d[l + 1], " +dA" if l > 0 else ""), ntp.ntp_nn_bwd,
-                        self.A[l][r0:r1], self.weights[l], self.H[l][r0:r1], self.dH[l][r0:r1],
-                        self.dA[l][r0:r1] if l > 0 else None, self.dW_part[l][w], r1 - r0, d[l], d[l + 1], ntp.NTP_ACT_NONE, ntp.NTP_F32,
-                        self.ws, self.ws_bytes, torch.cuda.current_stream())
-        else:
+        if r1 <= r0:
             self.dW_part[l][w].zero_()
+            return
+        # no activation here: the gradient of a hidden layer arrives masked (agg_bwd), the last layer has none
+        st = torch.cuda.current_stream()
+        args = (self.A[l][r0:r1], self.weights[l], self.H[l][r0:r1], self.dH[l][r0:r1])
+        shape = (r1 - r0, d[l], d[l + 1], ntp.NTP_ACT_NONE, ntp.NTP_F32)
+        if self.overlap_dw and l > 0:
+            ready = torch.cuda.Event()
+            ready.record(st)
+            self.dw_stream.wait_event(ready)
+            ntp.ntp_nn_bwd(*args, None, self.dW_part[l][w], *shape, self.ws2, self.ws_bytes, self.dw_stream)
+            self._timed("nn_bwd %dx%d dA only" % (d[l], d[l + 1]), ntp.ntp_nn_bwd, *args, self.dA[l][r0:r1], None, *shape, None, 0, st)
+        else:
+            self._timed("nn_bwd %dx%d%s" % (d[l], d[l + 1], " +dA" if l > 0 else ""), ntp.ntp_nn_bwd, *args,
+                        self.dA[l][r0:r1] if l > 0 else None, self.dW_part[l][w], *shape, self.ws, self.ws_bytes, st)
+
+    def _join_dw(self):
+        """the main stream waits for the weight gradients issued on the side stream"""
+        if self.overlap_dw:
+            done = torch.cuda.Event()
+            done.record(self.dw_stream)
+            torch.cuda.current_stream().wait_event(done)
 
     # ---- stand-ins for the exchange between the workers (device copies) ---------------------
     def _split(self, full, slices, l):
@@ -159,6 +179,7 @@ class TensorParallelEpoch:
         for l in range(L - 1, -1, -1):
             for w in range(W):
                 self.nn_bwd(l, w)
+            self._join_dw()
             torch.sum(self.dW_part[l], dim=0, out=self.dW[l])       # stands in for the all-reduce of the weight gradients
             if l > 0:
                 self._split(self.dA[l], self.dS[l], l)
@@ -178,3 +199,4 @@ class TensorParallelEpoch:
             self.nn_bwd(l, w)
             if l > 0:
                 self.agg_bwd(l, w)
+        self._join_dw()

@@ -46,7 +46,7 @@ def run_epoch_case(n, src, dst, flags, X, dims, order, chunked=False, scatter=Fa
     if workers:      # the same epoch cut into the calls of `workers` tensor-parallel workers (layer-wise order)
         from paper_2412_20379_amd.tp import TensorParallelEpoch
         assert order == "layerwise"
-        ep = TensorParallelEpoch(g, n, dims, workers=workers, chunked=chunked)
+        ep = TensorParallelEpoch(g, n, dims, workers=workers, chunked=chunked, overlap_dw=overlap_dw)
         ep.transform_first = [False] * (len(dims) - 1)
     else:
         ep = GcnEpoch(g, n, dims, order=order, chunked=chunked, overlap_dw=overlap_dw)
@@ -139,6 +139,7 @@ def test_worker_share_epoch_equals_full_model(cfg, scale):
         _run(cfg, "layerwise", scale=scale, workers=8, chunked=True, build_kw=dict(device_budget_bytes=8 * (ce * 8 + (1 << 20)), chunk_edges=ce))
     else:
         _run(cfg, "layerwise", scale=scale, workers=8)
+        _run(cfg, "layerwise", scale=scale, workers=8, overlap_dw=True)
 
 
 def test_epoch_class_count_padded_to_whole_lines():
