@@ -15,7 +15,7 @@
  *    of the current device.  The library never frees or keeps caller buffers: pointers
  *    are used only by the work enqueued during the call.
  *  - Feature / gradient matrices are row-major; ld* are row strides in ELEMENTS (>= the
- *    slice width).  Input and output of one call must not overlap.  Rows are read and
+ *    slice width, < 2^30).  Input and output of one call must not overlap.  Rows are read and
  *    written in aligned vectors of up to 16 bytes; the vector width is the largest that
  *    divides both row strides and the alignment of both base pointers.  When the slice
  *    width is not a multiple of it, the last vector of an input row is read whole, i.e.

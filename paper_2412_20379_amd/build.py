@@ -11,6 +11,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libntp.so")
+PROBE_SRC = os.path.join(CSRC, "line_rate_probe.hip")
+PROBE = os.path.join(PKG, "line_rate_probe")        # prints the chip's 128-byte line rates (L2 / Infinity Cache / HBM)
 
 SOURCES = ["graph_build.cpp", "plan.cpp", "ntp_api.hip", "agg_kernels.hip", "scatter_kernels.hip", "chunk_kernels.hip", "attention_kernels.hip", "attention_scores_kernels.hip", "loss_kernels.hip", "nn_kernels.hip"]
 HEADERS = [os.path.join(CSRC, "ntp_internal.h"), os.path.join(CSRC, "lane_util.h"), os.path.join(ROOT, "include", "ntp.h")]
@@ -64,6 +66,11 @@ def build(force: bool = False, verbose: bool = False) -> str:
         tmp = LIB + ".tmp%d" % os.getpid()
         run([hipcc, "-shared", "-fPIC", "-o", tmp] + objs + ["--offload-arch=gfx950", "-lpthread"])
         os.replace(tmp, LIB)
+    # the stand-alone measurement aid (its own executable: it links nothing of the library)
+    if force or _stale(PROBE, [PROBE_SRC]):
+        tmp = PROBE + ".tmp%d" % os.getpid()
+        run([hipcc, "-O3", "-std=c++17", "-ffp-contract=off", "-o", tmp, PROBE_SRC] + DEVICE)
+        os.replace(tmp, PROBE)
     return LIB
 
 

@@ -205,21 +205,30 @@ __device__ __forceinline__ void agg_item(const AggArgs& a, const int wave, const
 
     // the feature-row vectors of entry c: from memory, or for a hub entry (HUB, c < 0) from the LDS
     // table; the global load of a hub entry goes to the first hub's row, which stays in the L1
-    const int64_t hub0 = HUB ? (int64_t)a.hub_cols[0] * ldx : 0;
+    // Address of a gathered vector: one 32 x 32 -> 64-bit multiply-add per load (vertex id times the
+    // row stride in bytes, which the host keeps below 2^32, plus this lane's own base pointer).  A
+    // full 64-bit product of id and stride costs five more integer instructions per gathered row,
+    // which is what the gather loop's issue slots go to.
+    const uint32_t row_bytes = (uint32_t)(ldx * (int64_t)sizeof(T));
+    const char* xl[NACC];
+#pragma unroll
+    for (int j = 0; j < NACC; ++j) xl[j] = reinterpret_cast<const char*>(X + coff[j]);
+    auto row_ptr = [&](const int j, const uint32_t c) {
+        return reinterpret_cast<const T*>(xl[j] + (uint64_t)c * row_bytes);
+    };
+    const uint32_t hub0 = HUB ? (uint32_t)a.hub_cols[0] : 0u;
     auto load_row = [&](const int c, float (&x)[NACC][VEC]) {
         if constexpr (HUB) {
             const bool hub = c < 0;
-            const T* xr = X + (hub ? hub0 : (int64_t)c * ldx);
             const T* xt = table + (hub ? (c & 0x7fffffff) : 0) * (L * VEC) + l * VEC;
             float t[VEC];
-            IO::load(xr + coff[0], x[0]);
+            IO::load(row_ptr(0, hub ? hub0 : (uint32_t)c), x[0]);
             IO::load(xt, t);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) x[0][i] = hub ? t[i] : x[0][i];
         } else {
-            const T* xr = X + (int64_t)c * ldx;
 #pragma unroll
-            for (int j = 0; j < NACC; ++j) IO::load(xr + coff[j], x[j]);
+            for (int j = 0; j < NACC; ++j) IO::load(row_ptr(j, (uint32_t)c), x[j]);
         }
     };
     // acc += sum over u < U of w[u] * X[c[u], columns of this lane]; all loads first

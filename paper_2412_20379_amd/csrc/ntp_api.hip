@@ -292,6 +292,8 @@ int check_agg_args(const ntp_graph* g, const void* X, const void* Y, int64_t f, 
     if (dtype != NTP_F32 && dtype != NTP_BF16) { set_error("unknown dtype %d", dtype); return NTP_EINVAL; }
     if (f < 1 || f > (1 << 20)) { set_error("slice width %lld out of range (1..2^20)", (long long)f); return NTP_EINVAL; }
     if (ldx < f || ldy < f) { set_error("row stride smaller than the slice width"); return NTP_EINVAL; }
+    // the kernels form row addresses as vertex id x stride in bytes with a 32 x 32 -> 64-bit multiply
+    if (ldx >= (1ll << 30) || ldy >= (1ll << 30)) { set_error("row stride of 2^30 elements or more"); return NTP_EINVAL; }
     if (g->g.n > 0 && (!X || !Y)) { set_error("X or Y is NULL"); return NTP_EINVAL; }
     if (g->g.n > 0 && views_overlap(X, ldx, Y, ldy, g->g.n, f, dtype == NTP_BF16 ? 2 : 4)) {
         set_error("input and output must not overlap");

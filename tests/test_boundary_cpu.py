@@ -261,6 +261,9 @@ def test_overlapping_strided_views_are_refused():
     # different strides inside one span cannot be told apart cheaply: refused
     assert code(base, base + 64, 32, 256, 128) == ntp.NTP_EINVAL
     assert code(base, base + n * 256 * 4, 32, 256, 128) == ntp.NTP_EBUDGET
+    # row strides of 2^30 elements or more are refused (row addresses are id x stride-in-bytes in 32 x 32 -> 64 bits)
+    assert code(base, base + (1 << 40), 32, 1 << 30, 32) == ntp.NTP_EINVAL
+    assert code(base, base + (1 << 40), 32, 32, 1 << 30) == ntp.NTP_EINVAL
     # several right-hand sides: every output against every input and every other output
     L = ntp.lib()
     import ctypes
