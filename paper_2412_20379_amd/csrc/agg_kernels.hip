@@ -14,8 +14,7 @@
 //     partial sums to a scratch slot; reduce_kernel adds the slots of a row in order.
 // No atomics anywhere: the result is deterministic.
 //
-// Hub table (agg_hub_kernel).  What bounds the gather loop is the rate at which a compute unit's
-// L1 can miss: every gathered row is a miss.  On a power-law graph a few columns take a large
+// Hub table (agg_hub_kernel).  Every gathered row misses the L1.  On a power-law graph a few columns take a large
 // share of the gathers, so the graph build marks the most gathered columns ("hubs") in a second
 // column-id array: a hub entry carries 0x80000000 | slot instead of its vertex id.  The hub
 // kernel runs one persistent block of 16 wavefronts per compute unit, which first copies the hub
@@ -27,7 +26,9 @@
 // Measured on MI355X it does not pay and is therefore opt-in (graphs built with NTP_AGG_HUB=1 in
 // the environment): the L1-to-L2 requests fall by the hubs' share of the gathers (a third on a
 // 2.5 M-entry R-MAT graph), but the persistent blocks run 20-35 % behind the plain kernel with
-// one slot as with 1024, i.e. what the table saves never becomes the bottleneck.
+// one slot as with 1024, i.e. what the table saves never becomes the bottleneck: the launch time is
+// set by the gathers that miss the L2 (random lines beyond it arrive at 53-56 G lines/s on this chip),
+// and hub rows are the ones that hit it.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -144,9 +145,10 @@ __device__ __forceinline__ void agg_item(const AggArgs& a, const int wave, const
     constexpr int VEC = IO::kVec;
     constexpr int R = 64 / L;
     constexpr int PASS_W = L * VEC * NACC;
-    // gathers kept in flight per lane.  Measured on MI355X: 1, 2, 4 and 8 give the same
-    // throughput (the gather rate is set by the cache hierarchy, not by latency hiding in
-    // the wavefront), so a small count is used to keep the register footprint low.
+    // gathers kept in flight per lane.  Measured on MI355X: 1, 2 and 4 give the same
+    // throughput (the gather rate is set by the L2's miss path, not by latency hiding in
+    // the wavefront), so a small count is used to keep the register footprint low; 8 no longer
+    // fits the 64 registers of the line-wide shape and halves its speed.
     constexpr int UMAX = NACC == 4 ? 2 : 4;
     constexpr int U = L < UMAX ? L : UMAX;
 
