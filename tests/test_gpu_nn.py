@@ -22,7 +22,10 @@ def _abs_scale(A, B):
 
 
 SHAPES = [(1, 1, 1), (5, 3, 2), (300, 16, 7), (257, 33, 65), (1000, 128, 256), (2708, 1433, 16),
-          (4097, 256, 256), (3000, 256, 40), (2050, 100, 47), (1500, 602, 128), (999, 128, 41), (70000, 64, 32)]
+          (4097, 256, 256), (3000, 256, 40), (2050, 100, 47), (1500, 602, 128), (999, 128, 41), (70000, 64, 32),
+          # tall matrices (several rounds of blocks on the chip): ragged last tile, partial last contraction
+          # step, odd and narrow outputs, more than one column tile
+          (20001, 128, 256), (17000, 256, 40), (16500, 100, 47), (18000, 72, 300), (33000, 64, 64)]
 
 
 @pytest.mark.parametrize("n,k,m", SHAPES)
@@ -142,7 +145,7 @@ def test_relu_alone(n, f, ld, dtype):
     assert np.array_equal(back(dZ), want_dz)
 
 
-@pytest.mark.parametrize("n,k,m", [(2048, 1024, 256), (1111, 160, 130), (3000, 130, 256), (5000, 512, 192)])
+@pytest.mark.parametrize("n,k,m", [(2048, 1024, 256), (1111, 160, 130), (3000, 130, 256), (5000, 512, 192), (20000, 256, 256)])
 def test_wide_dynamic_range_keeps_fp32_accuracy(n, k, m):
     """Operands whose magnitudes span six decades: the transform (whose default core forms
     fp32 products from bf16 pieces) must stay at fp32-class accuracy, far inside the
