@@ -73,6 +73,33 @@ def copy_probe(torch, dev):
     return gbs
 
 
+def line_rate_probe():
+    """random 128-byte lines per second the memory system delivers beyond the L2 (Infinity Cache / HBM), measured by
+    the stand-alone probe paper_2412_20379_amd/line_rate_probe (its own process; run before this one touches the GPU).
+    Returns GB/s at 128 MB and at 1 GB, or None when the executable is not built."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2412_20379_amd", "line_rate_probe")
+    if not os.path.exists(exe):
+        return None
+    # under a profiler the GPU is initialised before this program starts, and a process that has
+    # initialised the GPU must not start another program: no probe then
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", "").lower():
+        log("line-rate probe skipped (profiler environment)")
+        return None
+    try:
+        r = subprocess.run([exe, "--quick"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, timeout=120)
+        w = [l for l in r.stdout.splitlines() if l.startswith("quick")][-1].split()
+        out = {"infinity_cache_128mb_gbs": float(w[1]) * 128.0, "hbm_1gb_gbs": float(w[2]) * 128.0}
+        log("line-rate probe: random 128-byte lines beyond the L2: %.0f GB/s (128 MB), %.0f GB/s (1 GB)" % (out["infinity_cache_128mb_gbs"], out["hbm_1gb_gbs"]))
+        return out
+    except Exception as e:
+        log("line-rate probe failed: %r" % (e,))
+        return None
+
+
+LINE_RATE = None
+
+
 def profile_traffic(key):
     """L2-boundary bytes per launch of the aggregation kernel as counted in an earlier rocprofv3
     run (profiles/traffic.json): not measured by this process, so it comes with the commit and
@@ -289,6 +316,10 @@ def step_bench(args, cfg, scale_down=1, agg_dtype="f32", copy_gbs=None, graph=No
                     algorithmic_bytes_per_launch=balg, avg_launch_ms=dur_ms,
                     traffic_gbs=(traffic / (dur_ms * 1e-3) / 1e9) if traffic else None,
                     overfetch=(traffic / balg) if traffic else None,
+                    # what this chip delivers for random 128-byte lines that miss the L2 (stand-alone probe, same
+                    # run), and the kernel's L2-boundary traffic against it: at 1.0 the kernel's time is its L2 misses
+                    random_line_rate_gbs=LINE_RATE,
+                    traffic_vs_random_line_rate=((traffic / (dur_ms * 1e-3) / 1e9) / LINE_RATE["hbm_1gb_gbs"]) if traffic and LINE_RATE else None,
                     # the algorithmic rate against a plain device copy measured in this run
                     copy_gbs=copy_gbs, frac_of_copy=(achieved / copy_gbs) if copy_gbs else None,
                     geps_kernel=nnz * fdom / (dur_ms * 1e-3) / 1e9)
@@ -423,6 +454,8 @@ def host_mem_available_gb():
 
 
 def run_step_mode(args):
+    global LINE_RATE
+    LINE_RATE = None if args.no_line_probe else line_rate_probe()
     import torch
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible; the HIP path has no CPU fallback")
@@ -517,6 +550,8 @@ def main():
     ap.add_argument("--unpermuted", action="store_true",
                     help="keep the generator's vertex numbering (hubs at the low ids) instead of the random relabelling "
                          "the configs ask for: the best case for locality, reported as context only")
+    ap.add_argument("--no-line-probe", action="store_true",
+                    help="do not run paper_2412_20379_amd/line_rate_probe (a child process, started before this one touches the GPU)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()

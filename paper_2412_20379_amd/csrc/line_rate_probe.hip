@@ -11,12 +11,15 @@
 //   hash     pseudo-random lines, ids computed in registers (no index stream, no dependent load)
 //   gather   random ids read from memory, 64 per wavefront load, handed to the lane groups through the
 //            cross-lane network, a weight per id, multiply-add: the aggregation kernel's inner loop
-// Usage: line_rate_probe            (prints one line per variant and buffer size)
+// Usage: line_rate_probe            (prints one line per buffer size: seq, hash, gather)
+//        line_rate_probe --quick    (the gather variant at 128 MB and 1 GB only, one line:
+//                                    "quick <G lines/s at 128 MB> <G lines/s at 1 GB>")
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
 #include <cstdlib>
 #include <random>
+#include <string>
 #include <vector>
 
 #define CK(x)                                                                        \
@@ -119,7 +122,8 @@ double run(size_t bytes) {
 
 }  // namespace
 
-int main() {
+int main(int argc, char** argv) {
+    const bool quick = argc > 1 && std::string(argv[1]) == "--quick";
     const size_t n = (size_t)WAVES * BATCHES * 64;
     const size_t sizes[] = {(size_t)1 << 20, (size_t)4 << 20, (size_t)32 << 20, (size_t)128 << 20, (size_t)1 << 30};
     const size_t maxb = (size_t)1 << 30;
@@ -131,6 +135,19 @@ int main() {
     CK(hipMalloc(&d_out, (size_t)WAVES * 4));
     CK(hipMemset(d_out, 0, (size_t)WAVES * 4));
     std::vector<int> h(n);
+    if (quick) {
+        double rate[2];
+        const size_t qs[2] = {(size_t)128 << 20, (size_t)1 << 30};
+        for (int q = 0; q < 2; ++q) {
+            std::mt19937 rng(1);
+            const unsigned lines = (unsigned)(qs[q] / 128);
+            for (size_t i = 0; i < n; ++i) h[i] = (int)(rng() % lines);
+            CK(hipMemcpy(d_idx, h.data(), n * 4, hipMemcpyHostToDevice));
+            rate[q] = run<GATHER>(qs[q]);
+        }
+        std::printf("quick %.1f %.1f\n", rate[0], rate[1]);
+        return 0;
+    }
     std::printf("%10s %14s %14s %14s   (G lines/s of 128 bytes; x 0.128 = TB/s)\n", "buffer", "seq", "hash", "gather");
     for (size_t b : sizes) {
         std::mt19937 rng(1);
