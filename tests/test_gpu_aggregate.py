@@ -290,3 +290,43 @@ def test_split_rows_handled_by_one_block_each():
             x = gen.normal_features(n, f, seed=f)
             check_agg(g, og, x, direction, dt, "block rows f=%d %s %s" % (f, dt, direction), ld_in=ld, ld_out=ld)
     g.close()
+
+
+@pytest.mark.parametrize("f,dtype", [(32, "f32"), (40, "f32"), (64, "bf16")])
+def test_rows_more_than_4_gib_apart(f, dtype):
+    """Row addresses are vertex id x row stride in bytes: a matrix whose last rows lie beyond 2^32 bytes
+    (66,000 rows, 64 KB apart; the slice is a narrow window of a very wide matrix) must be gathered and
+    stored with 64-bit offsets, forward and backward, from and to such a matrix."""
+    import torch
+    from helpers import assert_close, TOL_F32, TOL_BF16
+    n = 66000
+    src, dst = gen.directed_random_edges(n, 500000, 77, hub=n - 3, hub_in=9000, hub_out=3000)
+    og = oracle.build_graph(n, src, dst, oracle.DIRECTED_GCN_FLAGS)
+    g = ntp.ntp_graph_build(n, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    x = gen.normal_features(n, f, seed=5)
+    es = 4 if dtype == "f32" else 2
+    ld = 65600 // es                                   # 65,600 bytes per row: 66,000 rows span 4.33e9 bytes
+    assert (n - 1) * ld * es > (1 << 32)
+    tdt = torch.float32 if dtype == "f32" else torch.int16
+    xin = torch.empty((n, ld), dtype=tdt, device="cuda:0")
+    out = torch.empty((n, ld), dtype=tdt, device="cuda:0")
+    if dtype == "f32":
+        xin[:, :f] = torch.from_numpy(x).to("cuda:0")
+        x_used, code, tol = x, ntp.NTP_F32, TOL_F32
+    else:
+        bits = gen.to_bf16_bits(x)
+        xin[:, :f] = torch.from_numpy(bits.view(np.int16)).to("cuda:0")
+        x_used, code, tol = gen.bf16_bits_to_f32(bits), ntp.NTP_BF16, TOL_BF16
+    for direction, m, fn in (("fwd", og.csr, ntp.ntp_aggregate_fwd), ("bwd", og.csc, ntp.ntp_aggregate_bwd)):
+        say("rows_beyond_4gib", f, dtype, direction)
+        out[:, :f] = 0
+        fn(g, xin, out, f, ld, ld, code)
+        torch.cuda.synchronize()
+        res = out[:, :f].contiguous().cpu().numpy()
+        got = res if dtype == "f32" else gen.bf16_bits_to_f32(res.view(np.uint16))
+        ref, ref_abs = oracle.aggregate(m, x_used, with_abs=True)
+        if dtype == "bf16":
+            ref = oracle.round_bf16(ref).astype(np.float64)
+        assert_close(got, ref, ref_abs, tol, "rows beyond 4 GiB f=%d %s %s" % (f, dtype, direction))
+    del xin, out
+    g.close()
