@@ -209,3 +209,50 @@ def test_softmax_cross_entropy(n, c):
     assert float(loss) == first[0] and torch.equal(dZ, first[1])
     with pytest.raises(ntp.NtpError):
         ntp.ntp_softmax_xent(Zd, lab, dZ, loss, scratch, nb - 4, n, c, ld, c)
+
+
+def test_matrices_beyond_4_gib():
+    """4.4 M rows x 256 columns of fp32 are 4.5 GB: element offsets of A, H, dH and dA pass 2^32 bytes (the
+    share of one worker on the largest config is of that size).  Forward and dA on sampled rows (the first,
+    the last, a thousand in between) against the oracle's rows; dW, which contracts over all rows, against the
+    oracle's sum taken over row blocks."""
+    import torch
+    n, k, m = 4_400_000, 256, 256
+    assert n * k * 4 > (1 << 32)
+    say("nn beyond 4 GiB", n, k, m)
+    dev = "cuda:0"
+    gen_t = torch.Generator(device=dev)
+    gen_t.manual_seed(11)
+    A = torch.randn(n, k, device=dev, generator=gen_t)
+    dH = torch.randn(n, m, device=dev, generator=gen_t)
+    W = torch.from_numpy(gen.glorot_weight(k, m, seed=3)).to(dev)
+    H = torch.empty(n, m, device=dev)
+    dA = torch.empty(n, k, device=dev)
+    dW = torch.empty(k, m, device=dev)
+    wsb = ntp.ntp_nn_bwd_workspace_bytes(n, k, m)
+    ws = torch.empty(max(wsb, 4), dtype=torch.uint8, device=dev)
+    ntp.ntp_nn_fwd(A, W, H, n, k, m, ntp.NTP_ACT_RELU)
+    ntp.ntp_nn_bwd(A, W, H, dH, dA, dW, n, k, m, ntp.NTP_ACT_RELU, ntp.NTP_F32, ws, wsb)
+    torch.cuda.synchronize()
+    rng = gen.stream_rng(5, 77)
+    rows = np.unique(np.concatenate([np.arange(300), np.arange(n - 1000, n), rng.integers(0, n, 1000)]))
+    idx = torch.from_numpy(rows).to(dev)
+    Wn = W.cpu().numpy()
+    A_s, dH_s, H_s, dA_s = (t[idx].cpu().numpy() for t in (A, dH, H, dA))
+    ref_H = ogcn.nn_fwd(A_s, Wn, ntp.NTP_ACT_RELU)
+    assert_close(H_s, ref_H, _abs_scale(A_s, Wn), TOL_F32, "nn_fwd rows beyond 4 GiB")
+    # the backward call is given the device's H (as in test_nn_bwd_fp32 it is given the oracle's): same mask on both sides
+    ref_dA, _ = ogcn.nn_bwd(A_s, Wn, H_s, dH_s, ntp.NTP_ACT_RELU)
+    dZ_s = dH_s * (H_s > 0)
+    assert_close(dA_s, ref_dA, _abs_scale(dZ_s, Wn.T), TOL_F32, "dA rows beyond 4 GiB")
+    ref_dW = np.zeros((k, m))
+    mag_dW = np.zeros((k, m))
+    step = 200_000
+    for r0 in range(0, n, step):
+        a = A[r0:r0 + step].cpu().numpy()
+        h = H[r0:r0 + step].cpu().numpy()
+        d = dH[r0:r0 + step].cpu().numpy()
+        _, part = ogcn.nn_bwd(a, Wn, h, d, ntp.NTP_ACT_RELU, need_dA=False)
+        ref_dW += part
+        mag_dW += np.abs(a).astype(np.float64).T @ np.abs(d * (h > 0)).astype(np.float64)
+    assert_close(dW.cpu().numpy(), ref_dW, mag_dW, TOL_F32, "dW over 4.4 M rows")
