@@ -256,3 +256,36 @@ def test_matrices_beyond_4_gib():
         ref_dW += part
         mag_dW += np.abs(a).astype(np.float64).T @ np.abs(d * (h > 0)).astype(np.float64)
     assert_close(dW.cpu().numpy(), ref_dW, mag_dW, TOL_F32, "dW over 4.4 M rows")
+
+
+def test_softmax_cross_entropy_beyond_4_gib():
+    """6.4 M vertices x 172 classes are 4.4 GB of logits: row offsets pass 2^32 bytes.  The loss against the
+    oracle's mean taken over row blocks, the gradient on sampled rows (first, last, a thousand between)."""
+    import torch
+    n, c = 6_400_000, 172
+    assert n * c * 4 > (1 << 32)
+    say("softmax_xent beyond 4 GiB", n, c)
+    dev = "cuda:0"
+    gen_t = torch.Generator(device=dev)
+    gen_t.manual_seed(13)
+    Z = torch.randn(n, c, device=dev, generator=gen_t) * 4.0
+    lab = torch.randint(0, c, (n,), device=dev, generator=gen_t, dtype=torch.int64)
+    dZ = torch.empty(n, c, device=dev)
+    loss = torch.full((1,), float("nan"), device=dev)
+    nb = ntp.ntp_softmax_xent_scratch_bytes(n)
+    scratch = torch.empty(nb // 4, device=dev)
+    ntp.ntp_softmax_xent(Z, lab, dZ, loss, scratch, nb, n, c, c, c)
+    torch.cuda.synchronize()
+    total, step = 0.0, 400_000
+    for r0 in range(0, n, step):
+        l, _ = ogcn.softmax_cross_entropy(Z[r0:r0 + step].cpu().numpy(), lab[r0:r0 + step].cpu().numpy())
+        total += l * min(step, n - r0)
+    want_loss = total / n
+    assert abs(float(loss) - want_loss) <= 1e-5 * abs(want_loss), (float(loss), want_loss)
+    rng = gen.stream_rng(6, 78)
+    rows = np.unique(np.concatenate([np.arange(300), np.arange(n - 1000, n), rng.integers(0, n, 1000)]))
+    idx = torch.from_numpy(rows).to(dev)
+    _, want = ogcn.softmax_cross_entropy(Z[idx].cpu().numpy(), lab[idx].cpu().numpy())
+    # the oracle divides by the rows it is given; the device by all n
+    got = dZ[idx].cpu().numpy().astype(np.float64) * n
+    assert np.abs(got - want * rows.size).max() <= 1e-5
