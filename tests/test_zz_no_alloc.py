@@ -125,3 +125,37 @@ def test_static_scratch_needs_no_device_memory_from_the_handle():
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
     g.close()
+
+
+def test_captured_in_a_hip_graph_at_a_width_the_handle_has_no_scratch_for():
+    """what the entry point is for: a caller under HIP graph capture, at a slice width (512) for which the
+    allocating call would have to hipMalloc.  Captured once, replayed four times with eager work and
+    synchronisations between the replays; every replay gives the bits of the eager call."""
+    import torch
+    src, dst = _hub_graph(6000, 40000, 15, hub_in=3500)
+    g = ntp.ntp_graph_build(6000, src, dst, flags=ntp.NTP_DIRECTED_GCN_FLAGS)
+    x = torch.randn(6000, 512, device="cuda:0")
+    want = torch.empty_like(x)
+    before = ntp.ntp_graph_device_bytes(g)
+    ntp.ntp_aggregate_fwd_noalloc(g, x, want, 512, 512, 512, ntp.NTP_F32)
+    torch.cuda.synchronize()
+    y = torch.zeros_like(x)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):              # warm-up on the capture stream's kind, as torch asks for
+        ntp.ntp_aggregate_fwd_noalloc(g, x, y, 512, 512, 512, ntp.NTP_F32, torch.cuda.current_stream())
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ntp.ntp_aggregate_fwd_noalloc(g, x, y, 512, 512, 512, ntp.NTP_F32, torch.cuda.current_stream())
+    for r in range(4):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want), "replay %d" % r
+        _ = float((x * 2).sum())               # eager work between the replays
+    assert ntp.ntp_graph_device_bytes(g) == before
+    del graph
+    g.close()
